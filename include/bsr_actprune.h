@@ -1,0 +1,165 @@
+/*
+ * bsr_actprune.h -- C ABI of the structured-activation-pruning hot path for
+ * AMD MI355X (gfx950).
+ *
+ * The library implements, as hand-written HIP kernels, the two halves of the
+ * paper's block-sparse linear operator (Sec. III, Fig. 2):
+ *   forward side : rank the fixed-size blocks of a saved activation matrix by
+ *                  l2 magnitude, keep the best ones (Sec. IV) and store them in
+ *                  Block Sparse Row format (Sec. II-A);
+ *   backward side: the weight gradient dW = Xhat^T * dY computed directly from
+ *                  that BSR tensor (Sec. III, "BSpMM").
+ *
+ * Conventions shared by every call
+ *   - X is an [M x K] row-major matrix with leading dimension ldx (elements);
+ *     blocks are br x bc; nbr = ceil(M/br), nbc = ceil(K/bc), nblocks =
+ *     nbr*nbc; block (i,j) has the linear index i*nbc + j.  Blocks on a ragged
+ *     edge cover only the valid elements; inside `values` their padding is +0.0.
+ *   - dtype: BSR_F32 (IEEE binary32) or BSR_BF16 (bfloat16).  Indices are
+ *     32-bit (Table II prices one index like one value); nblocks < 2^31.
+ *   - Every pointer named below is a DEVICE pointer unless it says "host".  All
+ *     buffers, the workspace included, are owned by the caller; the library
+ *     never allocates, frees or synchronises.  Work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and the call
+ *     returns at once.  Buffers must stay alive until that work has finished.
+ *   - Pointers must be aligned to their element type; wider alignment (16 B,
+ *     what any framework allocator gives) selects the vectorised kernels.
+ *   - Return value: BSR_OK, or a negative BSR_ERR_* found on the host before
+ *     anything was launched (nothing has been written then), or BSR_ERR_HIP if
+ *     a launch failed (bsr_last_hip_error() holds the hipError_t).
+ *   - Calls on different streams may run concurrently if their workspaces and
+ *     outputs do not overlap.  The library keeps no state of its own besides a
+ *     per-thread last-error value.
+ */
+#ifndef BSR_ACTPRUNE_H
+#define BSR_ACTPRUNE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { BSR_F32 = 0, BSR_BF16 = 1 };
+
+enum {
+  BSR_OK = 0,
+  BSR_ERR_NULL = -1,      /* a required pointer is NULL */
+  BSR_ERR_SHAPE = -2,     /* negative / inconsistent / too large sizes */
+  BSR_ERR_DTYPE = -3,     /* dtype is neither BSR_F32 nor BSR_BF16 */
+  BSR_ERR_KEEP = -4,      /* keep outside [0,1] or NaN, or n_keep != bsr_keep_count range */
+  BSR_ERR_WORKSPACE = -5, /* ws is NULL or smaller than bsr_workspace_bytes() */
+  BSR_ERR_ALIGN = -6,     /* a pointer is not aligned to its element type */
+  BSR_ERR_HIP = -7        /* a HIP call failed; see bsr_last_hip_error() */
+};
+
+enum {
+  BSR_OP_SCORE_SELECT = 0,
+  BSR_OP_COMPRESS = 1,
+  BSR_OP_DECOMPRESS = 2,
+  BSR_OP_T_DENSE_MATMUL = 3
+};
+
+/* Host, pure.  Library version string. */
+const char *bsr_version(void);
+
+/* Host, pure.  Name of a BSR_ERR_* code. */
+const char *bsr_error_string(int code);
+
+/* Host.  hipError_t of the last failed HIP call on this thread (0 if none). */
+int bsr_last_hip_error(void);
+
+/*
+ * Host, pure.  Number of blocks that survive pruning (Sec. IV: k = N*s blocks
+ * are zeroed, s = 1 - keep): ceil(keep * nblocks) evaluated as one binary64
+ * product, clamped to [0, nblocks].  Returns -1 if keep is outside [0,1] or NaN
+ * or nblocks < 0.  Output buffers are sized from this value, so nothing is ever
+ * read back from the device.
+ */
+int64_t bsr_keep_count(int64_t nblocks, double keep);
+
+/*
+ * Host, pure.  Bytes of one BSR-encoded matrix (Sec. II-A, Table II): n_keep
+ * blocks of br*bc elements, one 4-byte column index per kept block, nbr+1
+ * 4-byte row pointers.  Returns -1 on invalid arguments.
+ */
+int64_t bsr_storage_bytes(int64_t M, int64_t K, int br, int bc, int64_t n_keep,
+                          int dtype);
+
+/*
+ * Host, pure.  Size in bytes of the device workspace `ws` that operation `op`
+ * (BSR_OP_*) needs for the given problem; N is only used by
+ * BSR_OP_T_DENSE_MATMUL.  The workspace needs no initialisation and holds
+ * nothing of value between calls.  Returns 0 for invalid arguments (the
+ * operation itself reports the error) and for operations that need none.
+ */
+size_t bsr_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int br,
+                           int bc, int dtype);
+
+/*
+ * Sec. IV, "Activation Pruning": score every block of X by its l2 magnitude
+ * and select the blocks to keep.
+ *   score[i*nbc+j] = sum of x^2 over the valid elements of block (i,j),
+ *                    accumulated in binary64 (ranks like the l2 norm);
+ *   keep_mask[b]   = 1 for the n_keep = bsr_keep_count(nblocks, keep) blocks of
+ *                    highest score, 0 otherwise; equal scores are resolved
+ *                    towards the lower linear block index; a NaN score ranks
+ *                    above +inf.
+ * X: [M x K] of dtype, leading dimension ldx >= K.  scores: [nblocks] binary64
+ * or NULL (then they live only in the workspace).  keep_mask: [nblocks] bytes.
+ * The whole matrix is one ranking group.  M == 0 or K == 0 is valid (nothing
+ * is written).
+ */
+int bsr_score_select(const void *X, int dtype, int64_t M, int64_t K,
+                     int64_t ldx, int br, int bc, double keep, double *scores,
+                     uint8_t *keep_mask, void *ws, size_t ws_bytes,
+                     void *stream);
+
+/*
+ * Sec. III / Sec. II-A: "the activation tensor is converted to the BSR
+ * format".  From X and a keep mask with exactly n_keep ones build
+ *   row_ptr [nbr+1] : running count of kept blocks per block-row (crow);
+ *   col_idx [n_keep]: block-column of every kept block, block-row after
+ *                     block-row, ascending inside a block-row (col);
+ *   values  [n_keep*br*bc] of dtype: the kept blocks, bit copies of X,
+ *                     row-major inside a block, +0.0 in edge padding.
+ * If the mask holds a different number of ones than n_keep the result is
+ * unspecified, but nothing is written outside the given buffers.
+ */
+int bsr_compress(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx,
+                 int br, int bc, const uint8_t *keep_mask, int64_t n_keep,
+                 int32_t *row_ptr, int32_t *col_idx, void *values, void *ws,
+                 size_t ws_bytes, void *stream);
+
+/*
+ * Sec. II-A read backwards: X_out [M x K] (leading dimension ldx) receives the
+ * kept blocks bit for bit and +0.0 everywhere else, i.e. mask (.) X.
+ * row_ptr must be a valid BSR row pointer array for col_idx / values.
+ */
+int bsr_decompress(const int32_t *row_ptr, const int32_t *col_idx,
+                   const void *values, int dtype, int64_t M, int64_t K,
+                   int64_t ldx, int br, int bc, void *X_out, void *stream);
+
+/*
+ * Sec. III, Fig. 2, "block-sparse matrix multiplication (BSpMM)": weight
+ * gradient of a linear layer from the pruned activation,
+ *   dW[j*bc + c, n] (+)= sum over kept blocks (i,j), rows r of the block:
+ *                          values[block][r][c] * dY[i*br + r, n].
+ * dY: [M x N] of the same dtype as values, leading dimension lddy.  dW: [K x N]
+ * binary32, leading dimension lddw; overwritten when accumulate == 0, added to
+ * otherwise.  Products are exact and accumulated in binary32 (matrix cores for
+ * bfloat16).  This is X^T*dY; torch's nn.Linear.weight.grad is its transpose.
+ * The contraction is split over block-rows; partial sums are reduced in a fixed
+ * order, so results are reproducible run to run.
+ */
+int bsr_t_dense_matmul(const int32_t *row_ptr, const int32_t *col_idx,
+                       const void *values, int dtype, int64_t M, int64_t K,
+                       int br, int bc, const void *dY, int64_t N, int64_t lddy,
+                       float *dW, int64_t lddw, int accumulate, void *ws,
+                       size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BSR_ACTPRUNE_H */

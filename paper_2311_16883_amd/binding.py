@@ -1,0 +1,236 @@
+"""ctypes binding of libbsr_actprune.so -- argument marshalling only.
+
+Every function here has the name of the C entry point it calls (see
+``include/bsr_actprune.h``) and does nothing but turn torch tensors into device
+pointers, sizes and the current HIP stream, allocate missing output buffers
+with torch, and raise on a non-zero status.  No step of the pruning path is
+computed in Python or by torch operators; if the HIP library cannot be loaded
+the import fails loudly -- there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from pathlib import Path
+from typing import Optional, Tuple
+
+import torch
+
+BSR_F32, BSR_BF16 = 0, 1
+BSR_OP_SCORE_SELECT, BSR_OP_COMPRESS, BSR_OP_DECOMPRESS, BSR_OP_T_DENSE_MATMUL = 0, 1, 2, 3
+
+BSR_OK = 0
+BSR_ERR_NULL, BSR_ERR_SHAPE, BSR_ERR_DTYPE, BSR_ERR_KEEP = -1, -2, -3, -4
+BSR_ERR_WORKSPACE, BSR_ERR_ALIGN, BSR_ERR_HIP = -5, -6, -7
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libbsr_actprune.so"
+
+EXPORTS = (
+    "bsr_version", "bsr_error_string", "bsr_last_hip_error", "bsr_keep_count",
+    "bsr_storage_bytes", "bsr_workspace_bytes", "bsr_score_select", "bsr_compress",
+    "bsr_decompress", "bsr_t_dense_matmul",
+)
+
+
+class BsrError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        name = lib().bsr_error_string(code).decode()
+        extra = f" (hipError_t {lib().bsr_last_hip_error()})" if code == BSR_ERR_HIP else ""
+        super().__init__(f"{where}: {name}{extra}")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded C library (built on first use only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not LIB_PATH.exists():
+        from . import build as _build
+        _build.build_library()
+    l = C.CDLL(str(LIB_PATH))
+    i64, i32, dbl, vp, sz = C.c_int64, C.c_int, C.c_double, C.c_void_p, C.c_size_t
+    l.bsr_version.restype = C.c_char_p
+    l.bsr_version.argtypes = []
+    l.bsr_error_string.restype = C.c_char_p
+    l.bsr_error_string.argtypes = [i32]
+    l.bsr_last_hip_error.restype = i32
+    l.bsr_last_hip_error.argtypes = []
+    l.bsr_keep_count.restype = i64
+    l.bsr_keep_count.argtypes = [i64, dbl]
+    l.bsr_storage_bytes.restype = i64
+    l.bsr_storage_bytes.argtypes = [i64, i64, i32, i32, i64, i32]
+    l.bsr_workspace_bytes.restype = sz
+    l.bsr_workspace_bytes.argtypes = [i32, i64, i64, i64, i32, i32, i32]
+    l.bsr_score_select.restype = i32
+    l.bsr_score_select.argtypes = [vp, i32, i64, i64, i64, i32, i32, dbl, vp, vp, vp, sz, vp]
+    l.bsr_compress.restype = i32
+    l.bsr_compress.argtypes = [vp, i32, i64, i64, i64, i32, i32, vp, i64, vp, vp, vp, vp, sz, vp]
+    l.bsr_decompress.restype = i32
+    l.bsr_decompress.argtypes = [vp, vp, vp, i32, i64, i64, i64, i32, i32, vp, vp]
+    l.bsr_t_dense_matmul.restype = i32
+    l.bsr_t_dense_matmul.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64, i32,
+                                     vp, sz, vp]
+    _lib = l
+    return l
+
+
+# ---------------------------------------------------------------------------
+# marshalling helpers
+# ---------------------------------------------------------------------------
+
+def dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return BSR_F32
+    if t == torch.bfloat16:
+        return BSR_BF16
+    raise BsrError(BSR_ERR_DTYPE, f"dtype {t}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None or t.numel() == 0:
+        return None if t is None else (t.data_ptr() or None)
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    h = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+    return h or None
+
+
+def _dense2d(x: torch.Tensor, what: str) -> Tuple[int, int, int]:
+    if x.dim() != 2 or not x.is_cuda:
+        raise ValueError(f"{what} must be a 2-D device tensor")
+    if x.shape[1] > 1 and x.stride(1) != 1:
+        raise ValueError(f"{what} must be row-major (unit stride along columns)")
+    ld = x.stride(0) if x.shape[0] > 1 else x.shape[1]
+    if ld < x.shape[1]:
+        raise ValueError(f"{what} has overlapping rows")
+    return x.shape[0], x.shape[1], ld
+
+
+def _workspace(nbytes: int, device, ws: Optional[torch.Tensor]) -> Optional[torch.Tensor]:
+    if ws is not None:
+        return ws
+    return torch.empty(max(nbytes, 1), dtype=torch.uint8, device=device) if nbytes > 0 else None
+
+
+def _check(code: int, where: str) -> None:
+    if code != BSR_OK:
+        raise BsrError(code, where)
+
+
+# ---------------------------------------------------------------------------
+# host-side pure functions
+# ---------------------------------------------------------------------------
+
+def bsr_version() -> str:
+    return lib().bsr_version().decode()
+
+
+def bsr_keep_count(nblocks: int, keep: float) -> int:
+    n = lib().bsr_keep_count(int(nblocks), float(keep))
+    if n < 0:
+        raise BsrError(BSR_ERR_KEEP, "bsr_keep_count")
+    return int(n)
+
+
+def bsr_storage_bytes(M: int, K: int, br: int, bc: int, n_keep: int, dtype) -> int:
+    code = dtype if isinstance(dtype, int) else dtype_code(dtype)
+    n = lib().bsr_storage_bytes(M, K, br, bc, n_keep, code)
+    if n < 0:
+        raise BsrError(BSR_ERR_SHAPE, "bsr_storage_bytes")
+    return int(n)
+
+
+def bsr_workspace_bytes(op: int, M: int, K: int, N: int, br: int, bc: int, dtype) -> int:
+    code = dtype if isinstance(dtype, int) else dtype_code(dtype)
+    return int(lib().bsr_workspace_bytes(op, M, K, N, br, bc, code))
+
+
+# ---------------------------------------------------------------------------
+# device entry points
+# ---------------------------------------------------------------------------
+
+def bsr_score_select(X: torch.Tensor, br: int, bc: int, keep: float, *,
+                     scores: Optional[torch.Tensor] = None, want_scores: bool = False,
+                     keep_mask: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+                     stream=None):
+    """-> keep_mask (uint8 [nblocks]) or (keep_mask, scores) when scores are requested."""
+    M, K, ldx = _dense2d(X, "X")
+    nblocks = (-(-M // br)) * (-(-K // bc)) if br > 0 and bc > 0 else 0
+    if scores is None and want_scores:
+        scores = torch.empty(nblocks, dtype=torch.float64, device=X.device)
+    if keep_mask is None:
+        keep_mask = torch.empty(nblocks, dtype=torch.uint8, device=X.device)
+    code = dtype_code(X.dtype)
+    ws = _workspace(bsr_workspace_bytes(BSR_OP_SCORE_SELECT, M, K, 0, br, bc, code), X.device, ws)
+    rc = lib().bsr_score_select(_ptr(X), code, M, K, ldx, br, bc, float(keep), _ptr(scores),
+                                _ptr(keep_mask), _ptr(ws), ws.numel() if ws is not None else 0,
+                                _stream(stream))
+    _check(rc, "bsr_score_select")
+    return (keep_mask, scores) if scores is not None else keep_mask
+
+
+def bsr_compress(X: torch.Tensor, br: int, bc: int, keep_mask: torch.Tensor, n_keep: int, *,
+                 row_ptr: Optional[torch.Tensor] = None, col_idx: Optional[torch.Tensor] = None,
+                 values: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+                 stream=None):
+    """-> (row_ptr int32 [nbr+1], col_idx int32 [n_keep], values [n_keep, br, bc])."""
+    M, K, ldx = _dense2d(X, "X")
+    nbr = -(-M // br) if br > 0 else 0
+    dev = X.device
+    if row_ptr is None:
+        row_ptr = torch.empty(nbr + 1, dtype=torch.int32, device=dev)
+    if col_idx is None:
+        col_idx = torch.empty(max(n_keep, 0), dtype=torch.int32, device=dev)
+    if values is None:
+        values = torch.empty((max(n_keep, 0), br, bc), dtype=X.dtype, device=dev)
+    code = dtype_code(X.dtype)
+    ws = _workspace(bsr_workspace_bytes(BSR_OP_COMPRESS, M, K, 0, br, bc, code), dev, ws)
+    rc = lib().bsr_compress(_ptr(X), code, M, K, ldx, br, bc, _ptr(keep_mask), int(n_keep),
+                            _ptr(row_ptr), _ptr(col_idx), _ptr(values), _ptr(ws),
+                            ws.numel() if ws is not None else 0, _stream(stream))
+    _check(rc, "bsr_compress")
+    return row_ptr, col_idx, values
+
+
+def bsr_decompress(row_ptr: torch.Tensor, col_idx: torch.Tensor, values: torch.Tensor, M: int,
+                   K: int, br: int, bc: int, *, out: Optional[torch.Tensor] = None, stream=None):
+    """-> X_out [M x K]: kept blocks bit for bit, +0.0 elsewhere."""
+    if out is None:
+        out = torch.empty((M, K), dtype=values.dtype, device=values.device)
+    _, _, ldx = _dense2d(out, "out")
+    rc = lib().bsr_decompress(_ptr(row_ptr), _ptr(col_idx), _ptr(values), dtype_code(values.dtype),
+                              M, K, ldx, br, bc, _ptr(out), _stream(stream))
+    _check(rc, "bsr_decompress")
+    return out
+
+
+def bsr_t_dense_matmul(row_ptr: torch.Tensor, col_idx: torch.Tensor, values: torch.Tensor, M: int,
+                       K: int, br: int, bc: int, dY: torch.Tensor, *,
+                       dW: Optional[torch.Tensor] = None, accumulate: bool = False,
+                       ws: Optional[torch.Tensor] = None, stream=None):
+    """-> dW [K x N] float32 = Xhat^T dY (added to dW when accumulate)."""
+    Md, N, lddy = _dense2d(dY, "dY")
+    if Md != M:
+        raise ValueError("dY must have M rows")
+    if dW is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing dW")
+        dW = torch.empty((K, N), dtype=torch.float32, device=dY.device)
+    _, _, lddw = _dense2d(dW, "dW")
+    code = dtype_code(dY.dtype)
+    if values.dtype != dY.dtype:
+        raise BsrError(BSR_ERR_DTYPE, "values and dY differ in dtype")
+    ws = _workspace(bsr_workspace_bytes(BSR_OP_T_DENSE_MATMUL, M, K, N, br, bc, code), dY.device, ws)
+    rc = lib().bsr_t_dense_matmul(_ptr(row_ptr), _ptr(col_idx), _ptr(values), code, M, K, br, bc,
+                                  _ptr(dY), N, lddy, _ptr(dW), lddw, 1 if accumulate else 0,
+                                  _ptr(ws), ws.numel() if ws is not None else 0, _stream(stream))
+    _check(rc, "bsr_t_dense_matmul")
+    return dW

@@ -1,0 +1,179 @@
+// C ABI of libbsr_actprune: argument validation on the host, then kernel
+// launches on the caller's stream.  See include/bsr_actprune.h for the contract
+// of every entry point.
+#include <cmath>
+
+#include "common.h"
+
+namespace bsr {
+
+static thread_local int g_last_hip_error = 0;
+
+void set_hip_error(int e) { g_last_hip_error = e; }
+
+int check_launch() {
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return BSR_OK;
+  g_last_hip_error = (int)e;
+  return BSR_ERR_HIP;
+}
+
+namespace {
+
+constexpr int64_t kMaxBlocks = (int64_t(1) << 31) - 1;
+constexpr int kMaxBlockDim = 1 << 16;
+
+struct Geometry {
+  int64_t nbr, nbc, nblocks;
+};
+
+// Shared shape checks.  ld is the leading dimension of the dense matrix.
+int check_shape(int dtype, int64_t M, int64_t K, int64_t ld, int br, int bc, Geometry *g) {
+  if (dtype != BSR_F32 && dtype != BSR_BF16) return BSR_ERR_DTYPE;
+  if (M < 0 || K < 0 || br < 1 || bc < 1 || br > kMaxBlockDim || bc > kMaxBlockDim) return BSR_ERR_SHAPE;
+  if (ld < K) return BSR_ERR_SHAPE;
+  if (M > (int64_t(1) << 40) || K > (int64_t(1) << 40) || ld > (int64_t(1) << 40)) return BSR_ERR_SHAPE;
+  g->nbr = ceil_div(M, br);
+  g->nbc = ceil_div(K, bc);
+  if (g->nbr > kMaxBlocks || g->nbc > kMaxBlocks) return BSR_ERR_SHAPE;
+  if (g->nbc != 0 && g->nbr > kMaxBlocks / g->nbc) return BSR_ERR_SHAPE;
+  g->nblocks = g->nbr * g->nbc;
+  if ((double)M * (double)ld * 4.0 > 9.0e18) return BSR_ERR_SHAPE;
+  return BSR_OK;
+}
+
+bool misaligned(const void *p, size_t a) { return p != nullptr && (uintptr_t)p % a != 0; }
+
+size_t score_select_ws(int64_t nblocks) { return align_up((size_t)nblocks * sizeof(double), 256); }
+
+}  // namespace
+}  // namespace bsr
+
+using namespace bsr;
+
+extern "C" {
+
+const char *bsr_version(void) { return "bsr_actprune 0.1 (gfx950)"; }
+
+const char *bsr_error_string(int code) {
+  switch (code) {
+    case BSR_OK: return "BSR_OK";
+    case BSR_ERR_NULL: return "BSR_ERR_NULL";
+    case BSR_ERR_SHAPE: return "BSR_ERR_SHAPE";
+    case BSR_ERR_DTYPE: return "BSR_ERR_DTYPE";
+    case BSR_ERR_KEEP: return "BSR_ERR_KEEP";
+    case BSR_ERR_WORKSPACE: return "BSR_ERR_WORKSPACE";
+    case BSR_ERR_ALIGN: return "BSR_ERR_ALIGN";
+    case BSR_ERR_HIP: return "BSR_ERR_HIP";
+    default: return "BSR_ERR_UNKNOWN";
+  }
+}
+
+int bsr_last_hip_error(void) { return g_last_hip_error; }
+
+int64_t bsr_keep_count(int64_t nblocks, double keep) {
+  if (nblocks < 0 || !(keep >= 0.0 && keep <= 1.0)) return -1;
+  const double v = std::ceil(keep * (double)nblocks);
+  int64_t n = (int64_t)v;
+  if (n < 0) n = 0;
+  if (n > nblocks) n = nblocks;
+  return n;
+}
+
+int64_t bsr_storage_bytes(int64_t M, int64_t K, int br, int bc, int64_t n_keep, int dtype) {
+  Geometry g;
+  if (check_shape(dtype, M, K, K, br, bc, &g) != BSR_OK) return -1;
+  if (n_keep < 0 || n_keep > g.nblocks) return -1;
+  return n_keep * (int64_t)br * bc * elem_bytes(dtype) + 4 * n_keep + 4 * (g.nbr + 1);
+}
+
+size_t bsr_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int br, int bc, int dtype) {
+  Geometry g;
+  if (check_shape(dtype, M, K, K, br, bc, &g) != BSR_OK) return 0;
+  switch (op) {
+    case BSR_OP_SCORE_SELECT: return score_select_ws(g.nblocks);
+    case BSR_OP_COMPRESS: return 0;
+    case BSR_OP_DECOMPRESS: return 0;
+    case BSR_OP_T_DENSE_MATMUL:
+      if (N < 0) return 0;
+      return align_up(dw_generic_ws_bytes(M, K, N, br, bc), 256);
+    default: return 0;
+  }
+}
+
+int bsr_score_select(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int br, int bc,
+                     double keep, double *scores, uint8_t *keep_mask, void *ws, size_t ws_bytes,
+                     void *stream) {
+  Geometry g;
+  int rc = check_shape(dtype, M, K, ldx, br, bc, &g);
+  if (rc != BSR_OK) return rc;
+  const int64_t n_keep = bsr_keep_count(g.nblocks, keep);
+  if (n_keep < 0) return BSR_ERR_KEEP;
+  if (g.nblocks == 0) return BSR_OK;
+  if (X == nullptr || keep_mask == nullptr) return BSR_ERR_NULL;
+  if (misaligned(X, elem_bytes(dtype)) || misaligned(scores, 8) || misaligned(ws, 8)) return BSR_ERR_ALIGN;
+  const size_t need = score_select_ws(g.nblocks);
+  if (ws == nullptr || ws_bytes < need) return BSR_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  double *sc = scores != nullptr ? scores : static_cast<double *>(ws);
+  rc = launch_score(X, dtype, M, K, ldx, br, bc, sc, s);
+  if (rc != BSR_OK) return rc;
+  return launch_select(sc, g.nblocks, n_keep, keep_mask, s);
+}
+
+int bsr_compress(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int br, int bc,
+                 const uint8_t *keep_mask, int64_t n_keep, int32_t *row_ptr, int32_t *col_idx,
+                 void *values, void *ws, size_t ws_bytes, void *stream) {
+  (void)ws;
+  (void)ws_bytes;
+  Geometry g;
+  int rc = check_shape(dtype, M, K, ldx, br, bc, &g);
+  if (rc != BSR_OK) return rc;
+  if (n_keep < 0 || n_keep > g.nblocks) return BSR_ERR_KEEP;
+  if (row_ptr == nullptr) return BSR_ERR_NULL;
+  if (g.nblocks > 0 && (X == nullptr || keep_mask == nullptr)) return BSR_ERR_NULL;
+  if (n_keep > 0 && (col_idx == nullptr || values == nullptr)) return BSR_ERR_NULL;
+  if (misaligned(X, elem_bytes(dtype)) || misaligned(values, elem_bytes(dtype)) ||
+      misaligned(row_ptr, 4) || misaligned(col_idx, 4))
+    return BSR_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = launch_index_build(keep_mask, g.nbr, g.nbc, n_keep, row_ptr, col_idx, s);
+  if (rc != BSR_OK) return rc;
+  return launch_pack(X, dtype, M, K, ldx, br, bc, row_ptr, col_idx, n_keep, values, s);
+}
+
+int bsr_decompress(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int dtype,
+                   int64_t M, int64_t K, int64_t ldx, int br, int bc, void *X_out, void *stream) {
+  Geometry g;
+  int rc = check_shape(dtype, M, K, ldx, br, bc, &g);
+  if (rc != BSR_OK) return rc;
+  if (g.nblocks == 0) return BSR_OK;
+  if (row_ptr == nullptr || X_out == nullptr) return BSR_ERR_NULL;
+  if (misaligned(X_out, elem_bytes(dtype)) || misaligned(values, elem_bytes(dtype)) ||
+      misaligned(row_ptr, 4) || misaligned(col_idx, 4))
+    return BSR_ERR_ALIGN;
+  return launch_decompress(row_ptr, col_idx, values, dtype, M, K, ldx, br, bc, X_out,
+                           static_cast<hipStream_t>(stream));
+}
+
+int bsr_t_dense_matmul(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int dtype,
+                       int64_t M, int64_t K, int br, int bc, const void *dY, int64_t N, int64_t lddy,
+                       float *dW, int64_t lddw, int accumulate, void *ws, size_t ws_bytes,
+                       void *stream) {
+  Geometry g;
+  int rc = check_shape(dtype, M, K, K, br, bc, &g);
+  if (rc != BSR_OK) return rc;
+  if (N < 0 || lddy < N || lddw < N || N > (int64_t(1) << 40)) return BSR_ERR_SHAPE;
+  if (K == 0 || N == 0) return BSR_OK;
+  if (dW == nullptr || row_ptr == nullptr) return BSR_ERR_NULL;
+  if (M > 0 && dY == nullptr) return BSR_ERR_NULL;
+  if (misaligned(values, elem_bytes(dtype)) || misaligned(dY, elem_bytes(dtype)) ||
+      misaligned(dW, 4) || misaligned(row_ptr, 4) || misaligned(col_idx, 4) || misaligned(ws, 16))
+    return BSR_ERR_ALIGN;
+  const size_t need = bsr_workspace_bytes(BSR_OP_T_DENSE_MATMUL, M, K, N, br, bc, dtype);
+  if (need > 0 && (ws == nullptr || ws_bytes < need)) return BSR_ERR_WORKSPACE;
+  return launch_dw_generic(row_ptr, col_idx, values, dtype, M, K, br, bc, dY, N, lddy, dW, lddw,
+                           accumulate, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

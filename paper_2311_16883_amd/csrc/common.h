@@ -1,0 +1,86 @@
+// Internal declarations shared by the HIP translation units of libbsr_actprune.
+// Nothing here is part of the C ABI (see include/bsr_actprune.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "bsr_actprune.h"
+
+namespace bsr {
+
+__host__ __device__ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static inline int elem_bytes(int dtype) { return dtype == BSR_F32 ? 4 : 2; }
+
+// Largest power-of-two vector width (in elements, at most max_v) such that
+// every vector access stays inside one block row and is naturally aligned.
+static inline int pick_vector(int max_v, int esize, int64_t bc, int64_t K, int64_t ld,
+                              const void *p0, const void *p1 = nullptr) {
+  int v = max_v;
+  while (v > 1) {
+    uintptr_t a = (uintptr_t)v * (uintptr_t)esize;
+    bool ok = bc % v == 0 && K % v == 0 && ld % v == 0 && (uintptr_t)p0 % a == 0 &&
+              (p1 == nullptr || (uintptr_t)p1 % a == 0);
+    if (ok) break;
+    v >>= 1;
+  }
+  return v;
+}
+
+// Records hipGetLastError() after a launch; returns BSR_OK or BSR_ERR_HIP.
+int check_launch();
+void set_hip_error(int e);
+
+// ---- launchers (one per kernel family); all enqueue on `s` and return ----
+
+// score.hip: scores[i*nbc+j] = sum of squares of block (i,j), binary64.
+int launch_score(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int br, int bc,
+                 double *scores, hipStream_t s);
+
+// select.hip: keep_mask = 1 for the n_keep best (score desc, index asc).
+int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t *keep_mask,
+                  hipStream_t s);
+
+// pack.hip
+int launch_index_build(const uint8_t *keep_mask, int64_t nbr, int64_t nbc, int64_t n_keep,
+                       int32_t *row_ptr, int32_t *col_idx, hipStream_t s);
+int launch_pack(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int br, int bc,
+                const int32_t *row_ptr, const int32_t *col_idx, int64_t n_keep, void *values,
+                hipStream_t s);
+int launch_decompress(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int dtype,
+                      int64_t M, int64_t K, int64_t ldx, int br, int bc, void *X_out, hipStream_t s);
+
+// dw_generic.hip: any block shape, binary32 FMA.
+size_t dw_generic_ws_bytes(int64_t M, int64_t K, int64_t N, int br, int bc);
+int launch_dw_generic(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int dtype,
+                      int64_t M, int64_t K, int br, int bc, const void *dY, int64_t N, int64_t lddy,
+                      float *dW, int64_t lddw, int accumulate, void *ws, size_t ws_bytes,
+                      hipStream_t s);
+
+// reduce.hip: dW = (accumulate ? dW : 0) + sum_s partial[s], s ascending.
+int launch_splitk_reduce(const float *partial, int splits, int64_t K, int64_t N, float *dW,
+                         int64_t lddw, int accumulate, hipStream_t s);
+
+// ---- device helpers ----
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t h) {
+  return __uint_as_float((uint32_t)h << 16);
+}
+
+template <typename T>
+__device__ __forceinline__ float elem_to_float(T v);
+template <>
+__device__ __forceinline__ float elem_to_float<float>(float v) { return v; }
+template <>
+__device__ __forceinline__ float elem_to_float<uint16_t>(uint16_t v) { return bf16_bits_to_float(v); }
+
+template <typename T, int V>
+struct alignas(sizeof(T) * V) Vec {
+  T e[V];
+};
+
+}  // namespace bsr

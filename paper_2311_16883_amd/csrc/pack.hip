@@ -1,0 +1,214 @@
+// Dense -> BSR conversion and its inverse (paper Sec. II-A: crow / col / values;
+// Sec. III: "the activation tensor is converted to the BSR format").
+//
+//   index build : exclusive prefix sum of the keep mask in linear block order
+//                 -> row_ptr (crow) and col_idx (col);
+//   pack        : bit copy of the kept blocks into `values` (HBM-bound gather);
+//   decompress  : BSR -> dense, pruned positions become +0.0.
+// All three are pure data movement / integer work and are bit-exact.
+#include "common.h"
+
+namespace bsr {
+
+namespace {
+
+constexpr int kIdxThreads = 1024;
+
+// One workgroup scans the whole mask: thread t owns the contiguous chunk
+// [t*chunk, (t+1)*chunk) of linear block indices.
+__global__ __launch_bounds__(kIdxThreads) void index_build_kernel(
+    const uint8_t *__restrict__ mask, int64_t nblocks, int64_t nbr, int64_t nbc, int64_t n_keep,
+    int32_t *__restrict__ row_ptr, int32_t *__restrict__ col_idx) {
+  __shared__ uint32_t wave_tot[kIdxThreads / 64];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int64_t chunk = ceil_div(nblocks, kIdxThreads);
+  const int64_t b0 = (int64_t)t * chunk;
+  const int64_t b1 = (b0 + chunk) < nblocks ? (b0 + chunk) : nblocks;
+  uint32_t cnt = 0;
+  for (int64_t b = b0; b < b1; ++b) cnt += mask[b] ? 1u : 0u;
+  uint32_t incl = cnt;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t o = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += o;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0;
+  for (int w = 0; w < wave; ++w) base += wave_tot[w];
+  int64_t run = (int64_t)base + incl - cnt;   // kept blocks before b0
+  if (b0 < b1) {
+    int64_t i = b0 / nbc, j = b0 % nbc;
+    for (int64_t b = b0; b < b1; ++b) {
+      if (j == 0) row_ptr[i] = (int32_t)run;
+      if (mask[b]) {
+        if (run < n_keep) col_idx[run] = (int32_t)j;
+        ++run;
+      }
+      if (++j == nbc) { j = 0; ++i; }
+    }
+    if (b1 == nblocks) row_ptr[nbr] = (int32_t)run;
+  }
+}
+
+__global__ void zero_row_ptr_kernel(int32_t *row_ptr, int64_t n) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n;
+       i += (int64_t)gridDim.x * blockDim.x)
+    row_ptr[i] = 0;
+}
+
+// Vector of VB bytes copied as a unit.
+template <int VB> struct BytesOf;
+template <> struct BytesOf<2> { typedef uint16_t type; };
+template <> struct BytesOf<4> { typedef uint32_t type; };
+template <> struct BytesOf<8> { typedef uint2 type; };
+template <> struct BytesOf<16> { typedef uint4 type; };
+
+template <int VB> __device__ __forceinline__ typename BytesOf<VB>::type zero_bytes();
+template <> __device__ __forceinline__ uint16_t zero_bytes<2>() { return 0; }
+template <> __device__ __forceinline__ uint32_t zero_bytes<4>() { return 0; }
+template <> __device__ __forceinline__ uint2 zero_bytes<8>() { return make_uint2(0, 0); }
+template <> __device__ __forceinline__ uint4 zero_bytes<16>() { return make_uint4(0, 0, 0, 0); }
+
+// Gather: one workgroup per block-row (grid-stride), threads over
+// (kept block, row, vector).  rowb / ldb / kb are in bytes.
+template <int VB>
+__global__ __launch_bounds__(256) void pack_kernel(
+    const uint8_t *__restrict__ X, int64_t M, int64_t kb, int64_t ldb, int br, int64_t bcb,
+    int64_t nbr, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+    int64_t n_keep, uint8_t *__restrict__ values) {
+  typedef typename BytesOf<VB>::type V;
+  const int vpb = (int)(bcb / VB);
+  for (int64_t i = blockIdx.x; i < nbr; i += gridDim.x) {
+    int64_t p0 = row_ptr[i], p1 = row_ptr[i + 1];
+    if (p1 > n_keep) p1 = n_keep;
+    const int64_t work = (p1 - p0) * br * vpb;
+    for (int64_t f = threadIdx.x; f < work; f += blockDim.x) {
+      const int v = (int)(f % vpb);
+      const int r = (int)((f / vpb) % br);
+      const int64_t q = f / ((int64_t)vpb * br);
+      const int64_t j = col_idx[p0 + q];
+      const int64_t m = i * br + r;
+      const int64_t cb = j * bcb + (int64_t)v * VB;
+      V val = zero_bytes<VB>();
+      if (m < M && cb < kb) val = *reinterpret_cast<const V *>(X + m * ldb + cb);
+      *reinterpret_cast<V *>(values + ((p0 + q) * br + r) * bcb + (int64_t)v * VB) = val;
+    }
+  }
+}
+
+constexpr int kMapCols = 1024;   // block-columns per workgroup in decompress
+
+// Scatter: a workgroup owns block-row i and a chunk of kMapCols block-columns;
+// an LDS table maps block-column -> position in `values` (or -1 = pruned).
+template <int VB>
+__global__ __launch_bounds__(256) void decompress_kernel(
+    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+    const uint8_t *__restrict__ values, int64_t M, int64_t kb, int64_t ldb, int br, int64_t bcb,
+    int64_t nbr, int64_t nbc, uint8_t *__restrict__ X_out) {
+  typedef typename BytesOf<VB>::type V;
+  __shared__ int32_t slot[kMapCols];
+  const int64_t j0 = (int64_t)blockIdx.x * kMapCols;
+  const int ncols = (int)((nbc - j0) < kMapCols ? (nbc - j0) : kMapCols);
+  const int vpb = (int)(bcb / VB);
+  for (int64_t i = blockIdx.y; i < nbr; i += gridDim.y) {
+    for (int c = threadIdx.x; c < ncols; c += blockDim.x) slot[c] = -1;
+    __syncthreads();
+    const int64_t p0 = row_ptr[i], p1 = row_ptr[i + 1];
+    for (int64_t p = p0 + threadIdx.x; p < p1; p += blockDim.x) {
+      const int64_t j = col_idx[p];
+      if (j >= j0 && j < j0 + ncols) slot[j - j0] = (int32_t)p;
+    }
+    __syncthreads();
+    const int rows = (int)((M - i * br) < br ? (M - i * br) : br);
+    const int64_t vrow = (int64_t)ncols * vpb;          // vectors per matrix row in the chunk
+    const int64_t work = (int64_t)rows * vrow;
+    for (int64_t f = threadIdx.x; f < work; f += blockDim.x) {
+      const int r = (int)(f / vrow);
+      const int64_t w = f % vrow;
+      const int c = (int)(w / vpb), v = (int)(w % vpb);
+      const int64_t cb = (j0 + c) * bcb + (int64_t)v * VB;
+      if (cb >= kb) continue;
+      V val = zero_bytes<VB>();
+      const int32_t p = slot[c];
+      if (p >= 0) val = *reinterpret_cast<const V *>(values + ((int64_t)p * br + r) * bcb + (int64_t)v * VB);
+      *reinterpret_cast<V *>(X_out + (i * br + r) * ldb + cb) = val;
+    }
+    __syncthreads();
+  }
+}
+
+// Widest byte vector that divides every extent and alignment involved.
+int pick_bytes(int esize, int bc, int64_t K, int64_t ld, const void *a, const void *b) {
+  int vb = 16;
+  while (vb > esize) {
+    const bool ok = ((int64_t)bc * esize) % vb == 0 && (K * esize) % vb == 0 && (ld * esize) % vb == 0 &&
+                    (uintptr_t)a % vb == 0 && (uintptr_t)b % vb == 0;
+    if (ok) break;
+    vb >>= 1;
+  }
+  return vb;
+}
+
+}  // namespace
+
+int launch_index_build(const uint8_t *keep_mask, int64_t nbr, int64_t nbc, int64_t n_keep,
+                       int32_t *row_ptr, int32_t *col_idx, hipStream_t s) {
+  const int64_t nblocks = nbr * nbc;
+  if (nblocks == 0) {
+    hipLaunchKernelGGL(zero_row_ptr_kernel, dim3(1), dim3(64), 0, s, row_ptr, nbr + 1);
+    return check_launch();
+  }
+  hipLaunchKernelGGL(index_build_kernel, dim3(1), dim3(kIdxThreads), 0, s, keep_mask, nblocks, nbr,
+                     nbc, n_keep, row_ptr, col_idx);
+  return check_launch();
+}
+
+int launch_pack(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int br, int bc,
+                const int32_t *row_ptr, const int32_t *col_idx, int64_t n_keep, void *values,
+                hipStream_t s) {
+  if (n_keep == 0 || M == 0 || K == 0) return BSR_OK;
+  const int e = elem_bytes(dtype);
+  const int64_t nbr = ceil_div(M, br);
+  const int vb = pick_bytes(e, bc, K, ldx, X, values);
+  const unsigned grid = (unsigned)(nbr < 8192 ? nbr : 8192);
+  const uint8_t *x = static_cast<const uint8_t *>(X);
+  uint8_t *v = static_cast<uint8_t *>(values);
+#define BSR_PACK(VB)                                                                             \
+  hipLaunchKernelGGL((pack_kernel<VB>), dim3(grid), dim3(256), 0, s, x, M, K * e, ldx * e, br,  \
+                     (int64_t)bc * e, nbr, row_ptr, col_idx, n_keep, v)
+  switch (vb) {
+    case 16: BSR_PACK(16); break;
+    case 8: BSR_PACK(8); break;
+    case 4: BSR_PACK(4); break;
+    default: BSR_PACK(2); break;
+  }
+#undef BSR_PACK
+  return check_launch();
+}
+
+int launch_decompress(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int dtype,
+                      int64_t M, int64_t K, int64_t ldx, int br, int bc, void *X_out, hipStream_t s) {
+  if (M == 0 || K == 0) return BSR_OK;
+  const int e = elem_bytes(dtype);
+  const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
+  const int vb = pick_bytes(e, bc, K, ldx, X_out, values);
+  const unsigned gx = (unsigned)ceil_div(nbc, kMapCols);
+  int64_t gy = nbr;
+  if (gy > 16384) gy = 16384;
+  const uint8_t *v = static_cast<const uint8_t *>(values);
+  uint8_t *x = static_cast<uint8_t *>(X_out);
+#define BSR_UNPACK(VB)                                                                          \
+  hipLaunchKernelGGL((decompress_kernel<VB>), dim3(gx, (unsigned)gy), dim3(256), 0, s, row_ptr, \
+                     col_idx, v, M, K * e, ldx * e, br, (int64_t)bc * e, nbr, nbc, x)
+  switch (vb) {
+    case 16: BSR_UNPACK(16); break;
+    case 8: BSR_UNPACK(8); break;
+    case 4: BSR_UNPACK(4); break;
+    default: BSR_UNPACK(2); break;
+  }
+#undef BSR_UNPACK
+  return check_launch();
+}
+
+}  // namespace bsr

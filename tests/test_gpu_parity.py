@@ -1,0 +1,246 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element, on the same seeded inputs.
+
+Bars: block indices, row_ptr, col_idx and BSR values bit-exact; scores to a few
+binary64 roundings (the reduction order differs, the precision does not);
+dW to max|dW - ref| / max|ref| <= 1e-5 for binary32 inputs and <= 2e-2 for
+bfloat16 inputs (both accumulate in binary32; exact bfloat16 products keep the
+bfloat16 path far inside its bar, which a second, tighter assertion records).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_16883_amd import binding as B
+from paper_2311_16883_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DW_TOL = {"f32": 1e-5, "bf16": 2e-2}
+DW_TOL_DERIVED = 2e-5       # binary32 accumulation of exact products, either dtype
+
+
+def to_dev(a: np.ndarray) -> torch.Tensor:
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def rand_pair(M, K, N, dtype, seed, dist="normal"):
+    spec = synth.TensorSpec("t", M, K, N, 1, 1, dtype, dist)
+    return synth.make_pair(spec, seed)
+
+
+def gpu_prune(Xd, br, bc, keep):
+    M, K = Xd.shape
+    nbr, nbc = oracle.grid(M, K, br, bc)
+    mask, scores = B.bsr_score_select(Xd, br, bc, keep, want_scores=True)
+    n_keep = B.bsr_keep_count(nbr * nbc, keep)
+    row_ptr, col_idx, values = B.bsr_compress(Xd, br, bc, mask, n_keep)
+    return scores, mask, row_ptr, col_idx, values
+
+
+def check_forward(X, br, bc, keep, label=""):
+    """score/select/compress/decompress of X against the oracle; returns device BSR."""
+    print(f"[case] forward {label} shape={X.shape} dtype={X.dtype} block={br}x{bc} keep={keep}", flush=True)
+    M, K = X.shape
+    Xd = to_dev(X)
+    o_scores, o_mask, o_rp, o_ci, o_val = oracle.prune(X, br, bc, keep)
+    scores, mask, row_ptr, col_idx, values = gpu_prune(Xd, br, bc, keep)
+    torch.cuda.synchronize()
+    g_scores = scores.cpu().numpy()
+    finite = np.isfinite(o_scores)
+    assert np.array_equal(np.isnan(g_scores), np.isnan(o_scores))
+    n_el = br * bc
+    assert np.all(np.abs(g_scores[finite] - o_scores[finite]) <= 2.0 ** -52 * n_el * np.abs(o_scores[finite]))
+    g_mask = mask.cpu().numpy()
+    if not np.array_equal(g_mask, o_mask):
+        diff = np.flatnonzero(g_mask != o_mask)
+        raise AssertionError(f"selection differs at blocks {diff[:8]}, oracle scores {o_scores[diff[:8]]}")
+    assert np.array_equal(row_ptr.cpu().numpy(), o_rp)
+    assert np.array_equal(col_idx.cpu().numpy(), o_ci)
+    assert to_host(values).tobytes() == o_val.tobytes()
+    back = B.bsr_decompress(row_ptr, col_idx, values, M, K, br, bc)
+    torch.cuda.synchronize()
+    assert to_host(back).tobytes() == oracle.mask_dense(X, br, bc, o_mask).tobytes()
+    return (row_ptr, col_idx, values), o_mask
+
+
+def dw_error(got: np.ndarray, ref: np.ndarray) -> float:
+    scale = float(np.max(np.abs(ref)))
+    return float(np.max(np.abs(got.astype(np.float64) - ref))) / (scale if scale > 0 else 1.0)
+
+
+FORWARD_CASES = [
+    # M, K, br, bc, dtype, keep
+    (256, 128, 16, 16, "f32", 0.5),
+    (1000, 200, 32, 32, "f32", 0.25),        # ragged rows and columns
+    (777, 196, 14, 14, "bf16", 0.5),         # the cross-patch block shape, ragged rows
+    (1024, 384, 32, 32, "bf16", 0.5),
+    (1024, 384, 32, 32, "bf16", 0.75),
+    (130, 1000, 1, 8, "bf16", 0.1),          # row segments (1 x b)
+    (300, 70, 7, 5, "f32", 0.9),             # nothing divides: scalar loads
+    (2048, 1536, 64, 64, "bf16", 0.5),
+    (96, 8192, 8, 4096, "bf16", 0.5),        # a block row wider than one workgroup pass
+    (50, 3, 64, 64, "f32", 0.5),             # a single ragged block
+    (4096, 384, 16, 16, "bf16", 0.9),        # > 4096 blocks: several radix levels
+]
+
+
+@pytest.mark.parametrize("M,K,br,bc,dtype,keep", FORWARD_CASES)
+def test_forward_parity(M, K, br, bc, dtype, keep):
+    X, _ = rand_pair(M, K, 8, dtype, seed=M + K, dist="gelu" if bc == 16 else "normal")
+    check_forward(X, br, bc, keep)
+
+
+def test_config1_tiny_end_to_end():
+    spec = synth.tiny()[0]
+    X, dY = synth.make_pair(spec, 0)
+    (row_ptr, col_idx, values), o_mask = check_forward(X, spec.br, spec.bc, spec.keep, "config1")
+    assert int(o_mask.sum()) == 64
+    dW = B.bsr_t_dense_matmul(row_ptr, col_idx, values, spec.M, spec.K, spec.br, spec.bc, to_dev(dY))
+    torch.cuda.synchronize()
+    ref = oracle.dw(oracle.mask_dense(X, spec.br, spec.bc, o_mask), dY)
+    assert dw_error(dW.cpu().numpy(), ref) <= DW_TOL["f32"]
+
+
+@pytest.mark.parametrize("keep", [0.0, 1.0 / 128, 0.3, 1.0])
+def test_degenerate_keeps(keep):
+    spec = synth.tiny()[0]
+    X, dY = synth.make_pair(spec, 1)
+    (row_ptr, col_idx, values), o_mask = check_forward(X, spec.br, spec.bc, keep, "degenerate")
+    dW = B.bsr_t_dense_matmul(row_ptr, col_idx, values, spec.M, spec.K, spec.br, spec.bc, to_dev(dY))
+    torch.cuda.synchronize()
+    ref = oracle.dw(oracle.mask_dense(X, spec.br, spec.bc, o_mask), dY)
+    if keep == 0.0:
+        assert not dW.cpu().numpy().any()
+    else:
+        assert dw_error(dW.cpu().numpy(), ref) <= DW_TOL["f32"]
+    if keep == 1.0:   # keep-ratio 1 reproduces the dense gradient
+        dense = X.astype(np.float64).T @ dY.astype(np.float64)
+        assert dw_error(dW.cpu().numpy(), dense) <= DW_TOL["f32"]
+
+
+@pytest.mark.parametrize("M,K,br,bc,dtype", [(512, 256, 16, 16, "f32"), (2048, 256, 16, 16, "bf16"),
+                                             (1030, 130, 8, 8, "bf16")])
+def test_ties_go_to_the_lowest_index(M, K, br, bc, dtype):
+    rng = np.random.default_rng(M)
+    # constant matrix: all full blocks tie; the first n_keep linear indices survive
+    X = np.full((M, K), 1.5, dtype=np.float32)
+    X = X if dtype == "f32" else synth.f32_to_bf16_bits(X)
+    for keep in (0.5, 0.37):
+        check_forward(X, br, bc, keep, "constant")
+    # small integers: exact sums in any order, many ties at every level
+    Xi = rng.integers(-2, 3, size=(M, K)).astype(np.float32)
+    Xi = Xi if dtype == "f32" else synth.f32_to_bf16_bits(Xi)
+    for keep in (0.5, 0.11, 0.93):
+        check_forward(Xi, br, bc, keep, "integers")
+
+
+def test_nan_inf_and_signed_zero_blocks():
+    X, _ = rand_pair(128, 128, 8, "f32", seed=3)
+    X[5, 5] = np.nan
+    X[40, 100] = np.inf
+    X[70, 3] = -0.0
+    X[100:116, 16:32] = 0.0
+    check_forward(X, 16, 16, 0.5, "nan/inf")
+    Xb = synth.f32_to_bf16_bits(X)
+    check_forward(Xb, 16, 16, 0.25, "nan/inf bf16")
+
+
+def test_strided_input_and_output_views():
+    X, dY = rand_pair(200, 96, 40, "bf16", seed=9)
+    big = torch.zeros((200, 160), dtype=torch.bfloat16, device="cuda")
+    big[:, 32:128] = to_dev(X)
+    view = big[:, 32:128]                       # ldx = 160, base offset 64 bytes
+    mask, scores = B.bsr_score_select(view, 8, 8, 0.5, want_scores=True)
+    n_keep = B.bsr_keep_count(mask.numel(), 0.5)
+    row_ptr, col_idx, values = B.bsr_compress(view, 8, 8, mask, n_keep)
+    torch.cuda.synchronize()
+    _, o_mask, o_rp, o_ci, o_val = oracle.prune(X, 8, 8, 0.5)
+    assert np.array_equal(mask.cpu().numpy(), o_mask)
+    assert np.array_equal(col_idx.cpu().numpy(), o_ci) and np.array_equal(row_ptr.cpu().numpy(), o_rp)
+    assert to_host(values).tobytes() == o_val.tobytes()
+    out = torch.full((200, 100), 7.0, dtype=torch.bfloat16, device="cuda")
+    B.bsr_decompress(row_ptr, col_idx, values, 200, 96, 8, 8, out=out[:, 2:98])
+    torch.cuda.synchronize()
+    host = to_host(out)
+    assert host[:, 2:98].tobytes() == oracle.mask_dense(X, 8, 8, o_mask).tobytes()
+    assert np.all(host[:, :2] == host[0, 0]) and np.all(host[:, 98:] == host[0, 0])   # untouched
+
+
+DW_CASES = [
+    # M, K, N, br, bc, dtype, keep
+    (512, 128, 96, 16, 16, "f32", 0.5),
+    (1000, 200, 130, 32, 32, "f32", 0.25),
+    (777, 196, 196, 14, 14, "bf16", 0.5),
+    (2048, 384, 1536, 32, 32, "bf16", 0.5),
+    (2048, 1536, 384, 32, 32, "bf16", 0.5),
+    (1024, 256, 64, 64, 64, "bf16", 0.75),
+    (640, 384, 100, 16, 16, "bf16", 0.1),
+    (260, 72, 40, 1, 8, "f32", 0.5),
+    (300, 70, 33, 7, 5, "bf16", 0.6),
+]
+
+
+@pytest.mark.parametrize("M,K,N,br,bc,dtype,keep", DW_CASES)
+def test_dw_parity(M, K, N, br, bc, dtype, keep):
+    print(f"[case] dW M={M} K={K} N={N} block={br}x{bc} {dtype} keep={keep}", flush=True)
+    X, dY = rand_pair(M, K, N, dtype, seed=M + N, dist="gelu" if K > 1000 else "normal")
+    o_scores, o_mask, o_rp, o_ci, o_val = oracle.prune(X, br, bc, keep)
+    ref = oracle.dw(oracle.mask_dense(X, br, bc, o_mask), dY)
+    dYd = to_dev(dY)
+    # BSR operands come from the oracle here so that this test isolates the operator
+    rp, ci = torch.from_numpy(o_rp).cuda(), torch.from_numpy(o_ci).cuda()
+    val = to_dev(o_val.reshape(-1, bc)).reshape(o_val.shape)
+    dW = B.bsr_t_dense_matmul(rp, ci, val, M, K, br, bc, dYd)
+    torch.cuda.synchronize()
+    err = dw_error(dW.cpu().numpy(), ref)
+    assert err <= DW_TOL[dtype] and err <= DW_TOL_DERIVED, err
+    # accumulate on top of an existing gradient
+    base = torch.full((K, N), 0.25, dtype=torch.float32, device="cuda")
+    B.bsr_t_dense_matmul(rp, ci, val, M, K, br, bc, dYd, dW=base, accumulate=True)
+    torch.cuda.synchronize()
+    assert dw_error(base.cpu().numpy() - 0.25, ref) <= 1e-4 * max(1.0, 0.25 / np.max(np.abs(ref)))
+    # strided dY and dW views
+    wide = torch.zeros((M, N + 24), dtype=dYd.dtype, device="cuda")
+    wide[:, 8:8 + N] = dYd
+    outw = torch.zeros((K, N + 8), dtype=torch.float32, device="cuda")
+    B.bsr_t_dense_matmul(rp, ci, val, M, K, br, bc, wide[:, 8:8 + N], dW=outw[:, 4:4 + N])
+    torch.cuda.synchronize()
+    assert np.array_equal(outw[:, 4:4 + N].cpu().numpy(), dW.cpu().numpy())
+    assert not outw[:, :4].any() and not outw[:, 4 + N:].any()
+
+
+def test_results_are_reproducible_run_to_run():
+    X, dY = rand_pair(2048, 384, 256, "bf16", seed=77)
+    Xd, dYd = to_dev(X), to_dev(dY)
+    outs = []
+    for _ in range(2):
+        scores, mask, rp, ci, val = gpu_prune(Xd, 32, 32, 0.5)
+        dW = B.bsr_t_dense_matmul(rp, ci, val, 2048, 384, 32, 32, dYd)
+        torch.cuda.synchronize()
+        outs.append([scores.cpu().numpy().tobytes(), mask.cpu().numpy().tobytes(), rp.cpu().numpy().tobytes(),
+                     ci.cpu().numpy().tobytes(), to_host(val).tobytes(), dW.cpu().numpy().tobytes()])
+    assert outs[0] == outs[1]
+
+
+def test_empty_inputs():
+    for (M, K) in [(0, 64), (64, 0)]:
+        X = torch.empty((M, K), dtype=torch.float32, device="cuda")
+        mask = B.bsr_score_select(X, 16, 16, 0.5)
+        assert mask.numel() == 0
+        rp, ci, val = B.bsr_compress(X, 16, 16, mask, 0)
+        torch.cuda.synchronize()
+        assert rp.cpu().numpy().tolist() == [0] * (-(-M // 16) + 1)
+        dY = torch.ones((M, 8), dtype=torch.float32, device="cuda")
+        dW = B.bsr_t_dense_matmul(rp, ci, val, M, K, 16, 16, dY)
+        torch.cuda.synchronize()
+        assert dW.shape == (K, 8) and not dW.cpu().numpy().any()

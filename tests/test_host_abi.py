@@ -1,0 +1,129 @@
+"""Host side of the C ABI (CPU only): the library loads, exports every symbol
+the header declares, its pure host functions agree with the oracle and the
+paper's tables, and invalid arguments are rejected before anything is launched."""
+import ctypes as C
+import re
+from pathlib import Path
+
+import pytest
+
+import oracle
+from paper_2311_16883_amd import binding as B
+
+ROOT = Path(__file__).resolve().parent.parent
+GOLDEN = Path(__file__).resolve().parent / "golden"
+
+
+def declared_symbols():
+    text = (ROOT / "include" / "bsr_actprune.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bsr_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    syms = declared_symbols()
+    assert set(syms) == set(B.EXPORTS) and len(syms) == 10
+    lib = B.lib()
+    for s in syms:
+        assert getattr(lib, s) is not None
+    assert "gfx950" in B.bsr_version()
+
+
+def test_keep_count_agrees_with_oracle():
+    for keep in (0.0, 0.1, 0.25, 1 / 3, 0.5, 0.7, 0.75, 0.9, 1.0):
+        for n in list(range(0, 300)) + [4704, 9408, 37632, 49154, 75264, 301056]:
+            assert B.bsr_keep_count(n, keep) == oracle.keep_count(n, keep)
+    for bad in (-1e-9, 1.0000001, float("nan"), float("inf")):
+        assert B.lib().bsr_keep_count(10, bad) == -1
+    assert B.lib().bsr_keep_count(-1, 0.5) == -1
+
+
+def test_storage_bytes_agree_with_oracle_and_table_2():
+    for (M, K, br, bc, dt, e) in [(6272, 384, 1, 16, B.BSR_F32, 4), (25088, 1536, 32, 32, B.BSR_BF16, 2),
+                                  (49152, 196, 14, 14, B.BSR_BF16, 2)]:
+        nbr, nbc = oracle.grid(M, K, br, bc)
+        for n_keep in (0, 1, nbr * nbc // 2, nbr * nbc):
+            assert B.bsr_storage_bytes(M, K, br, bc, n_keep, dt) == oracle.bsr_bytes(n_keep, nbr, br, bc, e)
+    # paper Table II, the b = 16 column (384-wide binary32 rows, 1 x b blocks)
+    rows = [l.split() for l in (GOLDEN / "table2_bsr_overhead.txt").read_text().splitlines()
+            if l and not l.startswith("#")]
+    col = rows[0].index("16")
+    R, D = 6272, 384
+    for row in rows[1:]:
+        s = int(row[0]) / 100
+        n_keep = round((1 - s) * R * (D // 16))
+        got = B.bsr_storage_bytes(R, D, 1, 16, n_keep, B.BSR_F32)
+        overhead = 100.0 * (got - (1 - s) * R * D * 4) / (R * D * 4)
+        assert abs(overhead - float(row[col])) <= 0.025
+    assert B.lib().bsr_storage_bytes(10, 10, 0, 4, 1, 0) == -1
+    assert B.lib().bsr_storage_bytes(10, 10, 2, 2, 26, 0) == -1
+
+
+def test_workspace_bytes_are_sane():
+    assert B.bsr_workspace_bytes(B.BSR_OP_SCORE_SELECT, 25088, 384, 0, 32, 32, B.BSR_BF16) >= 8 * 9408
+    assert B.bsr_workspace_bytes(B.BSR_OP_SCORE_SELECT, 25088, 384, 0, 32, 32, 9) == 0
+    assert B.bsr_workspace_bytes(99, 25088, 384, 0, 32, 32, B.BSR_BF16) == 0
+    assert B.bsr_workspace_bytes(B.BSR_OP_T_DENSE_MATMUL, 25088, 384, 1536, 32, 32, B.BSR_BF16) % 256 == 0
+
+
+def test_invalid_arguments_are_rejected_on_the_host():
+    """None of these reaches a kernel launch: they are safe without a GPU."""
+    lib = B.lib()
+    fake = C.c_void_p(0x1000)          # never dereferenced: validation fails first
+    odd = C.c_void_p(0x1001)
+    ss = lambda **k: lib.bsr_score_select(
+        k.get("X", fake), k.get("dtype", 0), k.get("M", 64), k.get("K", 64), k.get("ldx", 64),
+        k.get("br", 16), k.get("bc", 16), k.get("keep", 0.5), None, k.get("mask", fake),
+        k.get("ws", fake), k.get("ws_bytes", 1 << 20), None)
+    assert ss(dtype=2) == B.BSR_ERR_DTYPE
+    assert ss(M=-1) == B.BSR_ERR_SHAPE
+    assert ss(br=0) == B.BSR_ERR_SHAPE
+    assert ss(ldx=63) == B.BSR_ERR_SHAPE
+    assert ss(keep=1.5) == B.BSR_ERR_KEEP
+    assert ss(keep=float("nan")) == B.BSR_ERR_KEEP
+    assert ss(X=None) == B.BSR_ERR_NULL
+    assert ss(mask=None) == B.BSR_ERR_NULL
+    assert ss(X=odd) == B.BSR_ERR_ALIGN
+    assert ss(ws=None) == B.BSR_ERR_WORKSPACE
+    assert ss(ws_bytes=8) == B.BSR_ERR_WORKSPACE
+    assert ss(M=1 << 41) == B.BSR_ERR_SHAPE
+    assert ss(M=1 << 30, K=1 << 30, ldx=1 << 30, br=1, bc=1) == B.BSR_ERR_SHAPE   # nblocks >= 2^31
+    assert ss(M=0) == B.BSR_OK and ss(K=0, ldx=0) == B.BSR_OK                    # empty: nothing to do
+
+    cp = lambda **k: lib.bsr_compress(
+        k.get("X", fake), k.get("dtype", 1), 64, 64, 64, 16, 16, k.get("mask", fake),
+        k.get("n_keep", 8), k.get("row_ptr", fake), k.get("col_idx", fake), k.get("values", fake),
+        None, 0, None)
+    assert cp(dtype=-1) == B.BSR_ERR_DTYPE
+    assert cp(n_keep=17) == B.BSR_ERR_KEEP
+    assert cp(n_keep=-1) == B.BSR_ERR_KEEP
+    assert cp(row_ptr=None) == B.BSR_ERR_NULL
+    assert cp(values=None) == B.BSR_ERR_NULL
+    assert cp(values=odd) == B.BSR_ERR_ALIGN
+    assert cp(col_idx=C.c_void_p(0x1002)) == B.BSR_ERR_ALIGN
+
+    assert lib.bsr_decompress(fake, fake, fake, 1, 64, 64, 64, 16, 16, None, None) == B.BSR_ERR_NULL
+    assert lib.bsr_decompress(fake, fake, fake, 5, 64, 64, 64, 16, 16, fake, None) == B.BSR_ERR_DTYPE
+    assert lib.bsr_decompress(fake, fake, fake, 1, 64, 64, 32, 16, 16, fake, None) == B.BSR_ERR_SHAPE
+
+    mm = lambda **k: lib.bsr_t_dense_matmul(
+        fake, fake, fake, k.get("dtype", 1), 64, 64, 16, 16, k.get("dY", fake), k.get("N", 32),
+        k.get("lddy", 32), k.get("dW", fake), k.get("lddw", 32), 0, k.get("ws", fake),
+        k.get("ws_bytes", 1 << 30), None)
+    assert mm(dtype=3) == B.BSR_ERR_DTYPE
+    assert mm(N=-1) == B.BSR_ERR_SHAPE
+    assert mm(lddy=31) == B.BSR_ERR_SHAPE
+    assert mm(lddw=8) == B.BSR_ERR_SHAPE
+    assert mm(dW=None) == B.BSR_ERR_NULL
+    assert mm(dY=None) == B.BSR_ERR_NULL
+    assert mm(dW=C.c_void_p(0x1002)) == B.BSR_ERR_ALIGN
+    assert mm(N=0, lddy=0, lddw=0) == B.BSR_OK
+    assert B.lib().bsr_error_string(B.BSR_ERR_WORKSPACE) == b"BSR_ERR_WORKSPACE"
+
+
+def test_product_path_does_not_touch_the_oracle():
+    """The binding and the kernels never import or link the CPU oracle."""
+    pkg = ROOT / "paper_2311_16883_amd"
+    for f in list(pkg.glob("*.py")) + list((pkg / "csrc").glob("*")):
+        text = f.read_text()
+        assert "import oracle" not in text and "from oracle" not in text and "liboracle" not in text, f
