@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the structured-activation-pruning hot path on one MI355X.
+
+Workload (``config.workload``): the full pruned-activation set of ResMLP-S12 at
+batch 128, bfloat16 storage, binary32 accumulation, 50 % of the blocks kept:
+for each of the 12 residual blocks the cross-patch linear input [49152 x 196]
+(14 x 14 blocks), the fc1 input [25088 x 384] and the fc2 input [25088 x 1536]
+(32 x 32 blocks), each with its output gradient.  Inputs are seeded synthetic
+stand-ins (``paper_2311_16883_amd/synth.py``) and are resident in HBM before
+the clock starts.
+
+One step = one pass of the whole path over all 36 tensors:
+score+select -> compress -> decompress -> dW, every call through the C ABI.
+
+Prints ONE JSON line.  ``value`` is the whole-step rate: block-sparse dW flops
+on the kept blocks per step divided by the wall time of the whole step (so the
+compressor's time counts against it).  ``phases`` gives the two halves of the
+metric on their own clocks: compress GB/s and dW TFLOP/s.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBPS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=20)
+    p.add_argument("--warmup", type=int, default=3)
+    p.add_argument("--layers", type=int, default=12, help="residual blocks of the workload (12 = ResMLP-S12)")
+    p.add_argument("--batch", type=int, default=128)
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--phase-reps", type=int, default=5)
+    return p.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path is a single-GPU kernel pipeline "
+              "(sharding is described in DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2311_16883_amd import binding as B
+    from paper_2311_16883_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def to_dev(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)
+        return torch.from_numpy(a).to(dev)
+
+    specs = synth.s12_full(batch=args.batch, layers=args.layers)
+    tensors = []
+    host_sample = None
+    t_gen = time.time()
+    for idx, spec in enumerate(specs):
+        X, dY = synth.make_pair(spec, seed=idx)
+        if host_sample is None and spec.name.endswith("fc1"):
+            host_sample = (spec, X, dY)
+        tdt = torch.bfloat16 if spec.dtype == "bf16" else torch.float32
+        n_keep = B.bsr_keep_count(spec.nblocks, spec.keep)
+        code = B.dtype_code(tdt)
+        ws_bytes = max(B.bsr_workspace_bytes(op, spec.M, spec.K, spec.N, spec.br, spec.bc, code)
+                       for op in range(4))
+        tensors.append(dict(
+            spec=spec, n_keep=n_keep, X=to_dev(X), dY=to_dev(dY),
+            mask=torch.empty(spec.nblocks, dtype=torch.uint8, device=dev),
+            row_ptr=torch.empty(spec.nbr + 1, dtype=torch.int32, device=dev),
+            col_idx=torch.empty(n_keep, dtype=torch.int32, device=dev),
+            values=torch.empty((n_keep, spec.br, spec.bc), dtype=tdt, device=dev),
+            dW=torch.empty((spec.K, spec.N), dtype=torch.float32, device=dev),
+            ws=torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev),
+        ))
+        del X, dY
+    # one dense output buffer per tensor shape for the decompress row
+    outs = {}
+    for t in tensors:
+        s = t["spec"]
+        key = (s.M, s.K)
+        if key not in outs:
+            outs[key] = torch.empty((s.M, s.K), dtype=t["X"].dtype, device=dev)
+        t["Xhat"] = outs[key]
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+
+    def score_select(t):
+        s = t["spec"]
+        B.bsr_score_select(t["X"], s.br, s.bc, s.keep, keep_mask=t["mask"], ws=t["ws"])
+
+    def compress(t):
+        s = t["spec"]
+        B.bsr_compress(t["X"], s.br, s.bc, t["mask"], t["n_keep"], row_ptr=t["row_ptr"],
+                       col_idx=t["col_idx"], values=t["values"], ws=t["ws"])
+
+    def decompress(t):
+        s = t["spec"]
+        B.bsr_decompress(t["row_ptr"], t["col_idx"], t["values"], s.M, s.K, s.br, s.bc, out=t["Xhat"])
+
+    def dw(t):
+        s = t["spec"]
+        B.bsr_t_dense_matmul(t["row_ptr"], t["col_idx"], t["values"], s.M, s.K, s.br, s.bc, t["dY"],
+                             dW=t["dW"], ws=t["ws"])
+
+    phases = [("score_select", score_select), ("compress", compress), ("decompress", decompress), ("dw", dw)]
+
+    def step():
+        for t in tensors:
+            for _, f in phases:
+                f(t)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # ---- per-phase clocks (HIP events on the launch stream, after the timed region) ----
+    def timed(fn, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps      # ms
+
+    phase_ms = {}
+    for name, f in phases:
+        phase_ms[name] = timed(lambda: [f(t) for t in tensors], args.phase_reps)
+
+    # ---- the dominant kernel: one event pair around every dW launch ----
+    def per_launch_ms(fn, group):
+        pairs = []
+        for _ in range(args.phase_reps):
+            for t in group:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn(t)
+                e1.record()
+                pairs.append((e0, e1))
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
+
+    def flops(t):
+        s = t["spec"]
+        return 2.0 * t["n_keep"] * s.br * s.bc * s.N
+
+    def x_bytes(t):
+        s = t["spec"]
+        return s.M * s.K * s.elem_bytes
+
+    dw_launch_ms = per_launch_ms(dw, tensors)
+    total_flops = sum(flops(t) for t in tensors)
+    flops_per_launch = total_flops / len(tensors)
+    by_kind = {}
+    for kind in ("xpatch", "fc1", "fc2"):
+        grp = [t for t in tensors if t["spec"].name.endswith(kind)]
+        ms = per_launch_ms(dw, grp)
+        by_kind[kind] = {"ms_per_launch": round(ms, 5),
+                         "TFLOPs": round(flops(grp[0]) / (ms * 1e-3) / 1e12, 3)}
+
+    keep = specs[0].keep
+    comp_alg_bytes = sum((1.0 + 2.0 * keep) * x_bytes(t) for t in tensors)
+    comp_ms = phase_ms["score_select"] + phase_ms["compress"]
+    dense_bytes = sum(x_bytes(t) for t in tensors)
+    bsr_bytes = sum(B.bsr_storage_bytes(t["spec"].M, t["spec"].K, t["spec"].br, t["spec"].bc, t["n_keep"],
+                                        B.dtype_code(t["X"].dtype)) for t in tensors)
+
+    achieved_tflops = flops_per_launch / (dw_launch_ms * 1e-3) / 1e12
+    result = {
+        "metric": "compress GB/s + block-sparse dW TFLOP/s (nonzero blocks) at ResMLP-S12, 50% keep",
+        "value": round(total_flops / (ms_per_step * 1e-3) / 1e12, 4),
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"ResMLP-S12 full activation set, batch {args.batch}, {args.layers} layers x "
+                               "(xpatch 14x14, fc1 32x32, fc2 32x32), bf16, keep 0.5",
+                   "tensors_per_step": len(tensors), "keep": keep,
+                   "step": "score+select -> compress -> decompress -> dW for every tensor"},
+        "phases": {
+            "compress_GBps": round(comp_alg_bytes / (comp_ms * 1e-3) / 1e9, 2),
+            "compress_input_GBps": round(dense_bytes / (comp_ms * 1e-3) / 1e9, 2),
+            "dw_TFLOPs": round(total_flops / (phase_ms["dw"] * 1e-3) / 1e12, 3),
+            "ms": {k: round(v, 4) for k, v in phase_ms.items()},
+            "dw_by_tensor": by_kind,
+        },
+        "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 5),
+                     "traffic": None, "kernel": "bsr_t_dense_matmul (dW)",
+                     "flops_per_launch": flops_per_launch, "ms_per_launch": round(dw_launch_ms, 5)},
+        "roofline_compress": {"bound": "hbm", "achieved": round(comp_alg_bytes / (comp_ms * 1e-3) / 1e9, 2),
+                              "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                              "frac": round(comp_alg_bytes / (comp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 5),
+                              "bytes_per_step": comp_alg_bytes},
+        "activation_memory": {"dense_MiB": round(dense_bytes / 2 ** 20, 2), "bsr_MiB": round(bsr_bytes / 2 ** 20, 2),
+                              "saved_frac": round(1.0 - bsr_bytes / dense_bytes, 4)},
+        "input_generation_s": round(t_gen, 1),
+    }
+
+    if not args.no_cpu_baseline and host_sample is not None:
+        import oracle
+        spec, X, dY = host_sample
+        cores = oracle.num_threads()
+        c0 = time.perf_counter()
+        scores = oracle.block_scores(X, spec.br, spec.bc)
+        mask = oracle.select(scores, oracle.keep_count(spec.nblocks, spec.keep))
+        oracle.bsr_from_mask(X, spec.br, spec.bc, mask)
+        c1 = time.perf_counter()
+        xhat = oracle.mask_dense(X, spec.br, spec.bc, mask)
+        ncols = 1024                                          # bounded sample of the output columns
+        sub = np.ascontiguousarray(dY[:, :ncols])
+        c2 = time.perf_counter()
+        oracle.dw(xhat, sub)
+        c3 = time.perf_counter()
+        nk = int(mask.sum())
+        f = 2.0 * nk * spec.br * spec.bc * ncols
+        whole = (c1 - c0) + (c3 - c2)
+        result["cpu_baseline"] = {
+            "value": round(f / whole / 1e12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"layer 0 fc1 [{spec.M}x{spec.K}] bf16: score+select+BSR on the whole tensor, "
+                      f"dW on the first {ncols} of {spec.N} output columns",
+            "compress_GBps": round((1.0 + 2.0 * spec.keep) * X.nbytes / (c1 - c0) / 1e9, 3),
+            "dw_TFLOPs": round(f / (c3 - c2) / 1e12, 6),
+            "seconds": round(whole, 2),
+        }
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

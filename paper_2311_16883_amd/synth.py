@@ -16,6 +16,8 @@ nearest even from binary32).
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, replace
 from typing import List, Optional
 
@@ -28,10 +30,12 @@ DY_STD = 1e-3
 def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
     """Round binary32 to bfloat16 (nearest even); NaN stays a quiet NaN."""
     u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
-    rounded = (u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))) >> np.uint32(16)
+    bias = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    out = ((u + bias) >> np.uint32(16)).astype(np.uint16)
     nan = (u & np.uint32(0x7FFFFFFF)) > np.uint32(0x7F800000)
-    rounded = np.where(nan, (u >> np.uint32(16)) | np.uint32(0x0040), rounded)
-    return rounded.astype(np.uint16)
+    if nan.any():
+        out[nan] = ((u[nan] >> np.uint32(16)) | np.uint32(0x0040)).astype(np.uint16)
+    return out
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
@@ -88,27 +92,56 @@ def _store(a32: np.ndarray, dtype: str) -> np.ndarray:
     return a32 if dtype == "f32" else f32_to_bf16_bits(a32)
 
 
-def make_x(spec: TensorSpec, seed: int) -> np.ndarray:
-    rng = np.random.default_rng([seed, 1])
-    z = rng.standard_normal((spec.M, spec.K), dtype=np.float32)
-    if spec.x_dist == "gelu":
-        x = gelu_erf(z)
-    elif spec.x_dist == "normal":
-        x = z.astype(np.float64)
+_CHUNK_ROWS = 2048          # rows per independently seeded chunk (fixes the data, not the thread count)
+_THREADS = min(16, os.cpu_count() or 1)
+
+
+def _chunked(M: int, ncols: int, out_dtype, fill) -> np.ndarray:
+    """Fill an [M x ncols] array chunk by chunk; chunk c only depends on (seed, c)."""
+    out = np.empty((M, ncols), dtype=out_dtype)
+    chunks = [(c, r0, min(M, r0 + _CHUNK_ROWS)) for c, r0 in enumerate(range(0, M, _CHUNK_ROWS))]
+
+    def work(item):
+        c, r0, r1 = item
+        out[r0:r1] = fill(c, r1 - r0)
+
+    if len(chunks) > 1 and _THREADS > 1:
+        with ThreadPoolExecutor(max_workers=_THREADS) as ex:
+            list(ex.map(work, chunks))
     else:
-        raise ValueError(spec.x_dist)
+        for item in chunks:
+            work(item)
+    return out
+
+
+def make_x(spec: TensorSpec, seed: int) -> np.ndarray:
+    hot = None
     if spec.hot_cols > 0.0:
         nhot = int(np.floor(spec.hot_cols * spec.K))
-        cols = np.arange(nhot) if spec.hot_first else \
+        hot = np.arange(nhot) if spec.hot_first else \
             np.random.default_rng([seed, 3]).permutation(spec.K)[:nhot]
-        x[:, cols] *= spec.hot_scale
-    return _store(x.astype(np.float32), spec.dtype)
+    if spec.x_dist not in ("normal", "gelu"):
+        raise ValueError(spec.x_dist)
+
+    def fill(c, rows):
+        z = np.random.default_rng([seed, 1, c]).standard_normal((rows, spec.K), dtype=np.float32)
+        if spec.x_dist == "gelu" or hot is not None:
+            x = gelu_erf(z) if spec.x_dist == "gelu" else z.astype(np.float64)
+            if hot is not None:
+                x[:, hot] *= spec.hot_scale
+            z = x.astype(np.float32)
+        return _store(z, spec.dtype)
+
+    return _chunked(spec.M, spec.K, np.float32 if spec.dtype == "f32" else np.uint16, fill)
 
 
 def make_dy(spec: TensorSpec, seed: int) -> np.ndarray:
-    rng = np.random.default_rng([seed, 2])
-    g = rng.standard_normal((spec.M, spec.N), dtype=np.float32) * np.float32(DY_STD)
-    return _store(g, spec.dtype)
+    def fill(c, rows):
+        g = np.random.default_rng([seed, 2, c]).standard_normal((rows, spec.N), dtype=np.float32)
+        g *= np.float32(DY_STD)
+        return _store(g, spec.dtype)
+
+    return _chunked(spec.M, spec.N, np.float32 if spec.dtype == "f32" else np.uint16, fill)
 
 
 def make_pair(spec: TensorSpec, seed: int):
