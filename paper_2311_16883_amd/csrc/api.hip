@@ -96,7 +96,14 @@ size_t bsr_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int br, int 
     case BSR_OP_DECOMPRESS: return 0;
     case BSR_OP_T_DENSE_MATMUL:
       if (N < 0) return 0;
-      return align_up(dw_generic_ws_bytes(M, K, N, br, bc), 256);
+      {
+        size_t a = dw_generic_ws_bytes(M, K, N, br, bc);
+        if (dw_mfma_supported(dtype, br, bc, nullptr)) {
+          const size_t b = dw_mfma_ws_bytes(M, K, N, br, bc);
+          if (b > a) a = b;
+        }
+        return align_up(a, 256);
+      }
     default: return 0;
   }
 }
@@ -172,6 +179,9 @@ int bsr_t_dense_matmul(const int32_t *row_ptr, const int32_t *col_idx, const voi
     return BSR_ERR_ALIGN;
   const size_t need = bsr_workspace_bytes(BSR_OP_T_DENSE_MATMUL, M, K, N, br, bc, dtype);
   if (need > 0 && (ws == nullptr || ws_bytes < need)) return BSR_ERR_WORKSPACE;
+  if (dw_mfma_supported(dtype, br, bc, values))
+    return launch_dw_mfma(row_ptr, col_idx, values, M, K, br, bc, dY, N, lddy, dW, lddw, accumulate,
+                          ws, ws_bytes, static_cast<hipStream_t>(stream));
   return launch_dw_generic(row_ptr, col_idx, values, dtype, M, K, br, bc, dY, N, lddy, dW, lddw,
                            accumulate, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
