@@ -122,6 +122,26 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
   }
 }
 
+// Same sum, four columns per thread (N, lddw and the pointers allow 16-byte access).
+__global__ __launch_bounds__(256) void splitk_reduce4_kernel(const float4 *__restrict__ partial,
+                                                             int splits, int64_t K, int64_t N4,
+                                                             float *__restrict__ dW, int64_t lddw,
+                                                             int accumulate) {
+  const int64_t total4 = K * N4;
+  for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < total4;
+       e += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t k = e / N4, n4 = e % N4;
+    float4 *dst = reinterpret_cast<float4 *>(dW + k * lddw) + n4;
+    float4 s = accumulate ? *dst : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int sp = 0; sp < splits; ++sp) {
+      const float4 v = partial[(int64_t)sp * total4 + e];
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    *dst = s;
+  }
+}
+
 int generic_splits(int64_t M, int64_t K, int64_t N, int br) {
   const int64_t nbr = ceil_div(M, br);
   const int64_t tiles = ceil_div(K, TK) * ceil_div(N, TN);
@@ -139,8 +159,15 @@ int launch_splitk_reduce(const float *partial, int splits, int64_t K, int64_t N,
                          int64_t lddw, int accumulate, hipStream_t s) {
   const int64_t total = K * N;
   if (total == 0) return BSR_OK;
+  if (N % 4 == 0 && lddw % 4 == 0 && (uintptr_t)dW % 16 == 0 && (uintptr_t)partial % 16 == 0) {
+    const int64_t blocks = ceil_div(total / 4, 256);
+    hipLaunchKernelGGL(splitk_reduce4_kernel, dim3((unsigned)(blocks < 8192 ? blocks : 8192)),
+                       dim3(256), 0, s, reinterpret_cast<const float4 *>(partial), splits, K, N / 4,
+                       dW, lddw, accumulate);
+    return check_launch();
+  }
   const int64_t blocks = ceil_div(total, 256);
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256),
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)(blocks < 8192 ? blocks : 8192)), dim3(256),
                      0, s, partial, splits, K, N, dW, lddw, accumulate);
   return check_launch();
 }

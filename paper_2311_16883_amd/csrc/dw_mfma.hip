@@ -20,6 +20,8 @@
 // matrix-core granularity.  Global loads of stage s+1 are in flight (held in
 // registers) while stage s is multiplied.  With more than one split the partial
 // tiles go to the workspace and a second kernel adds them in a fixed order.
+#include <cstdlib>
+
 #include "common.h"
 
 namespace bsr {
@@ -32,27 +34,45 @@ typedef __attribute__((ext_vector_type(8))) __bf16 v8bf;
 typedef __attribute__((ext_vector_type(16))) float v16f;
 
 constexpr int kThreads = 256;
-constexpr int kMaxRowsPerSplit = 1024;   // block-rows whose tile index fits in LDS
+constexpr int kMaxRowsPerSplit = 512;   // block-rows whose tile index fits in LDS
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 template <int BYTES> struct Chunk;
-template <> struct Chunk<16> { typedef uint4 type; };
-template <> struct Chunk<8> { typedef uint2 type; };
+template <> struct Chunk<16> { typedef u32x4 type; };
+template <> struct Chunk<8> { typedef u32x2 type; };
 template <> struct Chunk<4> { typedef uint32_t type; };
 template <> struct Chunk<2> { typedef uint16_t type; };
 
-template <int BYTES> __device__ __forceinline__ typename Chunk<BYTES>::type chunk_zero();
-template <> __device__ __forceinline__ uint4 chunk_zero<16>() { return make_uint4(0, 0, 0, 0); }
-template <> __device__ __forceinline__ uint2 chunk_zero<8>() { return make_uint2(0, 0); }
-template <> __device__ __forceinline__ uint32_t chunk_zero<4>() { return 0u; }
-template <> __device__ __forceinline__ uint16_t chunk_zero<2>() { return 0; }
+constexpr uint32_t kOutOfRange = 0xFFFFFFFFu;   // buffer offset that reads as zero, touches no memory
+
+// Untyped buffer resource over [base, base + bytes): loads at offsets beyond
+// `bytes` return zero without a memory access, which predicates a load without
+// a branch (the compiler can then count outstanding loads exactly).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+
+template <int BYTES>
+__device__ __forceinline__ typename Chunk<BYTES>::type buffer_load(__amdgpu_buffer_rsrc_t r, uint32_t off);
+template <> __device__ __forceinline__ u32x4 buffer_load<16>(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+}
+template <> __device__ __forceinline__ u32x2 buffer_load<8>(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+  return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+}
+template <> __device__ __forceinline__ uint32_t buffer_load<4>(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+  return __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0);
+}
+template <> __device__ __forceinline__ uint16_t buffer_load<2>(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+  return __builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0);
+}
 
 // 8 contraction elements x 16 rows/columns for this lane's 16-lane group,
-// transposed out of a row-major LDS tile (two 4 x 16 sub-tiles).
-__device__ __forceinline__ v8bf read_fragment(const uint16_t *tile, int ld, int row0, int col0) {
-  const int l = threadIdx.x & 63, g = l >> 4, L = l & 15;
-  const int row = row0 + 8 * (g >> 1) + (L >> 2);
-  const int col = col0 + 16 * (g & 1) + 4 * (L & 3);
-  const uint16_t *p = tile + row * ld + col;
+// transposed out of a row-major LDS tile (two 4 x 16 sub-tiles).  `p` already
+// points at this lane's first sub-tile (see lane_fragment_offset).
+__device__ __forceinline__ v8bf read_fragment(const uint16_t *p, int ld) {
   typedef v4s __attribute__((address_space(3))) * lds_v4s;
   const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p));
   const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p + 4 * ld));
@@ -62,148 +82,289 @@ __device__ __forceinline__ v8bf read_fragment(const uint16_t *tile, int ld, int 
   return __builtin_bit_cast(v8bf, r);
 }
 
-template <int BR, int BC, int MS, int KT, int NT, int VB>
+// LDS tiles are 128 elements (256 bytes, all 64 banks) wide and unpadded.  The
+// transposing read fetches four consecutive rows per 16-lane group, which
+// would all hit the same banks; so the 32-byte chunk index of every element
+// is XOR-ed with twice the row's low two bits: four consecutive rows of one
+// chunk, and of the neighbouring chunk read by the next lane group, then land
+// on eight different bank groups.
+constexpr int kLd = 128;
+__device__ __forceinline__ int swizzled(int row, int col) {
+  return row * kLd + ((((col >> 4) ^ ((row & 3) << 1)) << 4) | (col & 15));
+}
+
+// Element offset of this lane's part of the 16-row x 32-column fragment whose
+// top-left corner is (0, col0): lanes 0-15 / 16-31 take columns 0-15 / 16-31 of
+// rows 0-7, lanes 32-63 the same columns of rows 8-15.  Adding a multiple of
+// 4 rows keeps the swizzle valid.
+__device__ __forceinline__ int lane_fragment_offset(int col0) {
+  const int l = threadIdx.x & 63, g = l >> 4, L = l & 15;
+  return swizzled(8 * (g >> 1) + (L >> 2), col0 + 16 * (g & 1) + 4 * (L & 3));
+}
+
+#ifdef BSR_DW_PROFILE
+__device__ unsigned long long g_prof[4096][8];
+#define PROF_T(x) const unsigned long long x = __builtin_readcyclecounter()
+#else
+#define PROF_T(x)
+#endif
+
+constexpr int KT = 128, NT = 128;   // dW tile of one workgroup: 2 x 2 waves of 64 x 64
+
+template <int BR, int BC, int MS, int VB>
 struct Geo {
   static constexpr int R = MS / BR;                       // block-rows per stage
   static constexpr int ROWS = R * BR;                     // rows of a stage that carry data
   static constexpr bool KALIGNED = (KT % BC == 0);
   static constexpr int JT = KALIGNED ? KT / BC : KT / BC + 2;   // block-columns that can cross a tile
-  static constexpr bool SKIP_ONLY = (BC % 32 == 0) && (BR % 16 == 0) && KALIGNED;  // no zero fill needed
+  // every 16 x 32 piece of the activation tile lies inside one block: pruned
+  // blocks are skipped outright and their LDS content is never read
+  static constexpr bool SKIP_ONLY = (BC % 32 == 0) && (BR % 16 == 0) && KALIGNED;
   static constexpr int VA = (BC % 8 == 0) ? 8 : ((BC % 4 == 0) ? 4 : ((BC % 2 == 0) ? 2 : 1));
   static constexpr int VPB = BR * BC / VA;                // vectors per block
   static constexpr int NA = (R * JT * VPB + kThreads - 1) / kThreads;
   static constexpr int NB = (ROWS * (NT / VB) + kThreads - 1) / kThreads;
-  static constexpr int LDA = KT + 16, LDB = NT + 16;      // padded LDS rows (elements)
-  static constexpr int KSUB = KT / 32, NSUB = NT / 32, MSUB = MS / 16;
-  static_assert(MS % 16 == 0 && KT % 64 == 0 && NT % 64 == 0 && R >= 1, "tile shape");
+  static constexpr int LDA = kLd, LDB = kLd;             // LDS rows (elements), swizzled not padded
+  static constexpr int MSUB = MS / 16;
+  // a wave-wide activation load (64 vectors) never straddles two blocks: the keep
+  // decision and the block address are wave-uniform and live in scalar registers
+  static constexpr bool UNIFORM_A = (VPB % 64 == 0);
+  static constexpr int STAGE_WORDS = (MS * LDA + MS * LDB) / 2;   // 32-bit words of one stage (A tile, B tile)
+  static_assert(MS % 16 == 0 && R >= 1 && MSUB <= 8, "stage shape");
   static_assert(JT <= 32, "tile index is a 32-bit mask");
-  static_assert(NA <= 16, "2 state bits per staged vector");
 };
 
-template <int BR, int BC, int MS, int KT, int NT, int VB>
+// D = stages whose global loads are in flight (register ring), D even.
+template <int BR, int BC, int MS, int VB, int D>
 __global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
     const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const uint16_t *__restrict__ values, const uint16_t *__restrict__ dY, float *__restrict__ out,
     int64_t M, int64_t K, int64_t N, int64_t lddy, int64_t ldo, int64_t split_stride, int64_t nbr,
-    int64_t nbc, int64_t stages_per_split, int accumulate) {
-  typedef Geo<BR, BC, MS, KT, NT, VB> G;
+    int64_t nbc, int64_t stages_per_split, int accumulate, int tiles_k, int tiles_n, int splits,
+    int xcd_map, uint32_t values_bytes, uint32_t dy_bytes) {
+  typedef Geo<BR, BC, MS, VB> G;
   typedef typename Chunk<G::VA * 2>::type AVec;
   typedef typename Chunk<VB * 2>::type BVec;
+  static_assert(D % 2 == 0, "ring depth and LDS double buffer stay in phase");
 
-  __shared__ __attribute__((aligned(16))) uint16_t sA[MS * G::LDA];
-  __shared__ __attribute__((aligned(16))) uint16_t sB[MS * G::LDB];
+  // Workgroup ids are dealt to the 8 XCDs round-robin.  All tiles of one split
+  // of the contraction read the same activation rows and dY rows, so a split
+  // can be pinned to one XCD and its tiles share that XCD's L2.
+  const int tiles = tiles_k * tiles_n;
+  int split, tile;
+  if (xcd_map) {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    split = xcd + 8 * (slot / tiles);
+    tile = slot % tiles;
+  } else {
+    split = blockIdx.x / tiles;
+    tile = blockIdx.x % tiles;
+  }
+  if (split >= splits) return;
+  const int tile_x = tile % tiles_k, tile_y = tile / tiles_k;
+
+  // two stage buffers (A tile then B tile each); before the main loop the
+  // same memory holds the column indices of this split
+  __shared__ __attribute__((aligned(16))) uint32_t sStage[2 * G::STAGE_WORDS];
   __shared__ uint32_t sMask[kMaxRowsPerSplit];
-  __shared__ int32_t sBase[kMaxRowsPerSplit];
-  __shared__ uint32_t sAct[2][G::MSUB];
+  __shared__ int32_t sBase[kMaxRowsPerSplit + 1];
+  __shared__ uint32_t sAct[3][8];
 
-  const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
+  // the wave index lives in a scalar register: everything derived from it (the
+  // activity bits, the skip branches) is then wave-uniform for the compiler too
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wk = wave >> 1, wn = wave & 1;
-  const int64_t k0 = (int64_t)blockIdx.x * KT, n0 = (int64_t)blockIdx.y * NT;
+  const int64_t k0 = (int64_t)tile_x * KT, n0 = (int64_t)tile_y * NT;
   const int64_t total_stages = ceil_div(nbr, G::R);
-  const int64_t s_begin = (int64_t)blockIdx.z * stages_per_split;
+  const int64_t s_begin = (int64_t)split * stages_per_split;
   int64_t s_end = s_begin + stages_per_split;
   if (s_end > total_stages) s_end = total_stages;
+  const int nstages = (int)(s_end - s_begin);
   const int64_t i_begin = s_begin * G::R;
-  const int nrows = (int)((s_end - s_begin) * G::R);       // block-rows of this split (may run past nbr)
+  const int nrows = nstages * G::R;                       // block-rows of this split (may run past nbr)
   const int64_t jfirst = k0 / BC;
   int64_t jlast = (k0 + KT - 1) / BC;
   if (jlast > nbc - 1) jlast = nbc - 1;
   const int jt = (int)(jlast - jfirst + 1);
 
   // ---- tile index: per block-row, which block-columns of the tile are kept ----
-  for (int e = t; e < MS * G::LDA / 2; e += kThreads) reinterpret_cast<uint32_t *>(sA)[e] = 0u;
-  for (int e = t; e < MS * G::LDB / 2; e += kThreads) reinterpret_cast<uint32_t *>(sB)[e] = 0u;
-  if (t < 2 * G::MSUB) (&sAct[0][0])[t] = 0u;
-  for (int rr = t; rr < nrows; rr += kThreads) {
+  // sBase[rr] first holds row_ptr of block-row i_begin + rr (clamped at nbr).
+  for (int rr = t; rr <= nrows; rr += kThreads) {
     const int64_t i = i_begin + rr;
+    sBase[rr] = row_ptr[i < nbr ? i : nbr];
+  }
+  if (t < 24) (&sAct[0][0])[t] = 0u;
+  __syncthreads();
+  const int32_t pos0 = sBase[0];
+  const int ncols = sBase[nrows] - pos0;                   // column indices of the whole split
+  const bool cols_in_lds = ncols <= 2 * G::STAGE_WORDS;
+  if (cols_in_lds)
+    for (int e = t; e < ncols; e += kThreads) sStage[e] = (uint32_t)col_idx[pos0 + e];
+  __syncthreads();
+  constexpr int kRowsPerThread = (kMaxRowsPerSplit + kThreads - 1) / kThreads;
+  uint32_t my_mask[kRowsPerThread];
+  int32_t my_base[kRowsPerThread];
+#pragma unroll
+  for (int q = 0; q < kRowsPerThread; ++q) {
+    const int rr = t + q * kThreads;
     uint32_t mask = 0;
     int32_t base = 0;
-    if (i < nbr) {
-      const int32_t p0 = row_ptr[i], p1 = row_ptr[i + 1];
+    if (rr < nrows) {
+      const int32_t p0 = sBase[rr], p1 = sBase[rr + 1];
       bool first = true;
       for (int32_t p = p0; p < p1; ++p) {
-        const int64_t j = col_idx[p];
+        const int64_t j = cols_in_lds ? (int64_t)sStage[p - pos0] : (int64_t)col_idx[p];
         if (j >= jfirst && j <= jlast) {
           if (first) { base = p; first = false; }
           mask |= 1u << (int)(j - jfirst);
         }
       }
     }
-    sMask[rr] = mask;
-    sBase[rr] = base;
+    my_mask[q] = mask;
+    my_base[q] = base;
   }
   __syncthreads();
-
-  AVec ra[G::NA];
-  uint32_t ra_state = 0;     // 2 bits per vector: 0 = leave LDS alone, 1 = data, 2 = zeros
-  BVec rb[G::NB];
-
-  auto prefetch = [&](int64_t s) {
-    const int rr0 = (int)((s - s_begin) * G::R);
-    ra_state = 0;
 #pragma unroll
-    for (int it = 0; it < G::NA; ++it) {
-      const int v = t + it * kThreads;
-      const int slot = v / G::VPB, off = v % G::VPB;
-      const int rbk = slot / G::JT, jl = slot % G::JT;
-      ra[it] = chunk_zero<G::VA * 2>();
-      if (slot < G::R * G::JT && jl < jt) {
-        const uint32_t mask = sMask[rr0 + rbk];
-        if ((mask >> jl) & 1u) {
-          const int64_t p = (int64_t)sBase[rr0 + rbk] + __popc(mask & ((1u << jl) - 1u));
-          ra[it] = *reinterpret_cast<const AVec *>(values + p * (BR * BC) + (int64_t)off * G::VA);
-          ra_state |= 1u << (2 * it);
-        } else if (!G::SKIP_ONLY) {
-          ra_state |= 2u << (2 * it);
-        }
+  for (int q = 0; q < kRowsPerThread; ++q) {
+    const int rr = t + q * kThreads;
+    if (rr < nrows) {
+      sMask[rr] = my_mask[q];
+      sBase[rr] = my_base[q];
+    }
+  }
+  // rows / columns of the stage buffers that no stage ever writes must read as zero
+  if (!G::SKIP_ONLY || G::ROWS < MS)
+    for (int e = t; e < 2 * G::STAGE_WORDS; e += kThreads) sStage[e] = 0u;
+  __syncthreads();
+
+  // ---- per-thread constants of the two loaders ----
+  const int wave_s = wave;
+  int a_row[G::NA];            // block-row of the stage (0..R-1), or -1: vector not used
+  int a_jl[G::NA];             // block-column inside the tile
+  uint32_t a_src[G::NA];       // byte offset inside the block
+  int a_dst[G::NA];            // element offset inside the A tile
+#pragma unroll
+  for (int it = 0; it < G::NA; ++it) {
+    const int v = t + it * kThreads;
+    const int slot = v / G::VPB, off = v % G::VPB;
+    const int rbk = slot / G::JT, jl = slot % G::JT;
+    const int r = (off * G::VA) / BC, c = (off * G::VA) % BC;
+    const int col = (int)((jfirst + jl) * BC - k0) + c;
+    const bool used = slot < G::R * G::JT && jl < jt && col >= 0 && col + G::VA <= KT;
+    a_row[it] = used ? rbk : -1;
+    a_jl[it] = jl;
+    a_src[it] = (uint32_t)(off * G::VA * 2);
+    a_dst[it] = swizzled(rbk * BR + r, used ? col : 0);
+  }
+  int b_row[G::NB];            // row of the stage, or MS: vector not used
+  uint32_t b_src[G::NB];       // byte offset relative to the first row of the stage (out of range if unused)
+  int b_dst[G::NB];
+#pragma unroll
+  for (int it = 0; it < G::NB; ++it) {
+    const int v = t + it * kThreads;
+    const int r = v / (NT / VB), c = (v % (NT / VB)) * VB;
+    const bool used = r < G::ROWS && n0 + c < N;
+    b_row[it] = used ? r : MS;
+    b_src[it] = used ? (uint32_t)(((int64_t)r * lddy + c) * 2) : kOutOfRange;
+    b_dst[it] = swizzled(r, c);
+  }
+  // dY seen from the first row / column of this workgroup; every stage gets its
+  // own buffer descriptor (scalar registers), so rows past the end of the
+  // matrix fall out of range by themselves
+  const int64_t dy_total = M > 0 ? ((M - 1) * lddy + N) * 2 : 0;           // bytes
+  const int64_t dy_first = (i_begin * BR * lddy + n0) * 2;
+  const int64_t dy_stage = (int64_t)G::ROWS * lddy * 2;
+  const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(values, values_bytes);
+  const uint32_t lane16 = (uint32_t)(lane * G::VA * 2);
+
+  AVec ra[D][G::NA];
+  BVec rb[D][G::NB];
+
+  // Global loads of stage index q (0-based inside the split) into ring slot d.
+  // Branch-free: a vector that is pruned, outside the matrix or beyond the last
+  // stage reads as zero through an out-of-range buffer offset.
+  auto prefetch = [&](int d, int q) {
+    const bool live = q < nstages;
+    const int rr0 = live ? q * G::R : 0;
+    if (G::UNIFORM_A) {
+      uint32_t mask[G::R];
+      uint32_t base[G::R];
+#pragma unroll
+      for (int rbk = 0; rbk < G::R; ++rbk) {
+        mask[rbk] = (uint32_t)__builtin_amdgcn_readfirstlane((int)sMask[rr0 + rbk]);
+        base[rbk] = (uint32_t)__builtin_amdgcn_readfirstlane(sBase[rr0 + rbk]);
+      }
+#pragma unroll
+      for (int it = 0; it < G::NA; ++it) {
+        const int v0 = wave_s * 64 + it * kThreads;                  // first vector of this wave's load
+        const int slot = v0 / G::VPB, off0 = v0 % G::VPB;
+        const int rbk = slot / G::JT, jl = slot % G::JT;
+        uint32_t m = 0, b = 0;
+#pragma unroll
+        for (int x = 0; x < G::R; ++x)
+          if (rbk == x) { m = mask[x]; b = base[x]; }
+        const bool kept = live && slot < G::R * G::JT && jl < jt && ((m >> jl) & 1u);
+        const uint32_t pos = b + __builtin_popcount(m & ((1u << jl) - 1u));
+        const uint16_t *src = values + (int64_t)pos * (BR * BC) + off0 * G::VA;
+        ra[d][it] = buffer_load<G::VA * 2>(make_rsrc(src, kept ? 64u * G::VA * 2u : 0u), lane16);
+      }
+    } else {
+      uint32_t mask[G::R];
+      uint32_t base[G::R];
+#pragma unroll
+      for (int rbk = 0; rbk < G::R; ++rbk) {
+        mask[rbk] = sMask[rr0 + rbk];
+        base[rbk] = (uint32_t)sBase[rr0 + rbk];
+      }
+#pragma unroll
+      for (int it = 0; it < G::NA; ++it) {
+        uint32_t m = 0, b = 0;
+#pragma unroll
+        for (int rbk = 0; rbk < G::R; ++rbk)
+          if (a_row[it] == rbk) { m = mask[rbk]; b = base[rbk]; }
+        const bool kept = live && a_row[it] >= 0 && ((m >> a_jl[it]) & 1u);
+        const uint32_t pos = b + __popc(m & ((1u << a_jl[it]) - 1u));
+        ra[d][it] = buffer_load<G::VA * 2>(rsrc_a, kept ? pos * (uint32_t)(BR * BC * 2) + a_src[it] : kOutOfRange);
       }
     }
-    const int64_t m0 = (i_begin + rr0) * BR;
+    const int64_t first = dy_first + (int64_t)q * dy_stage;
+    int64_t left = live ? dy_total - first : 0;
+    if (left < 0) left = 0;
+    if (left > 0xFFFFFFFFll) left = 0xFFFFFFFFll;
+    const __amdgpu_buffer_rsrc_t rsrc_b =
+        make_rsrc(reinterpret_cast<const char *>(dY) + first, (uint32_t)left);
 #pragma unroll
-    for (int it = 0; it < G::NB; ++it) {
-      const int v = t + it * kThreads;
-      const int r = v / (NT / VB), c = (v % (NT / VB)) * VB;
-      rb[it] = chunk_zero<VB * 2>();
-      if (r < G::ROWS && m0 + r < M && n0 + c < N)
-        rb[it] = *reinterpret_cast<const BVec *>(dY + (m0 + r) * lddy + n0 + c);
-    }
+    for (int it = 0; it < G::NB; ++it) rb[d][it] = buffer_load<VB * 2>(rsrc_b, b_src[it]);
   };
 
-  auto stage_to_lds = [&](int64_t s) {
-    const int rr0 = (int)((s - s_begin) * G::R);
-    const int par = (int)(s & 1);
+  // Ring slot d (stage index q) -> LDS stage buffer `buf`.
+  auto stage_to_lds = [&](int d, int q, int buf) {
+    uint16_t *sA = reinterpret_cast<uint16_t *>(sStage + buf * G::STAGE_WORDS);
+    uint16_t *sB = sA + MS * G::LDA;
 #pragma unroll
-    for (int it = 0; it < G::NA; ++it) {
-      const uint32_t st = (ra_state >> (2 * it)) & 3u;
-      if (st == 0) continue;
-      const int v = t + it * kThreads;
-      const int slot = v / G::VPB, off = v % G::VPB;
-      const int rbk = slot / G::JT, jl = slot % G::JT;
-      const int r = (off * G::VA) / BC, c = (off * G::VA) % BC;
-      const int col = (int)((jfirst + jl) * BC - k0) + c;
-      if (col < 0 || col + G::VA > KT) continue;
-      *reinterpret_cast<AVec *>(&sA[(rbk * BR + r) * G::LDA + col]) = ra[it];
-    }
+    for (int it = 0; it < G::NA; ++it)
+      if (a_row[it] >= 0) *reinterpret_cast<AVec *>(&sA[a_dst[it]]) = ra[d][it];   // data, zeros if pruned
 #pragma unroll
-    for (int it = 0; it < G::NB; ++it) {
-      const int v = t + it * kThreads;
-      const int r = v / (NT / VB), c = (v % (NT / VB)) * VB;
-      if (r < G::ROWS) *reinterpret_cast<BVec *>(&sB[r * G::LDB + c]) = rb[it];
-    }
-    // which 16-row x 32-column pieces of the activation tile hold a kept block
-    if (t < G::R * G::JT) {
-      const int rbk = t / G::JT, jl = t % G::JT;
-      if (jl < jt && ((sMask[rr0 + rbk] >> jl) & 1u)) {
-        int c0 = (int)((jfirst + jl) * BC - k0), c1 = c0 + BC - 1;
-        if (c0 < 0) c0 = 0;
-        if (c1 > KT - 1) c1 = KT - 1;
-        if (c0 <= c1) {
-          const uint32_t bits = ((2u << (c1 >> 5)) - 1u) & ~((1u << (c0 >> 5)) - 1u);
-          for (int ms = (rbk * BR) >> 4; ms <= (rbk * BR + BR - 1) >> 4; ++ms) atomicOr(&sAct[par][ms], bits);
+    for (int it = 0; it < G::NB; ++it)
+      if (b_row[it] < MS) *reinterpret_cast<BVec *>(&sB[b_dst[it]]) = rb[d][it];
+    if (!G::SKIP_ONLY) {
+      // which 16-row x 32-column pieces of the activation tile hold a kept block
+      const int rr0 = q * G::R;
+      if (t < G::R * G::JT && q < nstages) {
+        const int rbk = t / G::JT, jl = t % G::JT;
+        if (jl < jt && ((sMask[rr0 + rbk] >> jl) & 1u)) {
+          int c0 = (int)((jfirst + jl) * BC - k0), c1 = c0 + BC - 1;
+          if (c0 < 0) c0 = 0;
+          if (c1 > KT - 1) c1 = KT - 1;
+          if (c0 <= c1) {
+            const uint32_t bits = ((2u << (c1 >> 5)) - 1u) & ~((1u << (c0 >> 5)) - 1u);
+            for (int ms = (rbk * BR) >> 4; ms <= (rbk * BR + BR - 1) >> 4; ++ms) atomicOr(&sAct[q % 3][ms], bits);
+          }
         }
       }
+      if (t < 8) sAct[(q + 1) % 3][t] = 0u;
     }
-    if (t < G::MSUB) sAct[par ^ 1][t] = 0u;
   };
 
   v16f acc[2][2];
@@ -214,33 +375,96 @@ __global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[u][w][r] = 0.f;
 
-  static_assert(KT == 128 && NT == 128, "2 x 2 waves of 64 x 64");
+  const int frag_a0 = lane_fragment_offset((2 * wk) * 32), frag_a1 = lane_fragment_offset((2 * wk + 1) * 32);
+  const int frag_b0 = lane_fragment_offset((2 * wn) * 32), frag_b1 = lane_fragment_offset((2 * wn + 1) * 32);
 
-  if (s_begin < s_end) prefetch(s_begin);
-  for (int64_t s = s_begin; s < s_end; ++s) {
-    stage_to_lds(s);
-    __syncthreads();
-    if (s + 1 < s_end) prefetch(s + 1);
-    const int par = (int)(s & 1);
+  // Multiply stage q out of LDS buffer `buf`.
+  auto compute = [&](int q, int buf) {
+    const uint16_t *sA = reinterpret_cast<const uint16_t *>(sStage + buf * G::STAGE_WORDS);
+    const uint16_t *sB = sA + MS * G::LDA;
+    // two activity bits (this wave's two 32-column pieces) per 16-row step
+    uint32_t pam = 0;
+    if (G::SKIP_ONLY) {
 #pragma unroll
-    for (int ms = 0; ms < G::MSUB; ++ms) {
-      const uint32_t act = (uint32_t)__builtin_amdgcn_readfirstlane((int)sAct[par][ms]);
-      const uint32_t mine = (act >> (2 * wk)) & 3u;
-      if (mine == 0) continue;
-      const v8bf b0 = read_fragment(sB, G::LDB, ms * 16, (2 * wn) * 32);
-      const v8bf b1 = read_fragment(sB, G::LDB, ms * 16, (2 * wn + 1) * 32);
+      for (int rbk = 0; rbk < G::R; ++rbk) {
+        const uint32_t m = (uint32_t)__builtin_amdgcn_readfirstlane((int)sMask[q * G::R + rbk]);
+        const uint32_t two = ((m >> ((2 * wk * 32) / BC)) & 1u) | (((m >> (((2 * wk + 1) * 32) / BC)) & 1u) << 1);
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        if (!((mine >> u) & 1u)) continue;
-        const v8bf a = read_fragment(sA, G::LDA, ms * 16, (2 * wk + u) * 32);
-        acc[u][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, acc[u][0], 0, 0, 0);
-        acc[u][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, acc[u][1], 0, 0, 0);
+        for (int ms = rbk * (BR / 16); ms < (rbk + 1) * (BR / 16); ++ms) pam |= two << (2 * ms);
+      }
+    } else {
+#pragma unroll
+      for (int ms = 0; ms < G::MSUB; ++ms) {
+        const uint32_t act = (uint32_t)__builtin_amdgcn_readfirstlane((int)sAct[q % 3][ms]);
+        pam |= ((act >> (2 * wk)) & 3u) << (2 * ms);
       }
     }
-    __syncthreads();
-  }
+    // Static code per block-row (all its 16-row steps, both 32-column pieces of
+    // this wave), entered only if the block-row keeps something in these columns.
+#pragma unroll
+    for (int rbk = 0; rbk < (G::SKIP_ONLY ? G::R : 1); ++rbk) {
+      constexpr int STEPS = G::SKIP_ONLY ? BR / 16 : G::MSUB;
+      const uint32_t two = (pam >> (2 * rbk * STEPS)) & 3u;
+      if (G::SKIP_ONLY && two == 0) continue;
+#pragma unroll
+      for (int x = 0; x < STEPS; ++x) {
+        const int ms = rbk * STEPS + x;
+        const uint32_t mine = G::SKIP_ONLY ? two : (pam >> (2 * ms)) & 3u;
+        if (!G::SKIP_ONLY && mine == 0) continue;
+        const v8bf b0 = read_fragment(sB + frag_b0 + ms * 16 * G::LDB, G::LDB);
+        const v8bf b1 = read_fragment(sB + frag_b1 + ms * 16 * G::LDB, G::LDB);
+        const v8bf a0 = read_fragment(sA + frag_a0 + ms * 16 * G::LDA, G::LDA);
+        const v8bf a1 = read_fragment(sA + frag_a1 + ms * 16 * G::LDA, G::LDA);
+        if (mine & 1u) {
+          acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
+          acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
+        }
+        if (mine & 2u) {
+          acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
+          acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
+        }
+      }
+    }
+  };
 
-  float *o = out + (int64_t)blockIdx.z * split_stride;
+  // ---- main loop: stage q is multiplied out of LDS buffer q&1 while stage
+  // q+1 moves from registers to the other buffer and stage q+1+D leaves HBM ----
+#ifdef BSR_DW_PROFILE
+  unsigned long long p_store = 0, p_pref = 0, p_comp = 0, p_bar = 0;
+  const unsigned long long p_t0 = __builtin_readcyclecounter();
+#endif
+#pragma unroll
+  for (int d = 0; d < D; ++d) prefetch(d, d);
+  stage_to_lds(0, 0, 0);
+  prefetch(0, D);
+  __syncthreads();
+#ifdef BSR_DW_PROFILE
+  const unsigned long long p_t1 = __builtin_readcyclecounter();
+#endif
+  for (int q0 = 0; q0 < nstages; q0 += D) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      const int q = q0 + d;
+      if (q >= nstages) break;
+      PROF_T(ta);
+      stage_to_lds((d + 1) % D, q + 1, (d + 1) & 1);
+      PROF_T(tb);
+      prefetch((d + 1) % D, q + 1 + D);
+      PROF_T(tc);
+      compute(q, d & 1);
+      PROF_T(td);
+      __syncthreads();
+      PROF_T(te);
+#ifdef BSR_DW_PROFILE
+      p_store += tb - ta; p_pref += tc - tb; p_comp += td - tc; p_bar += te - td;
+#endif
+    }
+  }
+#ifdef BSR_DW_PROFILE
+  const unsigned long long p_t2 = __builtin_readcyclecounter();
+#endif
+
+  float *o = out + (int64_t)split * split_stride;
 #pragma unroll
   for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -254,6 +478,14 @@ __global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
           *dst = accumulate ? *dst + acc[u][w][r] : acc[u][w][r];
         }
       }
+#ifdef BSR_DW_PROFILE
+  if (lane == 0 && blockIdx.x < 1024) {
+    const unsigned long long p_t3 = __builtin_readcyclecounter();
+    unsigned long long *g = g_prof[blockIdx.x * 4 + wave];
+    g[0] = p_t1 - p_t0; g[1] = p_t2 - p_t1; g[2] = p_t3 - p_t2; g[3] = p_store; g[4] = p_pref; g[5] = p_comp;
+    g[6] = p_bar; g[7] = nstages;
+  }
+#endif
 }
 
 struct Plan {
@@ -267,7 +499,8 @@ Plan make_plan(int64_t M, int64_t K, int64_t N) {
   const int64_t nbr = ceil_div(M, BR);
   const int64_t stages = ceil_div(nbr, R);
   const int64_t tiles = ceil_div(K, 128) * ceil_div(N, 128);
-  int64_t s = 1024 / (tiles > 0 ? tiles : 1);
+  static const int target = getenv("BSR_DW_TARGET_WGS") ? atoi(getenv("BSR_DW_TARGET_WGS")) : 512;
+  int64_t s = (target + tiles / 2) / (tiles > 0 ? tiles : 1);
   if (s > stages) s = stages;
   if (s < 1) s = 1;
   int64_t sps = stages > 0 ? ceil_div(stages, s) : 1;
@@ -279,7 +512,7 @@ Plan make_plan(int64_t M, int64_t K, int64_t N) {
   return p;
 }
 
-template <int BR, int BC, int MS>
+template <int BR, int BC, int MS, int D>
 int run(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int64_t M, int64_t K,
         const void *dY, int64_t N, int64_t lddy, float *dW, int64_t lddw, int accumulate, void *ws,
         size_t ws_bytes, hipStream_t s) {
@@ -291,15 +524,21 @@ int run(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int6
   const int64_t ldo = p.splits > 1 ? N : lddw;
   const int64_t stride = p.splits > 1 ? K * N : 0;
   const int acc_direct = p.splits > 1 ? 0 : accumulate;
-  dim3 grid((unsigned)ceil_div(K, 128), (unsigned)ceil_div(N, 128), (unsigned)p.splits);
+  const int tiles_k = (int)ceil_div(K, 128), tiles_n = (int)ceil_div(N, 128);
+  static const int xcd_map = getenv("BSR_DW_XCD_MAP") ? atoi(getenv("BSR_DW_XCD_MAP")) : 0;
+  dim3 grid((unsigned)((xcd_map ? 8 * ceil_div(p.splits, 8) : p.splits) * tiles_k * tiles_n));
   const uint16_t *v = static_cast<const uint16_t *>(values);
   const uint16_t *y = static_cast<const uint16_t *>(dY);
+  // 32-bit buffer offsets: both operands must stay below 4 GiB (checked by dw_mfma_supported)
+  const uint32_t values_bytes = (uint32_t)(nbr * nbc * BR * BC * 2);
+  const uint32_t dy_bytes = M > 0 ? (uint32_t)(((M - 1) * lddy + N) * 2) : 0u;
   int vb = 8;
   while (vb > 1 && (N % vb != 0 || lddy % vb != 0 || (uintptr_t)dY % (2 * vb) != 0)) vb >>= 1;
 #define BSR_DW_LAUNCH(VB)                                                                         \
-  hipLaunchKernelGGL((dw_mfma_kernel<BR, BC, MS, 128, 128, VB>), grid, dim3(kThreads), 0, s,       \
+  hipLaunchKernelGGL((dw_mfma_kernel<BR, BC, MS, VB, D>), grid, dim3(kThreads), 0, s,              \
                      row_ptr, col_idx, v, y, out, M, K, N, lddy, ldo, stride, nbr, nbc,            \
-                     p.stages_per_split, acc_direct)
+                     p.stages_per_split, acc_direct, tiles_k, tiles_n, p.splits, xcd_map,           \
+                     values_bytes, dy_bytes)
   if (vb == 8) BSR_DW_LAUNCH(8);
   else if (vb == 4) BSR_DW_LAUNCH(4);
   else if (vb == 2) BSR_DW_LAUNCH(2);
@@ -318,17 +557,34 @@ size_t ws_for(int64_t M, int64_t K, int64_t N) {
 
 }  // namespace
 
-bool dw_mfma_supported(int dtype, int br, int bc, const void *values) {
+bool dw_mfma_supported(int dtype, int br, int bc, const void *values, int64_t M, int64_t K, int64_t N,
+                       int64_t lddy) {
   if (dtype != BSR_BF16) return false;
   if ((uintptr_t)values % 16 != 0) return false;
-  return (br == 32 && bc == 32) || (br == 64 && bc == 64) || (br == 16 && bc == 16) ||
-         (br == 14 && bc == 14);
+  const bool shape = (br == 32 && bc == 32) || (br == 64 && bc == 64) || (br == 16 && bc == 16) ||
+                     (br == 14 && bc == 14);
+  if (!shape) return false;
+  // the kernel addresses both operands with 32-bit byte offsets
+  const int64_t limit = (int64_t(1) << 32) - 64;
+  if (ceil_div(M, br) * br * ceil_div(K, bc) * bc * 2 >= limit) return false;
+  if (M * lddy * 2 >= limit || N > lddy) return false;
+  return true;
+}
+
+// Tuning knobs (development only): stage rows and prefetch depth of the 32 x 32 kernel.
+static int knob_ms32() {
+  static const int v = getenv("BSR_DW_MS") ? atoi(getenv("BSR_DW_MS")) : 64;
+  return v == 32 ? 32 : 64;
+}
+static int knob_depth() {
+  static const int v = getenv("BSR_DW_DEPTH") ? atoi(getenv("BSR_DW_DEPTH")) : 2;
+  return v;
 }
 
 size_t dw_mfma_ws_bytes(int64_t M, int64_t K, int64_t N, int br, int bc) {
   (void)bc;
   switch (br) {
-    case 32: return ws_for<32, 32>(M, K, N);
+    case 32: return knob_ms32() == 32 ? ws_for<32, 32>(M, K, N) : ws_for<32, 64>(M, K, N);
     case 64: return ws_for<64, 64>(M, K, N);
     case 16: return ws_for<16, 32>(M, K, N);
     case 14: return ws_for<14, 32>(M, K, N);
@@ -340,15 +596,22 @@ int launch_dw_mfma(const int32_t *row_ptr, const int32_t *col_idx, const void *v
                    int64_t K, int br, int bc, const void *dY, int64_t N, int64_t lddy, float *dW,
                    int64_t lddw, int accumulate, void *ws, size_t ws_bytes, hipStream_t s) {
   if (K == 0 || N == 0) return BSR_OK;
-  if (br == 32 && bc == 32)
-    return run<32, 32, 32>(row_ptr, col_idx, values, M, K, dY, N, lddy, dW, lddw, accumulate, ws, ws_bytes, s);
-  if (br == 64 && bc == 64)
-    return run<64, 64, 64>(row_ptr, col_idx, values, M, K, dY, N, lddy, dW, lddw, accumulate, ws, ws_bytes, s);
-  if (br == 16 && bc == 16)
-    return run<16, 16, 32>(row_ptr, col_idx, values, M, K, dY, N, lddy, dW, lddw, accumulate, ws, ws_bytes, s);
-  if (br == 14 && bc == 14)
-    return run<14, 14, 32>(row_ptr, col_idx, values, M, K, dY, N, lddy, dW, lddw, accumulate, ws, ws_bytes, s);
+#define BSR_ARGS row_ptr, col_idx, values, M, K, dY, N, lddy, dW, lddw, accumulate, ws, ws_bytes, s
+  if (br == 32 && bc == 32) {
+    if (knob_ms32() == 32) return knob_depth() >= 4 ? run<32, 32, 32, 4>(BSR_ARGS) : run<32, 32, 32, 2>(BSR_ARGS);
+    return knob_depth() >= 4 ? run<32, 32, 64, 4>(BSR_ARGS) : run<32, 32, 64, 2>(BSR_ARGS);
+  }
+  if (br == 64 && bc == 64) return run<64, 64, 64, 2>(BSR_ARGS);
+  if (br == 16 && bc == 16) return run<16, 16, 32, 4>(BSR_ARGS);
+  if (br == 14 && bc == 14) return run<14, 14, 32, 2>(BSR_ARGS);
+#undef BSR_ARGS
   return BSR_ERR_SHAPE;
 }
+
+#ifdef BSR_DW_PROFILE
+extern "C" int bsr_debug_read_prof(unsigned long long *host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_prof), sizeof(unsigned long long) * n, 0, hipMemcpyDeviceToHost);
+}
+#endif
 
 }  // namespace bsr
