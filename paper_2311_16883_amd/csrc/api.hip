@@ -44,7 +44,9 @@ int check_shape(int dtype, int64_t M, int64_t K, int64_t ld, int br, int bc, Geo
 
 bool misaligned(const void *p, size_t a) { return p != nullptr && (uintptr_t)p % a != 0; }
 
-size_t score_select_ws(int64_t nblocks) { return align_up((size_t)nblocks * sizeof(double), 256); }
+size_t scores_bytes(int64_t nblocks) { return align_up((size_t)nblocks * sizeof(double), 256); }
+
+size_t score_select_ws(int64_t nblocks) { return scores_bytes(nblocks) + select_ws_bytes(nblocks); }
 
 }  // namespace
 }  // namespace bsr
@@ -118,14 +120,14 @@ int bsr_score_select(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx
   if (n_keep < 0) return BSR_ERR_KEEP;
   if (g.nblocks == 0) return BSR_OK;
   if (X == nullptr || keep_mask == nullptr) return BSR_ERR_NULL;
-  if (misaligned(X, elem_bytes(dtype)) || misaligned(scores, 8) || misaligned(ws, 8)) return BSR_ERR_ALIGN;
+  if (misaligned(X, elem_bytes(dtype)) || misaligned(scores, 8) || misaligned(ws, 16)) return BSR_ERR_ALIGN;
   const size_t need = score_select_ws(g.nblocks);
   if (ws == nullptr || ws_bytes < need) return BSR_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   double *sc = scores != nullptr ? scores : static_cast<double *>(ws);
   rc = launch_score(X, dtype, M, K, ldx, br, bc, sc, s);
   if (rc != BSR_OK) return rc;
-  return launch_select(sc, g.nblocks, n_keep, keep_mask, s);
+  return launch_select(sc, g.nblocks, n_keep, keep_mask, static_cast<char *>(ws) + scores_bytes(g.nblocks), s);
 }
 
 int bsr_compress(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int br, int bc,

@@ -42,7 +42,8 @@ int launch_score(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, in
                  double *scores, hipStream_t s);
 
 // select.hip: keep_mask = 1 for the n_keep best (score desc, index asc).
-int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t *keep_mask,
+size_t select_ws_bytes(int64_t nblocks);
+int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t *keep_mask, void *ws,
                   hipStream_t s);
 
 // pack.hip

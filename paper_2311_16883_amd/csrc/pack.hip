@@ -2,7 +2,7 @@
 // Sec. III: "the activation tensor is converted to the BSR format").
 //
 //   index build : exclusive prefix sum of the keep mask in linear block order
-//                 -> row_ptr (crow) and col_idx (col);
+//                 -> row_ptr (crow) and col_idx (col), one launch;
 //   pack        : bit copy of the kept blocks into `values` (HBM-bound gather);
 //   decompress  : BSR -> dense, pruned positions become +0.0.
 // All three are pure data movement / integer work and are bit-exact.
@@ -12,21 +12,62 @@ namespace bsr {
 
 namespace {
 
-constexpr int kIdxThreads = 1024;
+constexpr int kIdxThreads = 256;
 
-// One workgroup scans the whole mask: thread t owns the contiguous chunk
-// [t*chunk, (t+1)*chunk) of linear block indices.
+__device__ __forceinline__ uint32_t nonzero_bytes(uint32_t x) {
+  // bit 7 of every byte that is not zero
+  return __popc((((x & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | x) & 0x80808080u);
+}
+
+// Workgroup w owns the linear block range [w*per_wg, (w+1)*per_wg).  It first
+// counts the kept blocks in front of its range (every workgroup re-reads the
+// mask prefix from L2: at most a few hundred KB, no second launch, no atomics),
+// then scans its own range: thread t owns a contiguous chunk.
 __global__ __launch_bounds__(kIdxThreads) void index_build_kernel(
     const uint8_t *__restrict__ mask, int64_t nblocks, int64_t nbr, int64_t nbc, int64_t n_keep,
-    int32_t *__restrict__ row_ptr, int32_t *__restrict__ col_idx) {
+    int64_t per_wg, int32_t *__restrict__ row_ptr, int32_t *__restrict__ col_idx) {
   __shared__ uint32_t wave_tot[kIdxThreads / 64];
+  __shared__ uint32_t sh_prefix;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int64_t chunk = ceil_div(nblocks, kIdxThreads);
-  const int64_t b0 = (int64_t)t * chunk;
-  const int64_t b1 = (b0 + chunk) < nblocks ? (b0 + chunk) : nblocks;
+  const int64_t lo = (int64_t)blockIdx.x * per_wg;
+  const int64_t hi = (lo + per_wg) < nblocks ? (lo + per_wg) : nblocks;
+
+  // ---- kept blocks in [0, lo) ----
   uint32_t cnt = 0;
-  for (int64_t b = b0; b < b1; ++b) cnt += mask[b] ? 1u : 0u;
-  uint32_t incl = cnt;
+  {
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(mask);
+    int64_t head = (int64_t)((16 - (addr & 15)) & 15);
+    if (head > lo) head = lo;
+    const int64_t nvec = (lo - head) / 16;
+    const int64_t tail0 = head + nvec * 16;
+    if (t < head) cnt += mask[t] ? 1u : 0u;
+    const uint4 *v = reinterpret_cast<const uint4 *>(mask + head);
+    for (int64_t e = t; e < nvec; e += kIdxThreads) {
+      const uint4 x = v[e];
+      cnt += nonzero_bytes(x.x) + nonzero_bytes(x.y) + nonzero_bytes(x.z) + nonzero_bytes(x.w);
+    }
+    if (tail0 + t < lo) cnt += mask[tail0 + t] ? 1u : 0u;
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d, 64);
+  if (lane == 0) wave_tot[wave] = cnt;
+  __syncthreads();
+  if (t == 0) {
+    uint32_t p = 0;
+    for (int w = 0; w < kIdxThreads / 64; ++w) p += wave_tot[w];
+    sh_prefix = p;
+  }
+  __syncthreads();
+  const uint32_t prefix = sh_prefix;
+  __syncthreads();
+
+  // ---- own range ----
+  const int64_t chunk = ceil_div(per_wg, kIdxThreads);
+  const int64_t b0 = lo + (int64_t)t * chunk;
+  const int64_t b1 = (b0 + chunk) < hi ? (b0 + chunk) : hi;
+  uint32_t mine = 0;
+  for (int64_t b = b0; b < b1; ++b) mine += mask[b] ? 1u : 0u;
+  uint32_t incl = mine;
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) {
     const uint32_t o = __shfl_up(incl, d, 64);
@@ -34,9 +75,9 @@ __global__ __launch_bounds__(kIdxThreads) void index_build_kernel(
   }
   if (lane == 63) wave_tot[wave] = incl;
   __syncthreads();
-  uint32_t base = 0;
+  uint32_t base = prefix;
   for (int w = 0; w < wave; ++w) base += wave_tot[w];
-  int64_t run = (int64_t)base + incl - cnt;   // kept blocks before b0
+  int64_t run = (int64_t)base + incl - mine;   // kept blocks before b0
   if (b0 < b1) {
     int64_t i = b0 / nbc, j = b0 % nbc;
     for (int64_t b = b0; b < b1; ++b) {
@@ -159,8 +200,11 @@ int launch_index_build(const uint8_t *keep_mask, int64_t nbr, int64_t nbc, int64
     hipLaunchKernelGGL(zero_row_ptr_kernel, dim3(1), dim3(64), 0, s, row_ptr, nbr + 1);
     return check_launch();
   }
-  hipLaunchKernelGGL(index_build_kernel, dim3(1), dim3(kIdxThreads), 0, s, keep_mask, nblocks, nbr,
-                     nbc, n_keep, row_ptr, col_idx);
+  int64_t wgs = ceil_div(nblocks, 2048);
+  if (wgs > 128) wgs = 128;
+  const int64_t per_wg = ceil_div(nblocks, wgs);
+  hipLaunchKernelGGL(index_build_kernel, dim3((unsigned)wgs), dim3(kIdxThreads), 0, s, keep_mask,
+                     nblocks, nbr, nbc, n_keep, per_wg, row_ptr, col_idx);
   return check_launch();
 }
 

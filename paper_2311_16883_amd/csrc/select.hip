@@ -2,28 +2,41 @@
 //
 // Exact selection of the n_keep best blocks in the total order
 //   (score descending, linear block index ascending)
-// without sorting everything and without a host round trip.  Every block gets
-// a unique 96-bit rank value
-//   C = key * 2^32 + (nblocks - 1 - index),
-// where key is the bit pattern of its non-negative binary64 score (orders like
-// the value; any NaN becomes one quiet-NaN pattern above +inf).  "Best" means
-// largest C.  The kernel finds the n_keep-th largest C by a most-significant-
-// digit-first radix select with 12-bit digits: a histogram of the current
-// digit over the blocks that still match the chosen prefix, a suffix scan to
-// find the digit that holds the n_keep-th element, repeat.  As soon as the
-// matching set fits in LDS it is ranked there exactly by counting, which also
-// settles ties through the index part of C.  All arithmetic is integer, so the
-// result is the same on every run.
+// without sorting everything and without a host round trip.  key is the bit
+// pattern of the non-negative binary64 score (orders like the value; any NaN
+// becomes one quiet-NaN pattern above +inf), so all arithmetic is integer and
+// the result is the same on every run.
+//
+// Small inputs: one workgroup runs a most-significant-digit-first radix select
+// (12-bit digits) on the 96-bit rank value C = key * 2^32 + (nblocks-1-index):
+// histogram of the current digit over the blocks that still match the chosen
+// prefix, suffix scan for the digit holding the n_keep-th element, repeat; once
+// the matching set fits in LDS it is ranked exactly by counting, which settles
+// ties through the index part of C.
+//
+// Large inputs: two grid-wide passes.
+//   pass 1  every workgroup draws the same 256-key sample, takes from it two
+//           order statistics lo <= hi that bracket the rank of the threshold,
+//           and histograms its slice of the keys into 4096 buckets: bucket 0
+//           below lo, the last bucket above hi, equal-width buckets in between
+//           (any monotone bucketing keeps the selection exact; a good bracket
+//           only makes the threshold bucket small).  The last workgroup to
+//           finish finds the bucket that holds the n_keep-th largest key.
+//   pass 2  buckets above it are kept, buckets below pruned, the keys inside it
+//           are appended to a candidate list; the last workgroup to finish
+//           ranks the candidates exactly (radix select as above if they do not
+//           fit in LDS) and writes their mask bytes.
 #include "common.h"
 
 namespace bsr {
 
 namespace {
 
-constexpr int kSelThreads = 1024;
 constexpr int kDigitBits = 12;
 constexpr int kBins = 1 << kDigitBits;
-constexpr int kCap = 1024;                 // candidates ranked in LDS
+constexpr int kCap = 1024;       // candidates ranked in LDS
+constexpr int kSample = 256;
+constexpr int kGridThreads = 256;
 
 typedef unsigned __int128 u128;
 
@@ -36,9 +49,30 @@ __device__ __forceinline__ u128 rank_value(uint64_t key, uint32_t inv_idx) {
   return ((u128)key << 32) | (u128)inv_idx;
 }
 
-// Exclusive prefix sum over the kSelThreads threads of the block.
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot,
-                                                         uint32_t *total) {
+// Where the elements to select from live: all scores, or a candidate list.
+struct AllScores {
+  const double *scores;
+  __device__ __forceinline__ uint64_t key(uint32_t e) const { return score_key(scores[e]); }
+  __device__ __forceinline__ uint32_t idx(uint32_t e) const { return e; }
+};
+struct Candidates {
+  const uint64_t *keys;
+  const uint32_t *idxs;
+  __device__ __forceinline__ uint64_t key(uint32_t e) const { return keys[e]; }
+  __device__ __forceinline__ uint32_t idx(uint32_t e) const { return idxs[e]; }
+};
+
+struct SelectShared {
+  uint32_t hist[kBins];
+  uint64_t ckey[kCap];
+  uint32_t cidx[kCap];
+  uint32_t wave_tot[16];
+  uint32_t digit, above, count, n;
+};
+
+// Exclusive prefix sum over the THREADS threads of the block.
+template <int THREADS>
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   uint32_t incl = v;
 #pragma unroll
@@ -48,104 +82,228 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *w
   }
   if (lane == 63) wave_tot[wave] = incl;
   __syncthreads();
-  uint32_t base = 0, tot = 0;
-  for (int w = 0; w < kSelThreads / 64; ++w) {
-    const uint32_t x = wave_tot[w];
-    if (w < wave) base += x;
-    tot += x;
-  }
+  uint32_t base = 0;
+  for (int w = 0; w < wave; ++w) base += wave_tot[w];
   __syncthreads();
-  *total = tot;
   return base + incl - v;
 }
 
-__global__ __launch_bounds__(kSelThreads) void select_kernel(const double *__restrict__ scores,
-                                                             int64_t nblocks, int64_t n_keep,
-                                                             uint8_t *__restrict__ mask) {
-  __shared__ uint32_t hist[kBins];
-  __shared__ uint64_t ckey[kCap];
-  __shared__ uint32_t cidx[kCap];
-  __shared__ uint32_t wave_tot[kSelThreads / 64];
-  __shared__ uint32_t sh_digit, sh_above, sh_count, sh_n;
-
+// One workgroup marks the `want` best of the n elements of `src` in mask
+// (1 = kept, 0 = pruned); every element of src gets its byte written.
+template <int THREADS, typename Source>
+__device__ void radix_select(const Source &src, uint32_t n, uint32_t want, uint32_t nblocks,
+                             uint8_t *__restrict__ mask, SelectShared &sh) {
   const int t = threadIdx.x;
-  const uint32_t nb = (uint32_t)nblocks;
-
+  constexpr int kPerThread = kBins / THREADS;
   u128 prefix = 0;          // the top 12*level bits every candidate shares
   int level = 0;
-  uint32_t want = (uint32_t)n_keep;   // how many of the candidates are kept
-  uint32_t n_cand = nb;
+  uint32_t n_cand = n;
 
-  while (n_cand > (uint32_t)kCap) {   // level < kDigits: distinct C leave <= 1 candidate after all digits
-    for (int b = t; b < kBins; b += kSelThreads) hist[b] = 0;
+  while (n_cand > (uint32_t)kCap) {   // distinct C: at most one candidate is left after all 8 digits
+    for (int b = t; b < kBins; b += THREADS) sh.hist[b] = 0;
     __syncthreads();
     const int shift_prefix = 96 - kDigitBits * level;
     const int shift_digit = shift_prefix - kDigitBits;
-    for (uint32_t b = t; b < nb; b += kSelThreads) {
-      const u128 c = rank_value(score_key(scores[b]), nb - 1 - b);
+    for (uint32_t e = t; e < n; e += THREADS) {
+      const u128 c = rank_value(src.key(e), nblocks - 1 - src.idx(e));
       if (level == 0 || (c >> shift_prefix) == prefix)
-        atomicAdd(&hist[(uint32_t)(c >> shift_digit) & (kBins - 1)], 1u);
+        atomicAdd(&sh.hist[(uint32_t)(c >> shift_digit) & (kBins - 1)], 1u);
     }
     __syncthreads();
-    // thread t owns the bins kBins-1-4t ... kBins-4-4t (descending digits)
-    uint32_t h[4], own = 0;
+    // thread t owns kPerThread bins, descending digits
+    uint32_t h[kPerThread], own = 0;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      h[u] = hist[kBins - 1 - (4 * t + u)];
+    for (int u = 0; u < kPerThread; ++u) {
+      h[u] = sh.hist[kBins - 1 - (kPerThread * t + u)];
       own += h[u];
     }
-    uint32_t total;
-    uint32_t above = block_exclusive_scan(own, wave_tot, &total);
+    uint32_t above = block_exclusive_scan<THREADS>(own, sh.wave_tot);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kPerThread; ++u) {
       if (above < want && want <= above + h[u]) {
-        sh_digit = (uint32_t)(kBins - 1 - (4 * t + u));
-        sh_above = above;
-        sh_count = h[u];
+        sh.digit = (uint32_t)(kBins - 1 - (kPerThread * t + u));
+        sh.above = above;
+        sh.count = h[u];
       }
       above += h[u];
     }
     __syncthreads();
-    prefix = (prefix << kDigitBits) | (u128)sh_digit;
-    want -= sh_above;
-    n_cand = sh_count;
+    prefix = (prefix << kDigitBits) | (u128)sh.digit;
+    want -= sh.above;
+    n_cand = sh.count;
     ++level;
     __syncthreads();
   }
 
-  // Everything above the prefix is kept, everything below is pruned, the
-  // candidates that match it go to LDS.
-  if (t == 0) sh_n = 0;
+  // Everything above the prefix is kept, everything below pruned, the
+  // candidates that match it are ranked in LDS.
+  if (t == 0) sh.n = 0;
   __syncthreads();
   const int shift_prefix = 96 - kDigitBits * level;
-  for (uint32_t b = t; b < nb; b += kSelThreads) {
-    const uint64_t key = score_key(scores[b]);
+  for (uint32_t e = t; e < n; e += THREADS) {
+    const uint64_t key = src.key(e);
+    const uint32_t idx = src.idx(e);
     bool inside = true;
     if (level > 0) {
-      const u128 top = rank_value(key, nb - 1 - b) >> shift_prefix;
+      const u128 top = rank_value(key, nblocks - 1 - idx) >> shift_prefix;
       if (top != prefix) {
         inside = false;
-        mask[b] = top > prefix ? 1 : 0;
+        mask[idx] = top > prefix ? 1 : 0;
       }
     }
     if (inside) {
-      const uint32_t pos = atomicAdd(&sh_n, 1u);
-      ckey[pos] = key;
-      cidx[pos] = b;
+      const uint32_t pos = atomicAdd(&sh.n, 1u);
+      sh.ckey[pos] = key;
+      sh.cidx[pos] = idx;
     }
   }
   __syncthreads();
-  const uint32_t n = sh_n;
-  if ((uint32_t)t < n) {
-    const uint64_t key = ckey[t];
-    const uint32_t idx = cidx[t];
+  const uint32_t m = sh.n;
+  for (uint32_t c = t; c < m; c += THREADS) {
+    const uint64_t key = sh.ckey[c];
+    const uint32_t idx = sh.cidx[c];
     uint32_t better = 0;   // candidates that rank strictly before this one
-    for (uint32_t o = 0; o < n; ++o) {
-      const uint64_t ok = ckey[o];
-      better += (ok > key || (ok == key && cidx[o] < idx)) ? 1u : 0u;
+    for (uint32_t o = 0; o < m; ++o) {
+      const uint64_t ok = sh.ckey[o];
+      better += (ok > key || (ok == key && sh.cidx[o] < idx)) ? 1u : 0u;
     }
     mask[idx] = better < want ? 1 : 0;
   }
+}
+
+__global__ __launch_bounds__(1024) void select_small_kernel(const double *__restrict__ scores,
+                                                            uint32_t nblocks, uint32_t n_keep,
+                                                            uint8_t *__restrict__ mask) {
+  __shared__ SelectShared sh;
+  AllScores src{scores};
+  radix_select<1024>(src, nblocks, n_keep, nblocks, mask, sh);
+}
+
+// Control block shared by the two grid-wide passes (lives in the workspace;
+// zeroed, together with the bucket counts, before pass 1 starts).
+struct SelectCtrl {
+  uint32_t ticket1, ticket2, n_cand, bucket;
+  uint32_t above, shift, pad0, pad1;
+  uint64_t lo, hi;
+};
+
+__global__ void select_zero_kernel(uint32_t *p, int words) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < words; i += gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+__device__ __forceinline__ uint32_t bucket_of(uint64_t key, uint64_t lo, uint64_t hi, uint32_t shift) {
+  if (key < lo) return 0u;
+  if (key > hi) return (uint32_t)kBins - 1u;
+  return 1u + (uint32_t)((key - lo) >> shift);
+}
+
+__global__ __launch_bounds__(kGridThreads) void select_hist_kernel(
+    const double *__restrict__ scores, uint32_t nblocks, uint32_t n_keep, uint32_t per_wg,
+    uint32_t *__restrict__ ghist, SelectCtrl *__restrict__ ctrl) {
+  __shared__ uint32_t hist[kBins];
+  __shared__ uint64_t sample[kSample];
+  __shared__ uint64_t bracket[2];
+  __shared__ uint32_t wave_tot[16];
+  __shared__ uint32_t is_last;
+  const int t = threadIdx.x;
+
+  // the same sample in every workgroup: kSample evenly spaced keys
+  sample[t] = score_key(scores[(uint64_t)t * nblocks / kSample]);
+  for (int b = t; b < kBins; b += kGridThreads) hist[b] = 0;
+  if (t < 2) bracket[t] = t == 0 ? 0ull : ~0ull;
+  __syncthreads();
+  {
+    // ascending rank of my sample key (ties by position), then the two order
+    // statistics around the threshold's expected position
+    const uint64_t mine = sample[t];
+    int rank = 0;
+    for (int o = 0; o < kSample; ++o) {
+      const uint64_t k = sample[o];
+      rank += (k < mine || (k == mine && o < t)) ? 1 : 0;
+    }
+    const double frac = 1.0 - (double)n_keep / (double)nblocks;       // threshold's quantile from below
+    const int pos = (int)(frac * kSample);
+    const int delta = 4 + (int)(4.0 * sqrt(kSample * frac * (1.0 - frac)));
+    if (rank == pos - delta) bracket[0] = mine;     // stays 0 if pos - delta < 0
+    if (rank == pos + delta) bracket[1] = mine;     // stays max if pos + delta >= kSample
+  }
+  __syncthreads();
+  const uint64_t lo = bracket[0], hi = bracket[1];
+  const uint64_t range = hi - lo;
+  uint32_t shift = 0;
+  while (shift < 64 && (range >> shift) > (uint64_t)(kBins - 3)) ++shift;
+
+  const uint32_t e0 = blockIdx.x * per_wg;
+  const uint32_t e1 = (e0 + per_wg) < nblocks ? (e0 + per_wg) : nblocks;
+  for (uint32_t e = e0 + t; e < e1; e += kGridThreads)
+    atomicAdd(&hist[bucket_of(score_key(scores[e]), lo, hi, shift)], 1u);
+  __syncthreads();
+  for (int b = t; b < kBins; b += kGridThreads)
+    if (hist[b]) atomicAdd(&ghist[b], hist[b]);
+  __threadfence();
+  __syncthreads();
+  if (t == 0) is_last = (atomicAdd(&ctrl->ticket1, 1u) == gridDim.x - 1) ? 1u : 0u;
+  __syncthreads();
+  if (!is_last) return;
+  __threadfence();
+
+  // last workgroup: the bucket that holds the n_keep-th largest key
+  constexpr int kPerThread = kBins / kGridThreads;
+  uint32_t h[kPerThread], own = 0;
+#pragma unroll
+  for (int u = 0; u < kPerThread; ++u) {
+    h[u] = __hip_atomic_load(&ghist[kBins - 1 - (kPerThread * t + u)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    own += h[u];
+  }
+  uint32_t above = block_exclusive_scan<kGridThreads>(own, wave_tot);
+#pragma unroll
+  for (int u = 0; u < kPerThread; ++u) {
+    if (above < n_keep && n_keep <= above + h[u]) {
+      ctrl->bucket = (uint32_t)(kBins - 1 - (kPerThread * t + u));
+      ctrl->above = above;
+      ctrl->shift = shift;
+      ctrl->lo = lo;
+      ctrl->hi = hi;
+    }
+    above += h[u];
+  }
+}
+
+__global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
+    const double *__restrict__ scores, uint32_t nblocks, uint32_t n_keep, uint32_t per_wg,
+    SelectCtrl *__restrict__ ctrl, uint64_t *__restrict__ cand_key, uint32_t *__restrict__ cand_idx,
+    uint8_t *__restrict__ mask) {
+  __shared__ SelectShared sh;
+  __shared__ uint32_t is_last;
+  const int t = threadIdx.x;
+  const uint32_t bucket = ctrl->bucket, shift = ctrl->shift;
+  const uint64_t lo = ctrl->lo, hi = ctrl->hi;
+
+  const uint32_t e0 = blockIdx.x * per_wg;
+  const uint32_t e1 = (e0 + per_wg) < nblocks ? (e0 + per_wg) : nblocks;
+  for (uint32_t e = e0 + t; e < e1; e += kGridThreads) {
+    const uint64_t key = score_key(scores[e]);
+    const uint32_t b = bucket_of(key, lo, hi, shift);
+    if (b != bucket) {
+      mask[e] = b > bucket ? 1 : 0;
+    } else {
+      const uint32_t pos = atomicAdd(&ctrl->n_cand, 1u);
+      cand_key[pos] = key;
+      cand_idx[pos] = e;
+    }
+  }
+  __threadfence();
+  __syncthreads();
+  if (t == 0) is_last = (atomicAdd(&ctrl->ticket2, 1u) == gridDim.x - 1) ? 1u : 0u;
+  __syncthreads();
+  if (!is_last) return;
+  __threadfence();
+
+  // last workgroup: exact ranking of the candidates
+  const uint32_t n = __hip_atomic_load(&ctrl->n_cand, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const uint32_t want = n_keep - ctrl->above;
+  Candidates src{cand_key, cand_idx};
+  radix_select<kGridThreads>(src, n, want, nblocks, mask, sh);
 }
 
 __global__ void fill_u8_kernel(uint8_t *p, int64_t n, uint8_t v) {
@@ -154,9 +312,29 @@ __global__ void fill_u8_kernel(uint8_t *p, int64_t n, uint8_t v) {
     p[i] = v;
 }
 
+constexpr int64_t kSmallLimit = 8192;      // one workgroup up to here
+
+struct SelectPlan {
+  size_t hist_off, ctrl_off, key_off, idx_off, total;
+};
+
+SelectPlan select_plan(int64_t nblocks) {
+  SelectPlan p;
+  p.hist_off = 0;
+  p.ctrl_off = align_up(kBins * sizeof(uint32_t), 256);
+  p.key_off = p.ctrl_off + align_up(sizeof(SelectCtrl), 256);
+  p.idx_off = p.key_off + align_up((size_t)nblocks * sizeof(uint64_t), 256);
+  p.total = p.idx_off + align_up((size_t)nblocks * sizeof(uint32_t), 256);
+  return p;
+}
+
 }  // namespace
 
-int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t *keep_mask,
+size_t select_ws_bytes(int64_t nblocks) {
+  return nblocks > kSmallLimit ? select_plan(nblocks).total : 0;
+}
+
+int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t *keep_mask, void *ws,
                   hipStream_t s) {
   if (nblocks == 0) return BSR_OK;
   if (n_keep <= 0 || n_keep >= nblocks) {
@@ -165,8 +343,31 @@ int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t
                        (uint8_t)(n_keep > 0 ? 1 : 0));
     return check_launch();
   }
-  hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kSelThreads), 0, s, scores, nblocks, n_keep,
-                     keep_mask);
+  if (nblocks <= kSmallLimit) {
+    hipLaunchKernelGGL(select_small_kernel, dim3(1), dim3(1024), 0, s, scores, (uint32_t)nblocks,
+                       (uint32_t)n_keep, keep_mask);
+    return check_launch();
+  }
+  const SelectPlan p = select_plan(nblocks);
+  char *base = static_cast<char *>(ws);
+  uint32_t *ghist = reinterpret_cast<uint32_t *>(base + p.hist_off);
+  SelectCtrl *ctrl = reinterpret_cast<SelectCtrl *>(base + p.ctrl_off);
+  uint64_t *cand_key = reinterpret_cast<uint64_t *>(base + p.key_off);
+  uint32_t *cand_idx = reinterpret_cast<uint32_t *>(base + p.idx_off);
+  // bucket counts and control block are contiguous: one fill
+  const int zero_words = (int)((p.key_off - p.hist_off) / 4);
+  hipLaunchKernelGGL(select_zero_kernel, dim3(8), dim3(256), 0, s, ghist, zero_words);
+  int rc = check_launch();
+  if (rc != BSR_OK) return rc;
+  int64_t wgs = ceil_div(nblocks, 2048);
+  if (wgs > 256) wgs = 256;
+  const uint32_t per_wg = (uint32_t)ceil_div(nblocks, wgs);
+  hipLaunchKernelGGL(select_hist_kernel, dim3((unsigned)wgs), dim3(kGridThreads), 0, s, scores,
+                     (uint32_t)nblocks, (uint32_t)n_keep, per_wg, ghist, ctrl);
+  rc = check_launch();
+  if (rc != BSR_OK) return rc;
+  hipLaunchKernelGGL(select_classify_kernel, dim3((unsigned)wgs), dim3(kGridThreads), 0, s, scores,
+                     (uint32_t)nblocks, (uint32_t)n_keep, per_wg, ctrl, cand_key, cand_idx, keep_mask);
   return check_launch();
 }
 

@@ -144,6 +144,28 @@ def test_ties_go_to_the_lowest_index(M, K, br, bc, dtype):
         check_forward(Xi, br, bc, keep, "integers")
 
 
+@pytest.mark.parametrize("keep", [0.5, 0.1, 0.9, 0.999])
+def test_grid_wide_selection_paths(keep):
+    """More than 8192 blocks: sampled bracket, bucket histogram, candidate ranking."""
+    M, K, br, bc = 8192, 512, 16, 16            # 16384 blocks
+    rng = np.random.default_rng(5)
+    X = synth.f32_to_bf16_bits(rng.standard_normal((M, K), dtype=np.float32))
+    check_forward(X, br, bc, keep, "normal")
+    # heavy tails and dead blocks: a third of the blocks are exactly zero, a few are huge / NaN
+    Xo = rng.standard_normal((M, K), dtype=np.float32)
+    dead = rng.random((M // br, K // bc)) < 0.33
+    Xo *= ~np.kron(dead, np.ones((br, bc), dtype=bool))
+    Xo[17, 5] = 1e30
+    Xo[4000, 100] = np.nan
+    check_forward(Xo, br, bc, keep, "outliers f32")
+    # small integers: thousands of exact ties inside the threshold bucket
+    Xi = synth.f32_to_bf16_bits(rng.integers(-1, 2, size=(M, K)).astype(np.float32))
+    check_forward(Xi, br, bc, keep, "integer ties")
+    # every block ties
+    Xc = synth.f32_to_bf16_bits(np.full((M, K), 0.5, dtype=np.float32))
+    check_forward(Xc, br, bc, keep, "all equal")
+
+
 def test_nan_inf_and_signed_zero_blocks():
     X, _ = rand_pair(128, 128, 8, "f32", seed=3)
     X[5, 5] = np.nan
