@@ -17,15 +17,16 @@
 // Large inputs: two grid-wide passes.
 //   pass 1  every workgroup draws the same 256-key sample, takes from it two
 //           order statistics lo <= hi that bracket the rank of the threshold,
-//           and histograms its slice of the keys into 4096 buckets: bucket 0
-//           below lo, the last bucket above hi, equal-width buckets in between
-//           (any monotone bucketing keeps the selection exact; a good bracket
-//           only makes the threshold bucket small).  The last workgroup to
-//           finish finds the bucket that holds the n_keep-th largest key.
-//   pass 2  buckets above it are kept, buckets below pruned, the keys inside it
-//           are appended to a candidate list; the last workgroup to finish
-//           ranks the candidates exactly (radix select as above if they do not
-//           fit in LDS) and writes their mask bytes.
+//           and counts its slice of the keys into 256 buckets: bucket 0 below
+//           lo, the last bucket above hi, equal-width buckets in between (any
+//           monotone bucketing keeps the selection exact; a good bracket only
+//           makes the threshold bucket small).  Each workgroup stores its own
+//           counts: no atomics, nothing to clear.
+//   pass 2  every workgroup adds up the counts, finds the bucket that holds the
+//           n_keep-th largest key, keeps the buckets above it, prunes the ones
+//           below and appends the keys inside it to a candidate list; the last
+//           workgroup to finish ranks the candidates exactly (radix select as
+//           above if they do not fit in LDS) and writes their mask bytes.
 #include "common.h"
 
 namespace bsr {
@@ -37,6 +38,7 @@ constexpr int kBins = 1 << kDigitBits;
 constexpr int kCap = 1024;       // candidates ranked in LDS
 constexpr int kSample = 256;
 constexpr int kGridThreads = 256;
+constexpr int kBuckets = 256;    // buckets of the grid-wide passes (one per thread)
 
 typedef unsigned __int128 u128;
 
@@ -163,6 +165,7 @@ __device__ void radix_select(const Source &src, uint32_t n, uint32_t want, uint3
     const uint64_t key = sh.ckey[c];
     const uint32_t idx = sh.cidx[c];
     uint32_t better = 0;   // candidates that rank strictly before this one
+#pragma unroll 8
     for (uint32_t o = 0; o < m; ++o) {
       const uint64_t ok = sh.ckey[o];
       better += (ok > key || (ok == key && sh.cidx[o] < idx)) ? 1u : 0u;
@@ -180,36 +183,29 @@ __global__ __launch_bounds__(1024) void select_small_kernel(const double *__rest
 }
 
 // Control block shared by the two grid-wide passes (lives in the workspace;
-// zeroed, together with the bucket counts, before pass 1 starts).
+// written by workgroup 0 of pass 1).
 struct SelectCtrl {
-  uint32_t ticket1, ticket2, n_cand, bucket;
-  uint32_t above, shift, pad0, pad1;
+  uint32_t ticket, n_cand, shift, pad;
   uint64_t lo, hi;
 };
 
-__global__ void select_zero_kernel(uint32_t *p, int words) {
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < words; i += gridDim.x * blockDim.x) p[i] = 0u;
-}
-
 __device__ __forceinline__ uint32_t bucket_of(uint64_t key, uint64_t lo, uint64_t hi, uint32_t shift) {
   if (key < lo) return 0u;
-  if (key > hi) return (uint32_t)kBins - 1u;
+  if (key > hi) return (uint32_t)kBuckets - 1u;
   return 1u + (uint32_t)((key - lo) >> shift);
 }
 
-__global__ __launch_bounds__(kGridThreads) void select_hist_kernel(
+__global__ __launch_bounds__(kGridThreads) void select_count_kernel(
     const double *__restrict__ scores, uint32_t nblocks, uint32_t n_keep, uint32_t per_wg,
-    uint32_t *__restrict__ ghist, SelectCtrl *__restrict__ ctrl) {
-  __shared__ uint32_t hist[kBins];
+    uint32_t *__restrict__ counts, SelectCtrl *__restrict__ ctrl) {
+  __shared__ uint32_t hist[kBuckets];
   __shared__ uint64_t sample[kSample];
   __shared__ uint64_t bracket[2];
-  __shared__ uint32_t wave_tot[16];
-  __shared__ uint32_t is_last;
   const int t = threadIdx.x;
 
   // the same sample in every workgroup: kSample evenly spaced keys
   sample[t] = score_key(scores[(uint64_t)t * nblocks / kSample]);
-  for (int b = t; b < kBins; b += kGridThreads) hist[b] = 0;
+  hist[t] = 0;
   if (t < 2) bracket[t] = t == 0 ? 0ull : ~0ull;
   __syncthreads();
   {
@@ -217,6 +213,7 @@ __global__ __launch_bounds__(kGridThreads) void select_hist_kernel(
     // statistics around the threshold's expected position
     const uint64_t mine = sample[t];
     int rank = 0;
+#pragma unroll 16
     for (int o = 0; o < kSample; ++o) {
       const uint64_t k = sample[o];
       rank += (k < mine || (k == mine && o < t)) ? 1 : 0;
@@ -230,54 +227,49 @@ __global__ __launch_bounds__(kGridThreads) void select_hist_kernel(
   __syncthreads();
   const uint64_t lo = bracket[0], hi = bracket[1];
   const uint64_t range = hi - lo;
-  uint32_t shift = 0;
-  while (shift < 64 && (range >> shift) > (uint64_t)(kBins - 3)) ++shift;
+  // smallest shift with (range >> shift) <= kBuckets - 3
+  uint32_t shift = range == 0 ? 0u : (uint32_t)(64 - __clzll((long long)range));   // bit length of range
+  shift = shift > 8 ? shift - 8 : 0u;
+  if ((range >> shift) > (uint64_t)(kBuckets - 3)) ++shift;
+  if (blockIdx.x == 0 && t == 0) {
+    ctrl->ticket = 0;
+    ctrl->n_cand = 0;
+    ctrl->shift = shift;
+    ctrl->lo = lo;
+    ctrl->hi = hi;
+  }
 
   const uint32_t e0 = blockIdx.x * per_wg;
   const uint32_t e1 = (e0 + per_wg) < nblocks ? (e0 + per_wg) : nblocks;
   for (uint32_t e = e0 + t; e < e1; e += kGridThreads)
     atomicAdd(&hist[bucket_of(score_key(scores[e]), lo, hi, shift)], 1u);
   __syncthreads();
-  for (int b = t; b < kBins; b += kGridThreads)
-    if (hist[b]) atomicAdd(&ghist[b], hist[b]);
-  __threadfence();
-  __syncthreads();
-  if (t == 0) is_last = (atomicAdd(&ctrl->ticket1, 1u) == gridDim.x - 1) ? 1u : 0u;
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-
-  // last workgroup: the bucket that holds the n_keep-th largest key
-  constexpr int kPerThread = kBins / kGridThreads;
-  uint32_t h[kPerThread], own = 0;
-#pragma unroll
-  for (int u = 0; u < kPerThread; ++u) {
-    h[u] = __hip_atomic_load(&ghist[kBins - 1 - (kPerThread * t + u)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    own += h[u];
-  }
-  uint32_t above = block_exclusive_scan<kGridThreads>(own, wave_tot);
-#pragma unroll
-  for (int u = 0; u < kPerThread; ++u) {
-    if (above < n_keep && n_keep <= above + h[u]) {
-      ctrl->bucket = (uint32_t)(kBins - 1 - (kPerThread * t + u));
-      ctrl->above = above;
-      ctrl->shift = shift;
-      ctrl->lo = lo;
-      ctrl->hi = hi;
-    }
-    above += h[u];
-  }
+  counts[blockIdx.x * kBuckets + t] = hist[t];
 }
 
 __global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
     const double *__restrict__ scores, uint32_t nblocks, uint32_t n_keep, uint32_t per_wg,
-    SelectCtrl *__restrict__ ctrl, uint64_t *__restrict__ cand_key, uint32_t *__restrict__ cand_idx,
-    uint8_t *__restrict__ mask) {
+    const uint32_t *__restrict__ counts, SelectCtrl *__restrict__ ctrl,
+    uint64_t *__restrict__ cand_key, uint32_t *__restrict__ cand_idx, uint8_t *__restrict__ mask) {
   __shared__ SelectShared sh;
   __shared__ uint32_t is_last;
   const int t = threadIdx.x;
-  const uint32_t bucket = ctrl->bucket, shift = ctrl->shift;
+  const uint32_t shift = ctrl->shift;
   const uint64_t lo = ctrl->lo, hi = ctrl->hi;
+
+  // the bucket that holds the n_keep-th largest key (same answer in every workgroup):
+  // thread t owns bucket kBuckets-1-t, the scan runs from the top
+  uint32_t own = 0;
+#pragma unroll 8
+  for (uint32_t w = 0; w < gridDim.x; ++w) own += counts[w * kBuckets + (kBuckets - 1 - t)];
+  const uint32_t above_me = block_exclusive_scan<kGridThreads>(own, sh.wave_tot);
+  if (above_me < n_keep && n_keep <= above_me + own) {
+    sh.digit = (uint32_t)(kBuckets - 1 - t);
+    sh.above = above_me;
+  }
+  __syncthreads();
+  const uint32_t bucket = sh.digit, above = sh.above;
+  __syncthreads();
 
   const uint32_t e0 = blockIdx.x * per_wg;
   const uint32_t e1 = (e0 + per_wg) < nblocks ? (e0 + per_wg) : nblocks;
@@ -294,16 +286,15 @@ __global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
   }
   __threadfence();
   __syncthreads();
-  if (t == 0) is_last = (atomicAdd(&ctrl->ticket2, 1u) == gridDim.x - 1) ? 1u : 0u;
+  if (t == 0) is_last = (atomicAdd(&ctrl->ticket, 1u) == gridDim.x - 1) ? 1u : 0u;
   __syncthreads();
   if (!is_last) return;
   __threadfence();
 
   // last workgroup: exact ranking of the candidates
   const uint32_t n = __hip_atomic_load(&ctrl->n_cand, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  const uint32_t want = n_keep - ctrl->above;
   Candidates src{cand_key, cand_idx};
-  radix_select<kGridThreads>(src, n, want, nblocks, mask, sh);
+  radix_select<kGridThreads>(src, n, n_keep - above, nblocks, mask, sh);
 }
 
 __global__ void fill_u8_kernel(uint8_t *p, int64_t n, uint8_t v) {
@@ -314,14 +305,16 @@ __global__ void fill_u8_kernel(uint8_t *p, int64_t n, uint8_t v) {
 
 constexpr int64_t kSmallLimit = 8192;      // one workgroup up to here
 
+constexpr int kMaxGridWgs = 256;
+
 struct SelectPlan {
-  size_t hist_off, ctrl_off, key_off, idx_off, total;
+  size_t counts_off, ctrl_off, key_off, idx_off, total;
 };
 
 SelectPlan select_plan(int64_t nblocks) {
   SelectPlan p;
-  p.hist_off = 0;
-  p.ctrl_off = align_up(kBins * sizeof(uint32_t), 256);
+  p.counts_off = 0;
+  p.ctrl_off = align_up((size_t)kMaxGridWgs * kBuckets * sizeof(uint32_t), 256);
   p.key_off = p.ctrl_off + align_up(sizeof(SelectCtrl), 256);
   p.idx_off = p.key_off + align_up((size_t)nblocks * sizeof(uint64_t), 256);
   p.total = p.idx_off + align_up((size_t)nblocks * sizeof(uint32_t), 256);
@@ -350,24 +343,20 @@ int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t
   }
   const SelectPlan p = select_plan(nblocks);
   char *base = static_cast<char *>(ws);
-  uint32_t *ghist = reinterpret_cast<uint32_t *>(base + p.hist_off);
+  uint32_t *counts = reinterpret_cast<uint32_t *>(base + p.counts_off);
   SelectCtrl *ctrl = reinterpret_cast<SelectCtrl *>(base + p.ctrl_off);
   uint64_t *cand_key = reinterpret_cast<uint64_t *>(base + p.key_off);
   uint32_t *cand_idx = reinterpret_cast<uint32_t *>(base + p.idx_off);
-  // bucket counts and control block are contiguous: one fill
-  const int zero_words = (int)((p.key_off - p.hist_off) / 4);
-  hipLaunchKernelGGL(select_zero_kernel, dim3(8), dim3(256), 0, s, ghist, zero_words);
+  int64_t wgs = ceil_div(nblocks, 1024);
+  if (wgs > kMaxGridWgs) wgs = kMaxGridWgs;
+  const uint32_t per_wg = (uint32_t)ceil_div(nblocks, wgs);
+  hipLaunchKernelGGL(select_count_kernel, dim3((unsigned)wgs), dim3(kGridThreads), 0, s, scores,
+                     (uint32_t)nblocks, (uint32_t)n_keep, per_wg, counts, ctrl);
   int rc = check_launch();
   if (rc != BSR_OK) return rc;
-  int64_t wgs = ceil_div(nblocks, 2048);
-  if (wgs > 256) wgs = 256;
-  const uint32_t per_wg = (uint32_t)ceil_div(nblocks, wgs);
-  hipLaunchKernelGGL(select_hist_kernel, dim3((unsigned)wgs), dim3(kGridThreads), 0, s, scores,
-                     (uint32_t)nblocks, (uint32_t)n_keep, per_wg, ghist, ctrl);
-  rc = check_launch();
-  if (rc != BSR_OK) return rc;
   hipLaunchKernelGGL(select_classify_kernel, dim3((unsigned)wgs), dim3(kGridThreads), 0, s, scores,
-                     (uint32_t)nblocks, (uint32_t)n_keep, per_wg, ctrl, cand_key, cand_idx, keep_mask);
+                     (uint32_t)nblocks, (uint32_t)n_keep, per_wg, counts, ctrl, cand_key, cand_idx,
+                     keep_mask);
   return check_launch();
 }
 
