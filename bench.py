@@ -42,6 +42,8 @@ def parse():
     p.add_argument("--batch", type=int, default=128)
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--phase-reps", type=int, default=5)
+    p.add_argument("--streams", type=int, default=4,
+                   help="HIP streams (default priority) the independent tensors of a step are spread over")
     return p.parse_args()
 
 
@@ -121,10 +123,30 @@ def main():
 
     phases = [("score_select", score_select), ("compress", compress), ("decompress", decompress), ("dw", dw)]
 
+    # The tensors of a step are independent: spread them over a few streams so that the
+    # short dependent kernels of one tensor overlap with the others'.  Stream i waits for
+    # the main stream at the start of a step and the main stream waits for every stream
+    # at its end, so the step is still one unit of work on the main stream.
+    main_stream = torch.cuda.current_stream()
+    side = [torch.cuda.Stream() for _ in range(max(args.streams, 1))] if args.streams > 1 else []
+
     def step():
-        for t in tensors:
-            for _, f in phases:
-                f(t)
+        if not side:
+            for t in tensors:
+                for _, f in phases:
+                    f(t)
+            return
+        fork = torch.cuda.Event()
+        fork.record(main_stream)
+        for i, st in enumerate(side):
+            st.wait_event(fork)
+            with torch.cuda.stream(st):
+                for t in tensors[i::len(side)]:
+                    for _, f in phases:
+                        f(t)
+            done = torch.cuda.Event()
+            done.record(st)
+            main_stream.wait_event(done)
 
     for _ in range(args.warmup):
         step()
@@ -200,7 +222,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"ResMLP-S12 full activation set, batch {args.batch}, {args.layers} layers x "
                                "(xpatch 14x14, fc1 32x32, fc2 32x32), bf16, keep 0.5",
-                   "tensors_per_step": len(tensors), "keep": keep,
+                   "tensors_per_step": len(tensors), "keep": keep, "streams": max(args.streams, 1),
                    "step": "score+select -> compress -> decompress -> dW for every tensor"},
         "phases": {
             "compress_GBps": round(comp_alg_bytes / (comp_ms * 1e-3) / 1e9, 2),

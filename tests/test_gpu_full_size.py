@@ -1,0 +1,96 @@
+"""GPU parity at the full sizes of the five workloads, in the launch
+configuration the benchmark times.
+
+The forward side (scores, selection, BSR) is compared with the oracle in full:
+the oracle's scoring / selection / packing take well under a second per tensor.
+The weight gradient is compared on sampled entries that the oracle computes one
+by one (its naive triple loop over a whole 384 x 1536 gradient with 25088 rows
+would take minutes), plus two properties that hold at any size: rows of dW that
+belong to block-columns with no kept block are exactly zero, and the result is
+bitwise reproducible.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_16883_amd import binding as B
+from paper_2311_16883_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DW_TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def to_dev(a):
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def to_host(t):
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def run_case(spec, seed, samples=192):
+    print(f"[case] {spec.name} X[{spec.M}x{spec.K}] dY[{spec.M}x{spec.N}] {spec.dtype} "
+          f"block {spec.br}x{spec.bc} keep {spec.keep}", flush=True)
+    X, dY = synth.make_pair(spec, seed)
+    Xd, dYd = to_dev(X), to_dev(dY)
+    n_keep = B.bsr_keep_count(spec.nblocks, spec.keep)
+    mask, scores = B.bsr_score_select(Xd, spec.br, spec.bc, spec.keep, want_scores=True)
+    row_ptr, col_idx, values = B.bsr_compress(Xd, spec.br, spec.bc, mask, n_keep)
+    dW = B.bsr_t_dense_matmul(row_ptr, col_idx, values, spec.M, spec.K, spec.br, spec.bc, dYd)
+    dW2 = B.bsr_t_dense_matmul(row_ptr, col_idx, values, spec.M, spec.K, spec.br, spec.bc, dYd)
+    torch.cuda.synchronize()
+
+    o_scores, o_mask, o_rp, o_ci, o_val = oracle.prune(X, spec.br, spec.bc, spec.keep)
+    assert int(o_mask.sum()) == n_keep
+    g_scores = scores.cpu().numpy()
+    assert np.all(np.abs(g_scores - o_scores) <= 2.0 ** -52 * spec.br * spec.bc * np.abs(o_scores))
+    g_mask = mask.cpu().numpy()
+    if not np.array_equal(g_mask, o_mask):
+        d = np.flatnonzero(g_mask != o_mask)
+        raise AssertionError(f"selection differs at blocks {d[:6]}; oracle scores {o_scores[d[:6]]}")
+    assert np.array_equal(row_ptr.cpu().numpy(), o_rp)
+    assert np.array_equal(col_idx.cpu().numpy(), o_ci)
+    assert to_host(values).tobytes() == o_val.tobytes()
+
+    g = dW.cpu().numpy()
+    assert g.tobytes() == dW2.cpu().numpy().tobytes()                 # reproducible
+    xhat = oracle.mask_dense(X, spec.br, spec.bc, o_mask)
+    rng = np.random.default_rng(seed + 1000)
+    ks, ns = rng.integers(0, spec.K, samples), rng.integers(0, spec.N, samples)
+    ref = np.array([oracle.dw_entry(xhat, dY, int(k), int(n)) for k, n in zip(ks, ns)])
+    scale = float(np.max(np.abs(g)))                                   # max |dW|, from the full GPU result
+    assert abs(scale - float(np.max(np.abs(ref)))) <= 0.8 * scale      # same order of magnitude as the oracle's entries
+    err = float(np.max(np.abs(g[ks, ns].astype(np.float64) - ref))) / scale
+    assert err <= DW_TOL[spec.dtype], err
+    dead = np.flatnonzero(o_mask.reshape(spec.nbr, spec.nbc).sum(axis=0) == 0)
+    for j in dead:
+        assert not g[j * spec.bc:(j + 1) * spec.bc].any()
+    return err
+
+
+def test_s12_fc1_f32_keep_sweep():
+    for i, spec in enumerate(synth.s12_fc1_f32()):
+        run_case(spec, 20 + i)
+
+
+def test_s12_layer_bf16_batch128():
+    for i, spec in enumerate(synth.s12_layer(128)):
+        run_case(spec, 30 + i)
+
+
+@pytest.mark.parametrize("name", ["s24_fc1_b16_k10", "s24_fc2_b16_k50", "s24_fc1_b64_k90", "s24_fc2_b64_k25",
+                                  "s24_fc2_b32_k50"])
+def test_s24_sweep_samples(name):
+    spec = {s.name: s for s in synth.s24_sweep()}[name]
+    run_case(spec, 40, samples=128)
+
+
+@pytest.mark.parametrize("hot_first", [False, True])
+def test_b24_fc2_skewed_norms(hot_first):
+    run_case(synth.b24_fc2(hot_first=hot_first)[0], 50 + int(hot_first), samples=128)
