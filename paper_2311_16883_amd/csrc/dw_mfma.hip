@@ -33,7 +33,6 @@ typedef __attribute__((ext_vector_type(8))) short v8s;
 typedef __attribute__((ext_vector_type(8))) __bf16 v8bf;
 typedef __attribute__((ext_vector_type(16))) float v16f;
 
-constexpr int kThreads = 256;
 constexpr int kMaxRowsPerSplit = 512;   // block-rows whose tile index fits in LDS
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
@@ -54,19 +53,22 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, ui
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
 }
 
+// off = per-lane byte offset (range-checked against the descriptor), soff =
+// wave-uniform byte offset added to the address.
 template <int BYTES>
-__device__ __forceinline__ typename Chunk<BYTES>::type buffer_load(__amdgpu_buffer_rsrc_t r, uint32_t off);
-template <> __device__ __forceinline__ u32x4 buffer_load<16>(__amdgpu_buffer_rsrc_t r, uint32_t off) {
-  return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+__device__ __forceinline__ typename Chunk<BYTES>::type buffer_load(__amdgpu_buffer_rsrc_t r, uint32_t off,
+                                                                   uint32_t soff = 0);
+template <> __device__ __forceinline__ u32x4 buffer_load<16>(__amdgpu_buffer_rsrc_t r, uint32_t off, uint32_t soff) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, off, soff, 0);
 }
-template <> __device__ __forceinline__ u32x2 buffer_load<8>(__amdgpu_buffer_rsrc_t r, uint32_t off) {
-  return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+template <> __device__ __forceinline__ u32x2 buffer_load<8>(__amdgpu_buffer_rsrc_t r, uint32_t off, uint32_t soff) {
+  return __builtin_amdgcn_raw_buffer_load_b64(r, off, soff, 0);
 }
-template <> __device__ __forceinline__ uint32_t buffer_load<4>(__amdgpu_buffer_rsrc_t r, uint32_t off) {
-  return __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0);
+template <> __device__ __forceinline__ uint32_t buffer_load<4>(__amdgpu_buffer_rsrc_t r, uint32_t off, uint32_t soff) {
+  return __builtin_amdgcn_raw_buffer_load_b32(r, off, soff, 0);
 }
-template <> __device__ __forceinline__ uint16_t buffer_load<2>(__amdgpu_buffer_rsrc_t r, uint32_t off) {
-  return __builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0);
+template <> __device__ __forceinline__ uint16_t buffer_load<2>(__amdgpu_buffer_rsrc_t r, uint32_t off, uint32_t soff) {
+  return __builtin_amdgcn_raw_buffer_load_b16(r, off, soff, 0);
 }
 
 // 8 contraction elements x 16 rows/columns for this lane's 16-lane group,
@@ -104,15 +106,18 @@ __device__ __forceinline__ int lane_fragment_offset(int col0) {
 
 #ifdef BSR_DW_PROFILE
 __device__ unsigned long long g_prof[4096][8];
+__device__ unsigned long long g_trace[4][64][6];
 #define PROF_T(x) const unsigned long long x = __builtin_readcyclecounter()
 #else
 #define PROF_T(x)
 #endif
 
-constexpr int KT = 128, NT = 128;   // dW tile of one workgroup: 2 x 2 waves of 64 x 64
+constexpr int KT = 128, NT = 128;   // dW tile of one workgroup: 2 x WN waves, 64 x (128 / WN) each
 
-template <int BR, int BC, int MS, int VB>
+template <int BR, int BC, int MS, int VB, int WN>
 struct Geo {
+  static constexpr int THREADS = 128 * WN;                // 2 x WN waves
+  static constexpr int NTW = NT / (32 * WN);               // 32-column pieces of dW per wave along N
   static constexpr int R = MS / BR;                       // block-rows per stage
   static constexpr int ROWS = R * BR;                     // rows of a stage that carry data
   static constexpr bool KALIGNED = (KT % BC == 0);
@@ -122,8 +127,8 @@ struct Geo {
   static constexpr bool SKIP_ONLY = (BC % 32 == 0) && (BR % 16 == 0) && KALIGNED;
   static constexpr int VA = (BC % 8 == 0) ? 8 : ((BC % 4 == 0) ? 4 : ((BC % 2 == 0) ? 2 : 1));
   static constexpr int VPB = BR * BC / VA;                // vectors per block
-  static constexpr int NA = (R * JT * VPB + kThreads - 1) / kThreads;
-  static constexpr int NB = (ROWS * (NT / VB) + kThreads - 1) / kThreads;
+  static constexpr int NA = (R * JT * VPB + THREADS - 1) / THREADS;
+  static constexpr int NB = (ROWS * (NT / VB) + THREADS - 1) / THREADS;
   static constexpr int LDA = kLd, LDB = kLd;             // LDS rows (elements), swizzled not padded
   static constexpr int MSUB = MS / 16;
   // a wave-wide activation load (64 vectors) never straddles two blocks: the keep
@@ -135,14 +140,16 @@ struct Geo {
 };
 
 // D = stages whose global loads are in flight (register ring), D even.
-template <int BR, int BC, int MS, int VB, int D>
-__global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
+// WN = waves along N (2: 64 x 64 per wave, 4: 64 x 32 per wave and twice the waves).
+template <int BR, int BC, int MS, int VB, int D, int WN>
+__global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
     const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const uint16_t *__restrict__ values, const uint16_t *__restrict__ dY, float *__restrict__ out,
     int64_t M, int64_t K, int64_t N, int64_t lddy, int64_t ldo, int64_t split_stride, int64_t nbr,
     int64_t nbc, int64_t stages_per_split, int accumulate, int tiles_k, int tiles_n, int splits,
     int xcd_map, uint32_t values_bytes, uint32_t dy_bytes) {
-  typedef Geo<BR, BC, MS, VB> G;
+  typedef Geo<BR, BC, MS, VB, WN> G;
+  constexpr int kThreads = G::THREADS;
   typedef typename Chunk<G::VA * 2>::type AVec;
   typedef typename Chunk<VB * 2>::type BVec;
   static_assert(D % 2 == 0, "ring depth and LDS double buffer stay in phase");
@@ -165,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
 
   // two stage buffers (A tile then B tile each); before the main loop the
   // same memory holds the column indices of this split
-  __shared__ __attribute__((aligned(16))) uint32_t sStage[2 * G::STAGE_WORDS];
+  __shared__ __attribute__((aligned(16))) uint32_t sStage[2 * G::STAGE_WORDS + kThreads * 4];   // + one 16-byte dump slot per thread
   __shared__ uint32_t sMask[kMaxRowsPerSplit];
   __shared__ int32_t sBase[kMaxRowsPerSplit + 1];
   __shared__ uint32_t sAct[3][8];
@@ -174,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
   // activity bits, the skip branches) is then wave-uniform for the compiler too
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wk = wave >> 1, wn = wave & 1;
+  const int wk = wave / WN, wn = wave % WN;
   const int64_t k0 = (int64_t)tile_x * KT, n0 = (int64_t)tile_y * NT;
   const int64_t total_stages = ceil_div(nbr, G::R);
   const int64_t s_begin = (int64_t)split * stages_per_split;
@@ -255,7 +262,7 @@ __global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
     a_row[it] = used ? rbk : -1;
     a_jl[it] = jl;
     a_src[it] = (uint32_t)(off * G::VA * 2);
-    a_dst[it] = swizzled(rbk * BR + r, used ? col : 0);
+    a_dst[it] = used ? swizzled(rbk * BR + r, col) : -1;
   }
   int b_row[G::NB];            // row of the stage, or MS: vector not used
   uint32_t b_src[G::NB];       // byte offset relative to the first row of the stage (out of range if unused)
@@ -267,7 +274,19 @@ __global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
     const bool used = r < G::ROWS && n0 + c < N;
     b_row[it] = used ? r : MS;
     b_src[it] = used ? (uint32_t)(((int64_t)r * lddy + c) * 2) : kOutOfRange;
-    b_dst[it] = swizzled(r, c);
+    b_dst[it] = used ? swizzled(r, c) : -1;
+  }
+  // element offsets of the LDS stores relative to stage buffer 0 (>= kDump: the dump slot)
+  constexpr int kDump = 2 * G::STAGE_WORDS * 2;
+  int a_lds[2][G::NA], b_lds[2][G::NB];
+#pragma unroll
+  for (int buf = 0; buf < 2; ++buf) {
+#pragma unroll
+    for (int it = 0; it < G::NA; ++it)
+      a_lds[buf][it] = a_dst[it] >= 0 ? buf * G::STAGE_WORDS * 2 + a_dst[it] : kDump + t * 8;
+#pragma unroll
+    for (int it = 0; it < G::NB; ++it)
+      b_lds[buf][it] = b_dst[it] >= 0 ? buf * G::STAGE_WORDS * 2 + MS * G::LDA + b_dst[it] : kDump + t * 8;
   }
   // dY seen from the first row / column of this workgroup; every stage gets its
   // own buffer descriptor (scalar registers), so rows past the end of the
@@ -306,8 +325,8 @@ __global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
           if (rbk == x) { m = mask[x]; b = base[x]; }
         const bool kept = live && slot < G::R * G::JT && jl < jt && ((m >> jl) & 1u);
         const uint32_t pos = b + __builtin_popcount(m & ((1u << jl) - 1u));
-        const uint16_t *src = values + (int64_t)pos * (BR * BC) + off0 * G::VA;
-        ra[d][it] = buffer_load<G::VA * 2>(make_rsrc(src, kept ? 64u * G::VA * 2u : 0u), lane16);
+        const uint32_t soff = kept ? pos * (uint32_t)(BR * BC * 2) + (uint32_t)(off0 * G::VA * 2) : 0u;
+        ra[d][it] = buffer_load<G::VA * 2>(rsrc_a, kept ? lane16 : kOutOfRange, soff);
       }
     } else {
       uint32_t mask[G::R];
@@ -340,14 +359,13 @@ __global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
 
   // Ring slot d (stage index q) -> LDS stage buffer `buf`.
   auto stage_to_lds = [&](int d, int q, int buf) {
-    uint16_t *sA = reinterpret_cast<uint16_t *>(sStage + buf * G::STAGE_WORDS);
-    uint16_t *sB = sA + MS * G::LDA;
+    // unused vectors go to this thread's dump slot: no store needs a predicate
+    uint16_t *s0 = reinterpret_cast<uint16_t *>(sStage);
 #pragma unroll
     for (int it = 0; it < G::NA; ++it)
-      if (a_row[it] >= 0) *reinterpret_cast<AVec *>(&sA[a_dst[it]]) = ra[d][it];   // data, zeros if pruned
+      *reinterpret_cast<AVec *>(&s0[a_lds[buf][it]]) = ra[d][it];   // data, zeros if pruned
 #pragma unroll
-    for (int it = 0; it < G::NB; ++it)
-      if (b_row[it] < MS) *reinterpret_cast<BVec *>(&sB[b_dst[it]]) = rb[d][it];
+    for (int it = 0; it < G::NB; ++it) *reinterpret_cast<BVec *>(&s0[b_lds[buf][it]]) = rb[d][it];
     if (!G::SKIP_ONLY) {
       // which 16-row x 32-column pieces of the activation tile hold a kept block
       const int rr0 = q * G::R;
@@ -367,18 +385,23 @@ __global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
     }
   };
 
-  v16f acc[2][2];
+  v16f acc[2][G::NTW];
 #pragma unroll
   for (int u = 0; u < 2; ++u)
 #pragma unroll
-    for (int w = 0; w < 2; ++w)
+    for (int w = 0; w < G::NTW; ++w)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[u][w][r] = 0.f;
 
   const int frag_a0 = lane_fragment_offset((2 * wk) * 32), frag_a1 = lane_fragment_offset((2 * wk + 1) * 32);
-  const int frag_b0 = lane_fragment_offset((2 * wn) * 32), frag_b1 = lane_fragment_offset((2 * wn + 1) * 32);
+  int frag_b[G::NTW];
+#pragma unroll
+  for (int w = 0; w < G::NTW; ++w) frag_b[w] = lane_fragment_offset((G::NTW * wn + w) * 32);
 
   // Multiply stage q out of LDS buffer `buf`.
+#ifdef BSR_DW_PROFILE
+  unsigned long long pam_dbg = 0;
+#endif
   auto compute = [&](int q, int buf) {
     const uint16_t *sA = reinterpret_cast<const uint16_t *>(sStage + buf * G::STAGE_WORDS);
     const uint16_t *sB = sA + MS * G::LDA;
@@ -399,31 +422,44 @@ __global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
         pam |= ((act >> (2 * wk)) & 3u) << (2 * ms);
       }
     }
-    // Static code per block-row (all its 16-row steps, both 32-column pieces of
-    // this wave), entered only if the block-row keeps something in these columns.
+    // Static, fully unrolled walk over the 16-row steps of the stage.  The
+    // four fragments of step ms+1 are requested from LDS before the multiplies
+    // of step ms are issued (their latency hides behind the matrix core); only
+    // the multiplies sit under the wave-uniform skip branches.
+#ifdef BSR_DW_PROFILE
+    pam_dbg = pam;
+#endif
+    if (pam == 0) return;
+    v8bf fb[G::NTW], fa0, fa1;
 #pragma unroll
-    for (int rbk = 0; rbk < (G::SKIP_ONLY ? G::R : 1); ++rbk) {
-      constexpr int STEPS = G::SKIP_ONLY ? BR / 16 : G::MSUB;
-      const uint32_t two = (pam >> (2 * rbk * STEPS)) & 3u;
-      if (G::SKIP_ONLY && two == 0) continue;
+    for (int w = 0; w < G::NTW; ++w) fb[w] = read_fragment(sB + frag_b[w], G::LDB);
+    fa0 = read_fragment(sA + frag_a0, G::LDA);
+    fa1 = read_fragment(sA + frag_a1, G::LDA);
 #pragma unroll
-      for (int x = 0; x < STEPS; ++x) {
-        const int ms = rbk * STEPS + x;
-        const uint32_t mine = G::SKIP_ONLY ? two : (pam >> (2 * ms)) & 3u;
-        if (!G::SKIP_ONLY && mine == 0) continue;
-        const v8bf b0 = read_fragment(sB + frag_b0 + ms * 16 * G::LDB, G::LDB);
-        const v8bf b1 = read_fragment(sB + frag_b1 + ms * 16 * G::LDB, G::LDB);
-        const v8bf a0 = read_fragment(sA + frag_a0 + ms * 16 * G::LDA, G::LDA);
-        const v8bf a1 = read_fragment(sA + frag_a1 + ms * 16 * G::LDA, G::LDA);
-        if (mine & 1u) {
-          acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
-          acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
-        }
-        if (mine & 2u) {
-          acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
-          acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
-        }
+    for (int ms = 0; ms < G::MSUB; ++ms) {
+      v8bf nb[G::NTW], na0 = fa0, na1 = fa1;
+#pragma unroll
+      for (int w = 0; w < G::NTW; ++w) nb[w] = fb[w];
+      if (ms + 1 < G::MSUB) {
+#pragma unroll
+        for (int w = 0; w < G::NTW; ++w) nb[w] = read_fragment(sB + frag_b[w] + (ms + 1) * 16 * G::LDB, G::LDB);
+        na0 = read_fragment(sA + frag_a0 + (ms + 1) * 16 * G::LDA, G::LDA);
+        na1 = read_fragment(sA + frag_a1 + (ms + 1) * 16 * G::LDA, G::LDA);
       }
+      const uint32_t mine = (pam >> (2 * ms)) & 3u;
+      if (mine & 1u) {
+#pragma unroll
+        for (int w = 0; w < G::NTW; ++w)
+          acc[0][w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb[w], acc[0][w], 0, 0, 0);
+      }
+      if (mine & 2u) {
+#pragma unroll
+        for (int w = 0; w < G::NTW; ++w)
+          acc[1][w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb[w], acc[1][w], 0, 0, 0);
+      }
+#pragma unroll
+      for (int w = 0; w < G::NTW; ++w) fb[w] = nb[w];
+      fa0 = na0; fa1 = na1;
     }
   };
 
@@ -457,6 +493,11 @@ __global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
       PROF_T(te);
 #ifdef BSR_DW_PROFILE
       p_store += tb - ta; p_pref += tc - tb; p_comp += td - tc; p_bar += te - td;
+      if (lane == 0 && wave == 0 && q < 64 && (blockIdx.x == 0 || blockIdx.x == 100 || blockIdx.x == 256 || blockIdx.x == 300)) {
+        const int wsel = blockIdx.x == 0 ? 0 : blockIdx.x == 100 ? 1 : blockIdx.x == 256 ? 2 : 3;
+        unsigned long long *g = g_trace[wsel][q];
+        g[0] = ta - p_t0; g[1] = tb - p_t0; g[2] = tc - p_t0; g[3] = td - p_t0; g[4] = te - p_t0; g[5] = pam_dbg;
+      }
 #endif
     }
   }
@@ -468,11 +509,11 @@ __global__ __launch_bounds__(kThreads) void dw_mfma_kernel(
 #pragma unroll
   for (int u = 0; u < 2; ++u)
 #pragma unroll
-    for (int w = 0; w < 2; ++w)
+    for (int w = 0; w < G::NTW; ++w)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int64_t k = k0 + (2 * wk + u) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const int64_t n = n0 + (2 * wn + w) * 32 + (lane & 31);
+        const int64_t n = n0 + (G::NTW * wn + w) * 32 + (lane & 31);
         if (k < K && n < N) {
           float *dst = o + k * ldo + n;
           *dst = accumulate ? *dst + acc[u][w][r] : acc[u][w][r];
@@ -512,7 +553,7 @@ Plan make_plan(int64_t M, int64_t K, int64_t N) {
   return p;
 }
 
-template <int BR, int BC, int MS, int D>
+template <int BR, int BC, int MS, int D, int WN>
 int run(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int64_t M, int64_t K,
         const void *dY, int64_t N, int64_t lddy, float *dW, int64_t lddw, int accumulate, void *ws,
         size_t ws_bytes, hipStream_t s) {
@@ -535,7 +576,7 @@ int run(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int6
   int vb = 8;
   while (vb > 1 && (N % vb != 0 || lddy % vb != 0 || (uintptr_t)dY % (2 * vb) != 0)) vb >>= 1;
 #define BSR_DW_LAUNCH(VB)                                                                         \
-  hipLaunchKernelGGL((dw_mfma_kernel<BR, BC, MS, VB, D>), grid, dim3(kThreads), 0, s,              \
+  hipLaunchKernelGGL((dw_mfma_kernel<BR, BC, MS, VB, D, WN>), grid, dim3(128 * WN), 0, s,          \
                      row_ptr, col_idx, v, y, out, M, K, N, lddy, ldo, stride, nbr, nbc,            \
                      p.stages_per_split, acc_direct, tiles_k, tiles_n, p.splits, xcd_map,           \
                      values_bytes, dy_bytes)
@@ -597,18 +638,22 @@ int launch_dw_mfma(const int32_t *row_ptr, const int32_t *col_idx, const void *v
                    int64_t lddw, int accumulate, void *ws, size_t ws_bytes, hipStream_t s) {
   if (K == 0 || N == 0) return BSR_OK;
 #define BSR_ARGS row_ptr, col_idx, values, M, K, dY, N, lddy, dW, lddw, accumulate, ws, ws_bytes, s
+  static const int wn = getenv("BSR_DW_WN") ? atoi(getenv("BSR_DW_WN")) : 4;
   if (br == 32 && bc == 32) {
-    if (knob_ms32() == 32) return knob_depth() >= 4 ? run<32, 32, 32, 4>(BSR_ARGS) : run<32, 32, 32, 2>(BSR_ARGS);
-    return knob_depth() >= 4 ? run<32, 32, 64, 4>(BSR_ARGS) : run<32, 32, 64, 2>(BSR_ARGS);
+    if (wn == 4) return knob_ms32() == 32 ? run<32, 32, 32, 2, 4>(BSR_ARGS) : run<32, 32, 64, 2, 4>(BSR_ARGS);
+    return knob_ms32() == 32 ? run<32, 32, 32, 2, 2>(BSR_ARGS) : run<32, 32, 64, 2, 2>(BSR_ARGS);
   }
-  if (br == 64 && bc == 64) return run<64, 64, 64, 2>(BSR_ARGS);
-  if (br == 16 && bc == 16) return run<16, 16, 32, 4>(BSR_ARGS);
-  if (br == 14 && bc == 14) return run<14, 14, 32, 2>(BSR_ARGS);
+  if (br == 64 && bc == 64) return wn == 4 ? run<64, 64, 64, 2, 4>(BSR_ARGS) : run<64, 64, 64, 2, 2>(BSR_ARGS);
+  if (br == 16 && bc == 16) return run<16, 16, 32, 4, 2>(BSR_ARGS);
+  if (br == 14 && bc == 14) return wn == 4 ? run<14, 14, 32, 2, 4>(BSR_ARGS) : run<14, 14, 32, 2, 2>(BSR_ARGS);
 #undef BSR_ARGS
   return BSR_ERR_SHAPE;
 }
 
 #ifdef BSR_DW_PROFILE
+extern "C" int bsr_debug_read_trace(unsigned long long *host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * n, 0, hipMemcpyDeviceToHost);
+}
 extern "C" int bsr_debug_read_prof(unsigned long long *host, int n) {
   return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_prof), sizeof(unsigned long long) * n, 0, hipMemcpyDeviceToHost);
 }
