@@ -44,6 +44,8 @@ def parse():
     p.add_argument("--phase-reps", type=int, default=5)
     p.add_argument("--streams", type=int, default=4,
                    help="HIP streams (default priority) the independent tensors of a step are spread over")
+    p.add_argument("--calibrate-copy", action="store_true",
+                   help="also run a plain 256 MiB device copy (known traffic) for scaling rocprofv3 byte counters")
     return p.parse_args()
 
 
@@ -148,6 +150,14 @@ def main():
             done.record(st)
             main_stream.wait_event(done)
 
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -211,6 +221,16 @@ def main():
     bsr_bytes = sum(B.bsr_storage_bytes(t["spec"].M, t["spec"].K, t["spec"].br, t["spec"].bc, t["n_keep"],
                                         B.dtype_code(t["X"].dtype)) for t in tensors)
 
+    # HBM bytes per dW launch as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
+    # plain copy of known size); taken from the committed summary, not measured in this run
+    traffic = None
+    tfile = ROOT / "profiles" / "dw_hbm_traffic.json"
+    if tfile.exists():
+        try:
+            traffic = json.loads(tfile.read_text()).get("bytes_per_launch")
+        except Exception:
+            traffic = None
+
     achieved_tflops = flops_per_launch / (dw_launch_ms * 1e-3) / 1e12
     result = {
         "metric": "compress GB/s + block-sparse dW TFLOP/s (nonzero blocks) at ResMLP-S12, 50% keep",
@@ -233,7 +253,7 @@ def main():
         },
         "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 5),
-                     "traffic": None, "kernel": "bsr_t_dense_matmul (dW)",
+                     "traffic": traffic, "kernel": "bsr_t_dense_matmul (dW)",
                      "flops_per_launch": flops_per_launch, "ms_per_launch": round(dw_launch_ms, 5)},
         "roofline_compress": {"bound": "hbm", "achieved": round(comp_alg_bytes / (comp_ms * 1e-3) / 1e9, 2),
                               "peak": HBM_PEAK_GBPS, "unit": "GB/s",

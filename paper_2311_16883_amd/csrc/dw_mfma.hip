@@ -154,20 +154,25 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
   typedef typename Chunk<VB * 2>::type BVec;
   static_assert(D % 2 == 0, "ring depth and LDS double buffer stay in phase");
 
-  // Workgroup ids are dealt to the 8 XCDs round-robin.  All tiles of one split
-  // of the contraction read the same activation rows and dY rows, so a split
-  // can be pinned to one XCD and its tiles share that XCD's L2.
+  // Workgroup ids are dealt to the 8 XCDs round-robin (id % 8).  All tiles of one
+  // split of the contraction read the same activation rows and dY rows, so the
+  // (split, tile) work items are numbered split-major and XCD x takes the x-th
+  // contiguous eighth of them: each XCD then works on (parts of) at most a few
+  // neighbouring splits, whose operands it fetches into its L2 once, and every
+  // XCD gets the same number of workgroups.  Only performance depends on the
+  // dispatch order assumption, never correctness.
   const int tiles = tiles_k * tiles_n;
-  int split, tile;
+  const int items = tiles * splits;
+  int item;
   if (xcd_map) {
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    split = xcd + 8 * (slot / tiles);
-    tile = slot % tiles;
+    const int per_xcd = (items + 7) / 8;
+    item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd) return;
   } else {
-    split = blockIdx.x / tiles;
-    tile = blockIdx.x % tiles;
+    item = blockIdx.x;
   }
-  if (split >= splits) return;
+  if (item >= items) return;
+  const int split = item / tiles, tile = item % tiles;
   const int tile_x = tile % tiles_k, tile_y = tile / tiles_k;
 
   // two stage buffers (A tile then B tile each); before the main loop the
@@ -566,8 +571,9 @@ int run(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int6
   const int64_t stride = p.splits > 1 ? K * N : 0;
   const int acc_direct = p.splits > 1 ? 0 : accumulate;
   const int tiles_k = (int)ceil_div(K, 128), tiles_n = (int)ceil_div(N, 128);
-  static const int xcd_map = getenv("BSR_DW_XCD_MAP") ? atoi(getenv("BSR_DW_XCD_MAP")) : 0;
-  dim3 grid((unsigned)((xcd_map ? 8 * ceil_div(p.splits, 8) : p.splits) * tiles_k * tiles_n));
+  static const int xcd_map = getenv("BSR_DW_XCD_MAP") ? atoi(getenv("BSR_DW_XCD_MAP")) : 1;
+  const int64_t n_items = (int64_t)p.splits * tiles_k * tiles_n;
+  dim3 grid((unsigned)(xcd_map ? 8 * ceil_div(n_items, 8) : n_items));
   const uint16_t *v = static_cast<const uint16_t *>(values);
   const uint16_t *y = static_cast<const uint16_t *>(dY);
   // 32-bit buffer offsets: both operands must stay below 4 GiB (checked by dw_mfma_supported)
