@@ -33,7 +33,7 @@ typedef __attribute__((ext_vector_type(8))) short v8s;
 typedef __attribute__((ext_vector_type(8))) __bf16 v8bf;
 typedef __attribute__((ext_vector_type(16))) float v16f;
 
-constexpr int kMaxRowsPerSplit = 512;   // block-rows whose tile index fits in LDS
+constexpr int kMaxRowsPerSplit = 256;   // block-rows of one split: its block table must fit in LDS
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
@@ -45,6 +45,9 @@ template <> struct Chunk<4> { typedef uint32_t type; };
 template <> struct Chunk<2> { typedef uint16_t type; };
 
 constexpr uint32_t kOutOfRange = 0xFFFFFFFFu;   // buffer offset that reads as zero, touches no memory
+// Table entry of a pruned block: still out of range after a byte offset inside a
+// block is added (the activation values must stay below 2 GiB).
+constexpr uint32_t kDead = 0x80000000u;
 
 // Untyped buffer resource over [base, base + bytes): loads at offsets beyond
 // `bytes` return zero without a memory access, which predicates a load without
@@ -104,13 +107,6 @@ __device__ __forceinline__ int lane_fragment_offset(int col0) {
   return swizzled(8 * (g >> 1) + (L >> 2), col0 + 16 * (g & 1) + 4 * (L & 3));
 }
 
-#ifdef BSR_DW_PROFILE
-__device__ unsigned long long g_prof[4096][8];
-__device__ unsigned long long g_trace[4][64][6];
-#define PROF_T(x) const unsigned long long x = __builtin_readcyclecounter()
-#else
-#define PROF_T(x)
-#endif
 
 constexpr int KT = 128, NT = 128;   // dW tile of one workgroup: 2 x WN waves, 64 x (128 / WN) each
 
@@ -175,12 +171,20 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
   const int split = item / tiles, tile = item % tiles;
   const int tile_x = tile % tiles_k, tile_y = tile / tiles_k;
 
-  // two stage buffers (A tile then B tile each); before the main loop the
-  // same memory holds the column indices of this split
-  __shared__ __attribute__((aligned(16))) uint32_t sStage[2 * G::STAGE_WORDS + kThreads * 4];   // + one 16-byte dump slot per thread
-  __shared__ uint32_t sMask[kMaxRowsPerSplit];
-  __shared__ int32_t sBase[kMaxRowsPerSplit + 1];
-  __shared__ uint32_t sAct[3][8];
+  // LDS: two stage buffers (A tile then B tile each) that also stage the column
+  // indices of the split before the main loop, a 1 KB dump slot (16 bytes per
+  // lane) for stores of unused vectors, the block table and the activity bits.
+  constexpr int kTail = (D + 2) * G::R;           // block-rows the loader may run past the split
+  __shared__ __attribute__((aligned(16))) uint32_t sStage[2 * G::STAGE_WORDS + 256];
+  // sTab[rr * JT + jl]: byte offset in `values` of the block in block-row rr of the
+  // split and block-column jl of the tile, kDead if pruned / outside
+  __shared__ uint32_t sTab[(kMaxRowsPerSplit + kTail) * G::JT];
+  // first the raw column masks per block-row, then per stage the activity bits of
+  // its 16-row steps (two per step, for the waves with wk = 0 in the low half-word)
+  __shared__ uint32_t sPam[kMaxRowsPerSplit + 64];
+  int32_t *const sPtr = reinterpret_cast<int32_t *>(sTab);   // row_ptr of the split while the table is built
+  static_assert((kMaxRowsPerSplit + kTail) * G::JT > kMaxRowsPerSplit, "row_ptr fits in the table's memory");
+  static_assert(kMaxRowsPerSplit <= kThreads, "one block-row per thread in the prologue");
 
   // the wave index lives in a scalar register: everything derived from it (the
   // activity bits, the skip branches) is then wave-uniform for the compiler too
@@ -192,7 +196,7 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
   const int64_t s_begin = (int64_t)split * stages_per_split;
   int64_t s_end = s_begin + stages_per_split;
   if (s_end > total_stages) s_end = total_stages;
-  const int nstages = (int)(s_end - s_begin);
+  const int nstages = s_end > s_begin ? (int)(s_end - s_begin) : 0;
   const int64_t i_begin = s_begin * G::R;
   const int nrows = nstages * G::R;                       // block-rows of this split (may run past nbr)
   const int64_t jfirst = k0 / BC;
@@ -200,62 +204,87 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
   if (jlast > nbc - 1) jlast = nbc - 1;
   const int jt = (int)(jlast - jfirst + 1);
 
-  // ---- tile index: per block-row, which block-columns of the tile are kept ----
-  // sBase[rr] first holds row_ptr of block-row i_begin + rr (clamped at nbr).
+  // ---- block table: which blocks of the tile's block-columns each block-row keeps ----
   for (int rr = t; rr <= nrows; rr += kThreads) {
     const int64_t i = i_begin + rr;
-    sBase[rr] = row_ptr[i < nbr ? i : nbr];
+    sPtr[rr] = row_ptr[i < nbr ? i : nbr];
   }
-  if (t < 24) (&sAct[0][0])[t] = 0u;
   __syncthreads();
-  const int32_t pos0 = sBase[0];
-  const int ncols = sBase[nrows] - pos0;                   // column indices of the whole split
+  const int32_t pos0 = sPtr[0];
+  const int ncols = sPtr[nrows] - pos0;                    // column indices of the whole split
   const bool cols_in_lds = ncols <= 2 * G::STAGE_WORDS;
   if (cols_in_lds)
     for (int e = t; e < ncols; e += kThreads) sStage[e] = (uint32_t)col_idx[pos0 + e];
   __syncthreads();
-  constexpr int kRowsPerThread = (kMaxRowsPerSplit + kThreads - 1) / kThreads;
-  uint32_t my_mask[kRowsPerThread];
-  int32_t my_base[kRowsPerThread];
-#pragma unroll
-  for (int q = 0; q < kRowsPerThread; ++q) {
-    const int rr = t + q * kThreads;
-    uint32_t mask = 0;
-    int32_t base = 0;
-    if (rr < nrows) {
-      const int32_t p0 = sBase[rr], p1 = sBase[rr + 1];
-      bool first = true;
-      for (int32_t p = p0; p < p1; ++p) {
-        const int64_t j = cols_in_lds ? (int64_t)sStage[p - pos0] : (int64_t)col_idx[p];
-        if (j >= jfirst && j <= jlast) {
-          if (first) { base = p; first = false; }
-          mask |= 1u << (int)(j - jfirst);
-        }
+  uint32_t my_mask = 0;                                     // block-row t: kept block-columns of the tile
+  int32_t my_base = 0;                                      // position of the first of them in col_idx / values
+  if (t < nrows) {
+    const int32_t p0 = sPtr[t], p1 = sPtr[t + 1];
+    bool first = true;
+    for (int32_t p = p0; p < p1; ++p) {
+      const int64_t j = cols_in_lds ? (int64_t)sStage[p - pos0] : (int64_t)col_idx[p];
+      if (j >= jfirst && j <= jlast) {
+        if (first) { my_base = p; first = false; }
+        my_mask |= 1u << (int)(j - jfirst);
       }
     }
-    my_mask[q] = mask;
-    my_base[q] = base;
   }
   __syncthreads();
+  if (t < nrows) {
 #pragma unroll
-  for (int q = 0; q < kRowsPerThread; ++q) {
-    const int rr = t + q * kThreads;
-    if (rr < nrows) {
-      sMask[rr] = my_mask[q];
-      sBase[rr] = my_base[q];
-    }
+    for (int jl = 0; jl < G::JT; ++jl)
+      sTab[t * G::JT + jl] = ((my_mask >> jl) & 1u)
+                                 ? (uint32_t)(my_base + __popc(my_mask & ((1u << jl) - 1u))) * (uint32_t)(BR * BC * 2)
+                                 : kDead;
   }
+  for (int e = t; e < kTail * G::JT; e += kThreads) sTab[nrows * G::JT + e] = kDead;
+  if (t < kMaxRowsPerSplit) sPam[t] = my_mask;
   // rows / columns of the stage buffers that no stage ever writes must read as zero
   if (!G::SKIP_ONLY || G::ROWS < MS)
     for (int e = t; e < 2 * G::STAGE_WORDS; e += kThreads) sStage[e] = 0u;
   __syncthreads();
+  {
+    // Block-columns of the tile that overlap the two 32-column pieces of the
+    // activation tile owned by the waves with wk = 0 / 1: a 16-row step of a piece
+    // carries data iff a block-row it overlaps keeps one of these columns.
+    uint32_t colmask[2][2] = {{0u, 0u}, {0u, 0u}};
+#pragma unroll
+    for (int jl = 0; jl < G::JT; ++jl) {
+      const int c0 = (int)((jfirst + jl) * BC - k0), c1 = c0 + BC - 1;
+#pragma unroll
+      for (int x = 0; x < 4; ++x)
+        if (jl < jt && c0 <= x * 32 + 31 && c1 >= x * 32) colmask[x >> 1][x & 1] |= 1u << jl;
+    }
+    uint32_t pam = 0;
+    if (t < nstages) {
+#pragma unroll
+      for (int rbk = 0; rbk < G::R; ++rbk) {
+        const uint32_t m = sPam[t * G::R + rbk];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          if (m & colmask[x >> 1][x & 1]) {
+#pragma unroll
+            for (int ms = (rbk * BR) / 16; ms <= (rbk * BR + BR - 1) / 16; ++ms)
+              pam |= 1u << (16 * (x >> 1) + 2 * ms + (x & 1));
+          }
+        }
+      }
+    }
+    __syncthreads();
+    if (t < kMaxRowsPerSplit) sPam[t] = pam;
+    __syncthreads();
+  }
 
-  // ---- per-thread constants of the two loaders ----
-  const int wave_s = wave;
-  int a_row[G::NA];            // block-row of the stage (0..R-1), or -1: vector not used
-  int a_jl[G::NA];             // block-column inside the tile
+  // ---- per-thread constants and state of the two loaders ----
+  // Activation vector `it` of a stage belongs to block (block-row a_row of the
+  // stage, block-column a_jl of the tile); its global offset is the block's table
+  // entry plus a_src.  The table entry of the next stage to fetch is read one
+  // stage ahead (a_val); a_tab walks down the table by a_inc entries per stage.
   uint32_t a_src[G::NA];       // byte offset inside the block
-  int a_dst[G::NA];            // element offset inside the A tile
+  uint32_t a_tab[G::NA];       // index into sTab of the entry behind a_val
+  uint32_t a_inc[G::NA];       // R * JT, or 0 for a vector that is never used (it stays on a dead entry)
+  uint32_t a_val[G::NA];
+  int a_dst[G::NA];            // element offset inside the A tile, -1: not used
 #pragma unroll
   for (int it = 0; it < G::NA; ++it) {
     const int v = t + it * kThreads;
@@ -264,21 +293,24 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
     const int r = (off * G::VA) / BC, c = (off * G::VA) % BC;
     const int col = (int)((jfirst + jl) * BC - k0) + c;
     const bool used = slot < G::R * G::JT && jl < jt && col >= 0 && col + G::VA <= KT;
-    a_row[it] = used ? rbk : -1;
-    a_jl[it] = jl;
     a_src[it] = (uint32_t)(off * G::VA * 2);
+    a_tab[it] = used ? (uint32_t)(rbk * G::JT + jl) : (uint32_t)(nrows * G::JT);
+    a_inc[it] = used ? (uint32_t)(G::R * G::JT) : 0u;
+    a_val[it] = sTab[a_tab[it]];
     a_dst[it] = used ? swizzled(rbk * BR + r, col) : -1;
   }
-  int b_row[G::NB];            // row of the stage, or MS: vector not used
-  uint32_t b_src[G::NB];       // byte offset relative to the first row of the stage (out of range if unused)
+  // dY is addressed through one descriptor that covers exactly the rows of this
+  // split (from the tile's first column on): rows past the split or the matrix
+  // end read as zero by themselves; b_cur walks down by one stage per fetch.
+  uint32_t b_cur[G::NB], b_inc[G::NB];
   int b_dst[G::NB];
 #pragma unroll
   for (int it = 0; it < G::NB; ++it) {
     const int v = t + it * kThreads;
     const int r = v / (NT / VB), c = (v % (NT / VB)) * VB;
     const bool used = r < G::ROWS && n0 + c < N;
-    b_row[it] = used ? r : MS;
-    b_src[it] = used ? (uint32_t)(((int64_t)r * lddy + c) * 2) : kOutOfRange;
+    b_cur[it] = used ? (uint32_t)(((int64_t)r * lddy + c) * 2) : kOutOfRange;
+    b_inc[it] = used ? (uint32_t)((int64_t)G::ROWS * lddy * 2) : 0u;
     b_dst[it] = used ? swizzled(r, c) : -1;
   }
   // element offsets of the LDS stores relative to stage buffer 0 (>= kDump: the dump slot)
@@ -288,107 +320,41 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
   for (int buf = 0; buf < 2; ++buf) {
 #pragma unroll
     for (int it = 0; it < G::NA; ++it)
-      a_lds[buf][it] = a_dst[it] >= 0 ? buf * G::STAGE_WORDS * 2 + a_dst[it] : kDump + t * 8;
+      a_lds[buf][it] = a_dst[it] >= 0 ? buf * G::STAGE_WORDS * 2 + a_dst[it] : kDump + lane * 8;
 #pragma unroll
     for (int it = 0; it < G::NB; ++it)
-      b_lds[buf][it] = b_dst[it] >= 0 ? buf * G::STAGE_WORDS * 2 + MS * G::LDA + b_dst[it] : kDump + t * 8;
+      b_lds[buf][it] = b_dst[it] >= 0 ? buf * G::STAGE_WORDS * 2 + MS * G::LDA + b_dst[it] : kDump + lane * 8;
   }
-  // dY seen from the first row / column of this workgroup; every stage gets its
-  // own buffer descriptor (scalar registers), so rows past the end of the
-  // matrix fall out of range by themselves
-  const int64_t dy_total = M > 0 ? ((M - 1) * lddy + N) * 2 : 0;           // bytes
-  const int64_t dy_first = (i_begin * BR * lddy + n0) * 2;
-  const int64_t dy_stage = (int64_t)G::ROWS * lddy * 2;
   const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(values, values_bytes);
-  const uint32_t lane16 = (uint32_t)(lane * G::VA * 2);
+  int64_t split_rows = (i_begin + nrows) * BR;
+  if (split_rows > M) split_rows = M;
+  split_rows -= i_begin * BR;                                                // dY rows of this split
+  const int64_t dy_split = split_rows > 0 ? ((split_rows - 1) * lddy + (N - n0)) * 2 : 0;
+  const __amdgpu_buffer_rsrc_t rsrc_b =
+      make_rsrc(reinterpret_cast<const char *>(dY) + (i_begin * BR * lddy + n0) * 2, (uint32_t)dy_split);
 
   AVec ra[D][G::NA];
   BVec rb[D][G::NB];
 
-  // Global loads of stage index q (0-based inside the split) into ring slot d.
-  // Branch-free: a vector that is pruned, outside the matrix or beyond the last
-  // stage reads as zero through an out-of-range buffer offset.
-  auto prefetch = [&](int d, int q) {
-    const bool live = q < nstages;
-    const int rr0 = live ? q * G::R : 0;
-    if (G::UNIFORM_A) {
-      uint32_t mask[G::R];
-      uint32_t base[G::R];
-#pragma unroll
-      for (int rbk = 0; rbk < G::R; ++rbk) {
-        mask[rbk] = (uint32_t)__builtin_amdgcn_readfirstlane((int)sMask[rr0 + rbk]);
-        base[rbk] = (uint32_t)__builtin_amdgcn_readfirstlane(sBase[rr0 + rbk]);
-      }
-#pragma unroll
-      for (int it = 0; it < G::NA; ++it) {
-        const int v0 = wave_s * 64 + it * kThreads;                  // first vector of this wave's load
-        const int slot = v0 / G::VPB, off0 = v0 % G::VPB;
-        const int rbk = slot / G::JT, jl = slot % G::JT;
-        uint32_t m = 0, b = 0;
-#pragma unroll
-        for (int x = 0; x < G::R; ++x)
-          if (rbk == x) { m = mask[x]; b = base[x]; }
-        const bool kept = live && slot < G::R * G::JT && jl < jt && ((m >> jl) & 1u);
-        const uint32_t pos = b + __builtin_popcount(m & ((1u << jl) - 1u));
-        const uint32_t soff = kept ? pos * (uint32_t)(BR * BC * 2) + (uint32_t)(off0 * G::VA * 2) : 0u;
-        ra[d][it] = buffer_load<G::VA * 2>(rsrc_a, kept ? lane16 : kOutOfRange, soff);
-      }
-    } else {
-      uint32_t mask[G::R];
-      uint32_t base[G::R];
-#pragma unroll
-      for (int rbk = 0; rbk < G::R; ++rbk) {
-        mask[rbk] = sMask[rr0 + rbk];
-        base[rbk] = (uint32_t)sBase[rr0 + rbk];
-      }
-#pragma unroll
-      for (int it = 0; it < G::NA; ++it) {
-        uint32_t m = 0, b = 0;
-#pragma unroll
-        for (int rbk = 0; rbk < G::R; ++rbk)
-          if (a_row[it] == rbk) { m = mask[rbk]; b = base[rbk]; }
-        const bool kept = live && a_row[it] >= 0 && ((m >> a_jl[it]) & 1u);
-        const uint32_t pos = b + __popc(m & ((1u << a_jl[it]) - 1u));
-        ra[d][it] = buffer_load<G::VA * 2>(rsrc_a, kept ? pos * (uint32_t)(BR * BC * 2) + a_src[it] : kOutOfRange);
-      }
-    }
-    const int64_t first = dy_first + (int64_t)q * dy_stage;
-    int64_t left = live ? dy_total - first : 0;
-    if (left < 0) left = 0;
-    if (left > 0xFFFFFFFFll) left = 0xFFFFFFFFll;
-    const __amdgpu_buffer_rsrc_t rsrc_b =
-        make_rsrc(reinterpret_cast<const char *>(dY) + first, (uint32_t)left);
-#pragma unroll
-    for (int it = 0; it < G::NB; ++it) rb[d][it] = buffer_load<VB * 2>(rsrc_b, b_src[it]);
+  // Global load of the next stage's activation vector `it` / dY vector `it` into
+  // ring slot d.  Branch-free: a vector that is pruned, outside the matrix or
+  // beyond the split reads as zero through an out-of-range offset, so the number
+  // of loads in flight is known at compile time.  Each call moves the vector's
+  // state on by one stage.
+  auto load_a = [&](int d, int it) {
+    ra[d][it] = buffer_load<G::VA * 2>(rsrc_a, a_val[it] + a_src[it]);
+    a_tab[it] += a_inc[it];
+    a_val[it] = sTab[a_tab[it]];
   };
-
-  // Ring slot d (stage index q) -> LDS stage buffer `buf`.
-  auto stage_to_lds = [&](int d, int q, int buf) {
-    // unused vectors go to this thread's dump slot: no store needs a predicate
-    uint16_t *s0 = reinterpret_cast<uint16_t *>(sStage);
-#pragma unroll
-    for (int it = 0; it < G::NA; ++it)
-      *reinterpret_cast<AVec *>(&s0[a_lds[buf][it]]) = ra[d][it];   // data, zeros if pruned
-#pragma unroll
-    for (int it = 0; it < G::NB; ++it) *reinterpret_cast<BVec *>(&s0[b_lds[buf][it]]) = rb[d][it];
-    if (!G::SKIP_ONLY) {
-      // which 16-row x 32-column pieces of the activation tile hold a kept block
-      const int rr0 = q * G::R;
-      if (t < G::R * G::JT && q < nstages) {
-        const int rbk = t / G::JT, jl = t % G::JT;
-        if (jl < jt && ((sMask[rr0 + rbk] >> jl) & 1u)) {
-          int c0 = (int)((jfirst + jl) * BC - k0), c1 = c0 + BC - 1;
-          if (c0 < 0) c0 = 0;
-          if (c1 > KT - 1) c1 = KT - 1;
-          if (c0 <= c1) {
-            const uint32_t bits = ((2u << (c1 >> 5)) - 1u) & ~((1u << (c0 >> 5)) - 1u);
-            for (int ms = (rbk * BR) >> 4; ms <= (rbk * BR + BR - 1) >> 4; ++ms) atomicOr(&sAct[q % 3][ms], bits);
-          }
-        }
-      }
-      if (t < 8) sAct[(q + 1) % 3][t] = 0u;
-    }
+  auto load_b = [&](int d, int it) {
+    rb[d][it] = buffer_load<VB * 2>(rsrc_b, b_cur[it]);
+    b_cur[it] += b_inc[it];
   };
+  // Ring slot d -> LDS stage buffer `buf`; unused vectors go to the dump slot,
+  // so no store needs a predicate.
+  uint16_t *const s0 = reinterpret_cast<uint16_t *>(sStage);
+  auto store_a = [&](int d, int it, int buf) { *reinterpret_cast<AVec *>(&s0[a_lds[buf][it]]) = ra[d][it]; };
+  auto store_b = [&](int d, int it, int buf) { *reinterpret_cast<BVec *>(&s0[b_lds[buf][it]]) = rb[d][it]; };
 
   v16f acc[2][G::NTW];
 #pragma unroll
@@ -403,38 +369,25 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
 #pragma unroll
   for (int w = 0; w < G::NTW; ++w) frag_b[w] = lane_fragment_offset((G::NTW * wn + w) * 32);
 
-  // Multiply stage q out of LDS buffer `buf`.
-#ifdef BSR_DW_PROFILE
-  unsigned long long pam_dbg = 0;
-#endif
-  auto compute = [&](int q, int buf) {
+  // One stage of the main loop.  Stage q is multiplied out of LDS buffer `buf`
+  // in MSUB steps of 16 activation rows; spread over the same steps, the vectors
+  // of stage q+1 move from ring slot d to the other LDS buffer and the slot is
+  // refilled with stage q+1+D from global memory, one vector at a time, so the
+  // texture path, the LDS and the matrix core are busy side by side instead of
+  // in turn.  The fragments of step ms+1 are requested before the multiplies of
+  // step ms are issued; only the multiplies sit under the wave-uniform skip
+  // branches.  The loop is bound by instruction issue, so everything that can be
+  // tabulated per stage was tabulated in the prologue: the activity bits of 64
+  // stages sit in one register (lane = stage) and reach a scalar register through
+  // one v_readlane.
+  constexpr int NV = G::NA + G::NB;
+  uint32_t pam_reg = 0;
+  auto stage = [&](int d, int q, int buf) {
     const uint16_t *sA = reinterpret_cast<const uint16_t *>(sStage + buf * G::STAGE_WORDS);
     const uint16_t *sB = sA + MS * G::LDA;
-    // two activity bits (this wave's two 32-column pieces) per 16-row step
-    uint32_t pam = 0;
-    if (G::SKIP_ONLY) {
-#pragma unroll
-      for (int rbk = 0; rbk < G::R; ++rbk) {
-        const uint32_t m = (uint32_t)__builtin_amdgcn_readfirstlane((int)sMask[q * G::R + rbk]);
-        const uint32_t two = ((m >> ((2 * wk * 32) / BC)) & 1u) | (((m >> (((2 * wk + 1) * 32) / BC)) & 1u) << 1);
-#pragma unroll
-        for (int ms = rbk * (BR / 16); ms < (rbk + 1) * (BR / 16); ++ms) pam |= two << (2 * ms);
-      }
-    } else {
-#pragma unroll
-      for (int ms = 0; ms < G::MSUB; ++ms) {
-        const uint32_t act = (uint32_t)__builtin_amdgcn_readfirstlane((int)sAct[q % 3][ms]);
-        pam |= ((act >> (2 * wk)) & 3u) << (2 * ms);
-      }
-    }
-    // Static, fully unrolled walk over the 16-row steps of the stage.  The
-    // four fragments of step ms+1 are requested from LDS before the multiplies
-    // of step ms are issued (their latency hides behind the matrix core); only
-    // the multiplies sit under the wave-uniform skip branches.
-#ifdef BSR_DW_PROFILE
-    pam_dbg = pam;
-#endif
-    if (pam == 0) return;
+    if ((q & 63) == 0) pam_reg = sPam[q + lane];
+    uint32_t pam = (uint32_t)__builtin_amdgcn_readlane((int)pam_reg, q & 63) >> (16 * wk);
+    asm volatile("" : "+s"(pam));           // one scalar register, tested bit by bit below
     v8bf fb[G::NTW], fa0, fa1;
 #pragma unroll
     for (int w = 0; w < G::NTW; ++w) fb[w] = read_fragment(sB + frag_b[w], G::LDB);
@@ -451,13 +404,23 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
         na0 = read_fragment(sA + frag_a0 + (ms + 1) * 16 * G::LDA, G::LDA);
         na1 = read_fragment(sA + frag_a1 + (ms + 1) * 16 * G::LDA, G::LDA);
       }
-      const uint32_t mine = (pam >> (2 * ms)) & 3u;
-      if (mine & 1u) {
+      // this step's share of the data movement
+#pragma unroll
+      for (int v = ms * NV / G::MSUB; v < (ms + 1) * NV / G::MSUB; ++v) {
+        if (v < G::NA) {
+          store_a(d, v, buf ^ 1);
+          load_a(d, v);
+        } else {
+          store_b(d, v - G::NA, buf ^ 1);
+          load_b(d, v - G::NA);
+        }
+      }
+      if (pam & (1u << (2 * ms))) {
 #pragma unroll
         for (int w = 0; w < G::NTW; ++w)
           acc[0][w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb[w], acc[0][w], 0, 0, 0);
       }
-      if (mine & 2u) {
+      if (pam & (2u << (2 * ms))) {
 #pragma unroll
         for (int w = 0; w < G::NTW; ++w)
           acc[1][w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb[w], acc[1][w], 0, 0, 0);
@@ -470,45 +433,31 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
 
   // ---- main loop: stage q is multiplied out of LDS buffer q&1 while stage
   // q+1 moves from registers to the other buffer and stage q+1+D leaves HBM ----
-#ifdef BSR_DW_PROFILE
-  unsigned long long p_store = 0, p_pref = 0, p_comp = 0, p_bar = 0;
-  const unsigned long long p_t0 = __builtin_readcyclecounter();
-#endif
 #pragma unroll
-  for (int d = 0; d < D; ++d) prefetch(d, d);
-  stage_to_lds(0, 0, 0);
-  prefetch(0, D);
+  for (int d = 0; d < D; ++d) {
+#pragma unroll
+    for (int it = 0; it < G::NA; ++it) load_a(d, it);
+#pragma unroll
+    for (int it = 0; it < G::NB; ++it) load_b(d, it);
+  }
+#pragma unroll
+  for (int it = 0; it < G::NA; ++it) { store_a(0, it, 0); load_a(0, it); }
+#pragma unroll
+  for (int it = 0; it < G::NB; ++it) { store_b(0, it, 0); load_b(0, it); }
   __syncthreads();
-#ifdef BSR_DW_PROFILE
-  const unsigned long long p_t1 = __builtin_readcyclecounter();
-#endif
-  for (int q0 = 0; q0 < nstages; q0 += D) {
+  // Several trips round the ring per loop iteration: at the loop header the
+  // compiler's count of loads in flight falls back to a conservative value, so
+  // the first stage of an iteration waits for nearly all of them.
+  constexpr int U = 4 * D;
+  for (int q0 = 0; q0 < nstages; q0 += U) {
 #pragma unroll
-    for (int d = 0; d < D; ++d) {
+    for (int d = 0; d < U; ++d) {
       const int q = q0 + d;
       if (q >= nstages) break;
-      PROF_T(ta);
-      stage_to_lds((d + 1) % D, q + 1, (d + 1) & 1);
-      PROF_T(tb);
-      prefetch((d + 1) % D, q + 1 + D);
-      PROF_T(tc);
-      compute(q, d & 1);
-      PROF_T(td);
+      stage((d + 1) % D, q, d & 1);
       __syncthreads();
-      PROF_T(te);
-#ifdef BSR_DW_PROFILE
-      p_store += tb - ta; p_pref += tc - tb; p_comp += td - tc; p_bar += te - td;
-      if (lane == 0 && wave == 0 && q < 64 && (blockIdx.x == 0 || blockIdx.x == 100 || blockIdx.x == 256 || blockIdx.x == 300)) {
-        const int wsel = blockIdx.x == 0 ? 0 : blockIdx.x == 100 ? 1 : blockIdx.x == 256 ? 2 : 3;
-        unsigned long long *g = g_trace[wsel][q];
-        g[0] = ta - p_t0; g[1] = tb - p_t0; g[2] = tc - p_t0; g[3] = td - p_t0; g[4] = te - p_t0; g[5] = pam_dbg;
-      }
-#endif
     }
   }
-#ifdef BSR_DW_PROFILE
-  const unsigned long long p_t2 = __builtin_readcyclecounter();
-#endif
 
   float *o = out + (int64_t)split * split_stride;
 #pragma unroll
@@ -524,14 +473,6 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
           *dst = accumulate ? *dst + acc[u][w][r] : acc[u][w][r];
         }
       }
-#ifdef BSR_DW_PROFILE
-  if (lane == 0 && blockIdx.x < 1024) {
-    const unsigned long long p_t3 = __builtin_readcyclecounter();
-    unsigned long long *g = g_prof[blockIdx.x * 4 + wave];
-    g[0] = p_t1 - p_t0; g[1] = p_t2 - p_t1; g[2] = p_t3 - p_t2; g[3] = p_store; g[4] = p_pref; g[5] = p_comp;
-    g[6] = p_bar; g[7] = nstages;
-  }
-#endif
 }
 
 struct Plan {
@@ -611,10 +552,11 @@ bool dw_mfma_supported(int dtype, int br, int bc, const void *values, int64_t M,
   const bool shape = (br == 32 && bc == 32) || (br == 64 && bc == 64) || (br == 16 && bc == 16) ||
                      (br == 14 && bc == 14);
   if (!shape) return false;
-  // the kernel addresses both operands with 32-bit byte offsets
-  const int64_t limit = (int64_t(1) << 32) - 64;
-  if (ceil_div(M, br) * br * ceil_div(K, bc) * bc * 2 >= limit) return false;
-  if (M * lddy * 2 >= limit || N > lddy) return false;
+  // the kernel addresses both operands with 32-bit byte offsets; offsets of
+  // activation values at or above 2 GiB mean "pruned", and the dY offsets of the
+  // stages fetched ahead past the end of a split must not wrap
+  if (ceil_div(M, br) * br * ceil_div(K, bc) * bc * 2 >= (int64_t(1) << 31)) return false;
+  if ((M + 8 * 64) * lddy * 2 >= (int64_t(1) << 32) - 64 || N > lddy) return false;
   return true;
 }
 
@@ -656,13 +598,5 @@ int launch_dw_mfma(const int32_t *row_ptr, const int32_t *col_idx, const void *v
   return BSR_ERR_SHAPE;
 }
 
-#ifdef BSR_DW_PROFILE
-extern "C" int bsr_debug_read_trace(unsigned long long *host, int n) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * n, 0, hipMemcpyDeviceToHost);
-}
-extern "C" int bsr_debug_read_prof(unsigned long long *host, int n) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_prof), sizeof(unsigned long long) * n, 0, hipMemcpyDeviceToHost);
-}
-#endif
 
 }  // namespace bsr
