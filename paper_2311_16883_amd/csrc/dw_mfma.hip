@@ -8,19 +8,29 @@
 // row-major order and the fragments come back through ds_read_b64_tr_b16, which
 // transposes 4 x 16 sub-tiles across 16 lanes.
 //
-// Work decomposition.  A workgroup (4 waves, 2 x 2) owns a KT x NT tile of dW
-// and a contiguous range of block-rows (split of the contraction).  At start it
-// turns the BSR row segments that cross its tile into one (bit mask, first
-// position) pair per block-row in LDS; after that the main loop reads no index
-// from global memory.  The loop walks stages of MS activation rows: the kept
-// blocks of the stage are copied into a dense LDS tile (zeros where a pruned
-// block shares a 32-wide matrix-core tile with a kept one), dY rows next to it,
-// and every 16-row x 32-column piece of the activation tile that holds no kept
-// block is skipped by a wave-uniform branch -- the sparsity is exploited at
-// matrix-core granularity.  Global loads of stage s+1 are in flight (held in
-// registers) while stage s is multiplied.  With more than one split the partial
-// tiles go to the workspace and a second kernel adds them in a fixed order.
+// Work decomposition.  A workgroup owns a KT x NT tile of dW and a contiguous
+// range of block-rows (one split of the contraction).  At start it turns the BSR
+// row segments that cross its tile into a table of block offsets and per-stage
+// activity bits in LDS; after that the main loop reads no index from global
+// memory.  The loop walks stages of MS activation rows: the kept blocks of the
+// stage are copied into a dense LDS tile (zeros where a pruned block shares a
+// 32-wide matrix-core tile with a kept one), dY rows next to it, and every
+// 16-row x 32-column piece of the activation tile that holds no kept block is
+// skipped by a wave-uniform branch -- the sparsity is exploited at matrix-core
+// granularity.
+//
+// The waves of a workgroup have two roles.  Half of them (the loaders) only move
+// data: global memory -> a ring of registers several stages deep -> LDS.  The
+// other half (the multipliers) only read fragments from LDS and feed the matrix
+// cores.  A wave issues in order, so a wave that does both stalls its multiplies
+// whenever the texture path's queue is full and leaves the texture path idle
+// while it multiplies; with the roles split the loaders keep that path (64 bytes
+// per clock and compute unit, the busiest resource of this kernel) occupied all
+// the time.  One barrier per stage hands LDS buffer q&1 from the loaders to the
+// multipliers.  With more than one split the partial tiles go to the workspace
+// and a second kernel adds them in a fixed order.
 #include <cstdlib>
+#include <utility>
 
 #include "common.h"
 
@@ -43,6 +53,18 @@ template <> struct Chunk<16> { typedef u32x4 type; };
 template <> struct Chunk<8> { typedef u32x2 type; };
 template <> struct Chunk<4> { typedef uint32_t type; };
 template <> struct Chunk<2> { typedef uint16_t type; };
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose
+// index is a compile-time constant in every trip, whatever its length (register
+// arrays indexed with it never end up in scratch memory).
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F &&f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F &&>(f));
+}
 
 constexpr uint32_t kOutOfRange = 0xFFFFFFFFu;   // buffer offset that reads as zero, touches no memory
 // Table entry of a pruned block: still out of range after a byte offset inside a
@@ -112,7 +134,7 @@ constexpr int KT = 128, NT = 128;   // dW tile of one workgroup: 2 x WN waves, 6
 
 template <int BR, int BC, int MS, int VB, int WN>
 struct Geo {
-  static constexpr int THREADS = 128 * WN;                // 2 x WN waves
+  static constexpr int THREADS = 128 * WN;                // threads per role: 2 x WN waves
   static constexpr int NTW = NT / (32 * WN);               // 32-column pieces of dW per wave along N
   static constexpr int R = MS / BR;                       // block-rows per stage
   static constexpr int ROWS = R * BR;                     // rows of a stage that carry data
@@ -135,20 +157,21 @@ struct Geo {
   static_assert(JT <= 32, "tile index is a 32-bit mask");
 };
 
-// D = stages whose global loads are in flight (register ring), D even.
-// WN = waves along N (2: 64 x 64 per wave, 4: 64 x 32 per wave and twice the waves).
+// D = stages whose global loads are in flight (register ring of the loaders).
+// WN = multiplier waves along N (2: 64 x 64 per wave, 4: 64 x 32 per wave); the
+// workgroup has 2 x WN multiplier waves and as many loader waves.
 template <int BR, int BC, int MS, int VB, int D, int WN>
-__global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
+__global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(
     const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
     const uint16_t *__restrict__ values, const uint16_t *__restrict__ dY, float *__restrict__ out,
     int64_t M, int64_t K, int64_t N, int64_t lddy, int64_t ldo, int64_t split_stride, int64_t nbr,
     int64_t nbc, int64_t stages_per_split, int accumulate, int tiles_k, int tiles_n, int splits,
-    int xcd_map, uint32_t values_bytes, uint32_t dy_bytes) {
+    int xcd_map, uint32_t values_bytes) {
   typedef Geo<BR, BC, MS, VB, WN> G;
-  constexpr int kThreads = G::THREADS;
+  constexpr int kRole = G::THREADS;              // threads per role
+  constexpr int kThreads = 2 * kRole;            // workgroup
   typedef typename Chunk<G::VA * 2>::type AVec;
   typedef typename Chunk<VB * 2>::type BVec;
-  static_assert(D % 2 == 0, "ring depth and LDS double buffer stay in phase");
 
   // Workgroup ids are dealt to the 8 XCDs round-robin (id % 8).  All tiles of one
   // split of the contraction read the same activation rows and dY rows, so the
@@ -174,7 +197,7 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
   // LDS: two stage buffers (A tile then B tile each) that also stage the column
   // indices of the split before the main loop, a 1 KB dump slot (16 bytes per
   // lane) for stores of unused vectors, the block table and the activity bits.
-  constexpr int kTail = (D + 2) * G::R;           // block-rows the loader may run past the split
+  constexpr int kTail = (D + 2) * G::R;           // block-rows the loaders may run past the split
   __shared__ __attribute__((aligned(16))) uint32_t sStage[2 * G::STAGE_WORDS + 256];
   // sTab[rr * JT + jl]: byte offset in `values` of the block in block-row rr of the
   // split and block-column jl of the tile, kDead if pruned / outside
@@ -187,10 +210,13 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
   static_assert(kMaxRowsPerSplit <= kThreads, "one block-row per thread in the prologue");
 
   // the wave index lives in a scalar register: everything derived from it (the
-  // activity bits, the skip branches) is then wave-uniform for the compiler too
+  // role, the activity bits, the skip branches) is then wave-uniform for the
+  // compiler too
   const int t = threadIdx.x, lane = t & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wk = wave / WN, wn = wave % WN;
+  const int wave_wg = __builtin_amdgcn_readfirstlane(t >> 6);
+  const bool loader = wave_wg >= 2 * WN;
+  const int wave = loader ? wave_wg - 2 * WN : wave_wg;      // wave inside its role
+  const int tg = loader ? t - kRole : t;                       // thread inside its role
   const int64_t k0 = (int64_t)tile_x * KT, n0 = (int64_t)tile_y * NT;
   const int64_t total_stages = ceil_div(nbr, G::R);
   const int64_t s_begin = (int64_t)split * stages_per_split;
@@ -238,7 +264,7 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
                                  : kDead;
   }
   for (int e = t; e < kTail * G::JT; e += kThreads) sTab[nrows * G::JT + e] = kDead;
-  if (t < kMaxRowsPerSplit) sPam[t] = my_mask;
+  for (int e = t; e < kMaxRowsPerSplit + 64; e += kThreads) sPam[e] = e == t ? my_mask : 0u;
   // rows / columns of the stage buffers that no stage ever writes must read as zero
   if (!G::SKIP_ONLY || G::ROWS < MS)
     for (int e = t; e < 2 * G::STAGE_WORDS; e += kThreads) sStage[e] = 0u;
@@ -275,87 +301,124 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
     __syncthreads();
   }
 
-  // ---- per-thread constants and state of the two loaders ----
-  // Activation vector `it` of a stage belongs to block (block-row a_row of the
-  // stage, block-column a_jl of the tile); its global offset is the block's table
-  // entry plus a_src.  The table entry of the next stage to fetch is read one
-  // stage ahead (a_val); a_tab walks down the table by a_inc entries per stage.
-  uint32_t a_src[G::NA];       // byte offset inside the block
-  uint32_t a_tab[G::NA];       // index into sTab of the entry behind a_val
-  uint32_t a_inc[G::NA];       // R * JT, or 0 for a vector that is never used (it stays on a dead entry)
-  uint32_t a_val[G::NA];
-  int a_dst[G::NA];            // element offset inside the A tile, -1: not used
+  if (loader) {
+    // ================= loader waves =================
+    // Activation vector `it` of a stage belongs to block (block-row a_row of the
+    // stage, block-column a_jl of the tile); its global offset is the block's table
+    // entry plus a_src.  The table entry of the next stage to fetch is read one
+    // stage ahead (a_val); a_tab walks down the table by a_inc entries per stage.
+    uint32_t a_src[G::NA];       // byte offset inside the block
+    uint32_t a_tab[G::NA];       // index into sTab of the entry behind a_val
+    uint32_t a_inc[G::NA];       // R * JT, or 0 for a vector that is never used (it stays on a dead entry)
+    uint32_t a_val[G::NA];
+    int a_dst[G::NA];            // element offset inside the A tile, -1: not used
 #pragma unroll
-  for (int it = 0; it < G::NA; ++it) {
-    const int v = t + it * kThreads;
-    const int slot = v / G::VPB, off = v % G::VPB;
-    const int rbk = slot / G::JT, jl = slot % G::JT;
-    const int r = (off * G::VA) / BC, c = (off * G::VA) % BC;
-    const int col = (int)((jfirst + jl) * BC - k0) + c;
-    const bool used = slot < G::R * G::JT && jl < jt && col >= 0 && col + G::VA <= KT;
-    a_src[it] = (uint32_t)(off * G::VA * 2);
-    a_tab[it] = used ? (uint32_t)(rbk * G::JT + jl) : (uint32_t)(nrows * G::JT);
-    a_inc[it] = used ? (uint32_t)(G::R * G::JT) : 0u;
-    a_val[it] = sTab[a_tab[it]];
-    a_dst[it] = used ? swizzled(rbk * BR + r, col) : -1;
-  }
-  // dY is addressed through one descriptor that covers exactly the rows of this
-  // split (from the tile's first column on): rows past the split or the matrix
-  // end read as zero by themselves; b_cur walks down by one stage per fetch.
-  uint32_t b_cur[G::NB], b_inc[G::NB];
-  int b_dst[G::NB];
+    for (int it = 0; it < G::NA; ++it) {
+      const int v = tg + it * kRole;
+      const int slot = v / G::VPB, off = v % G::VPB;
+      const int rbk = slot / G::JT, jl = slot % G::JT;
+      const int r = (off * G::VA) / BC, c = (off * G::VA) % BC;
+      const int col = (int)((jfirst + jl) * BC - k0) + c;
+      const bool used = slot < G::R * G::JT && jl < jt && col >= 0 && col + G::VA <= KT;
+      a_src[it] = (uint32_t)(off * G::VA * 2);
+      a_tab[it] = used ? (uint32_t)(rbk * G::JT + jl) : (uint32_t)(nrows * G::JT);
+      a_inc[it] = used ? (uint32_t)(G::R * G::JT) : 0u;
+      a_val[it] = sTab[a_tab[it]];
+      a_dst[it] = used ? swizzled(rbk * BR + r, col) : -1;
+    }
+    // dY is addressed through one descriptor that covers exactly the rows of this
+    // split (from the tile's first column on): rows past the split or the matrix
+    // end read as zero by themselves; b_cur walks down by one stage per fetch.
+    uint32_t b_cur[G::NB], b_inc[G::NB];
+    int b_dst[G::NB];
 #pragma unroll
-  for (int it = 0; it < G::NB; ++it) {
-    const int v = t + it * kThreads;
-    const int r = v / (NT / VB), c = (v % (NT / VB)) * VB;
-    const bool used = r < G::ROWS && n0 + c < N;
-    b_cur[it] = used ? (uint32_t)(((int64_t)r * lddy + c) * 2) : kOutOfRange;
-    b_inc[it] = used ? (uint32_t)((int64_t)G::ROWS * lddy * 2) : 0u;
-    b_dst[it] = used ? swizzled(r, c) : -1;
-  }
-  // element offsets of the LDS stores relative to stage buffer 0 (>= kDump: the dump slot)
-  constexpr int kDump = 2 * G::STAGE_WORDS * 2;
-  int a_lds[2][G::NA], b_lds[2][G::NB];
+    for (int it = 0; it < G::NB; ++it) {
+      const int v = tg + it * kRole;
+      const int r = v / (NT / VB), c = (v % (NT / VB)) * VB;
+      const bool used = r < G::ROWS && n0 + c < N;
+      b_cur[it] = used ? (uint32_t)(((int64_t)r * lddy + c) * 2) : kOutOfRange;
+      b_inc[it] = used ? (uint32_t)((int64_t)G::ROWS * lddy * 2) : 0u;
+      b_dst[it] = used ? swizzled(r, c) : -1;
+    }
+    // element offsets of the LDS stores relative to stage buffer 0 (>= kDump: the dump slot)
+    constexpr int kDump = 2 * G::STAGE_WORDS * 2;
+    int a_lds[2][G::NA], b_lds[2][G::NB];
 #pragma unroll
-  for (int buf = 0; buf < 2; ++buf) {
+    for (int buf = 0; buf < 2; ++buf) {
 #pragma unroll
-    for (int it = 0; it < G::NA; ++it)
-      a_lds[buf][it] = a_dst[it] >= 0 ? buf * G::STAGE_WORDS * 2 + a_dst[it] : kDump + lane * 8;
+      for (int it = 0; it < G::NA; ++it)
+        a_lds[buf][it] = a_dst[it] >= 0 ? buf * G::STAGE_WORDS * 2 + a_dst[it] : kDump + lane * 8;
 #pragma unroll
-    for (int it = 0; it < G::NB; ++it)
-      b_lds[buf][it] = b_dst[it] >= 0 ? buf * G::STAGE_WORDS * 2 + MS * G::LDA + b_dst[it] : kDump + lane * 8;
-  }
-  const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(values, values_bytes);
-  int64_t split_rows = (i_begin + nrows) * BR;
-  if (split_rows > M) split_rows = M;
-  split_rows -= i_begin * BR;                                                // dY rows of this split
-  const int64_t dy_split = split_rows > 0 ? ((split_rows - 1) * lddy + (N - n0)) * 2 : 0;
-  const __amdgpu_buffer_rsrc_t rsrc_b =
-      make_rsrc(reinterpret_cast<const char *>(dY) + (i_begin * BR * lddy + n0) * 2, (uint32_t)dy_split);
+      for (int it = 0; it < G::NB; ++it)
+        b_lds[buf][it] = b_dst[it] >= 0 ? buf * G::STAGE_WORDS * 2 + MS * G::LDA + b_dst[it] : kDump + lane * 8;
+    }
+    const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(values, values_bytes);
+    int64_t split_rows = (i_begin + nrows) * BR;
+    if (split_rows > M) split_rows = M;
+    split_rows -= i_begin * BR;                                                // dY rows of this split
+    const int64_t dy_split = split_rows > 0 ? ((split_rows - 1) * lddy + (N - n0)) * 2 : 0;
+    const __amdgpu_buffer_rsrc_t rsrc_b =
+        make_rsrc(reinterpret_cast<const char *>(dY) + (i_begin * BR * lddy + n0) * 2, (uint32_t)dy_split);
 
-  AVec ra[D][G::NA];
-  BVec rb[D][G::NB];
+    AVec ra[D][G::NA];
+    BVec rb[D][G::NB];
+    // Global load of the next stage's activation vector `it` / dY vector `it` into
+    // ring slot d.  Branch-free: a vector that is pruned, outside the matrix or
+    // beyond the split reads as zero through an out-of-range offset, so the number
+    // of loads in flight is known at compile time.  Each call moves the vector's
+    // state on by one stage.
+    auto load_a = [&](int d, int it) {
+      ra[d][it] = buffer_load<G::VA * 2>(rsrc_a, a_val[it] + a_src[it]);
+      a_tab[it] += a_inc[it];
+      a_val[it] = sTab[a_tab[it]];
+    };
+    auto load_b = [&](int d, int it) {
+      rb[d][it] = buffer_load<VB * 2>(rsrc_b, b_cur[it]);
+      b_cur[it] += b_inc[it];
+    };
+    // Ring slot d -> LDS stage buffer `buf`; unused vectors go to the dump slot,
+    // so no store needs a predicate.
+    uint16_t *const s0 = reinterpret_cast<uint16_t *>(sStage);
+    auto store_a = [&](int d, int it, int buf) { *reinterpret_cast<AVec *>(&s0[a_lds[buf][it]]) = ra[d][it]; };
+    auto store_b = [&](int d, int it, int buf) { *reinterpret_cast<BVec *>(&s0[b_lds[buf][it]]) = rb[d][it]; };
 
-  // Global load of the next stage's activation vector `it` / dY vector `it` into
-  // ring slot d.  Branch-free: a vector that is pruned, outside the matrix or
-  // beyond the split reads as zero through an out-of-range offset, so the number
-  // of loads in flight is known at compile time.  Each call moves the vector's
-  // state on by one stage.
-  auto load_a = [&](int d, int it) {
-    ra[d][it] = buffer_load<G::VA * 2>(rsrc_a, a_val[it] + a_src[it]);
-    a_tab[it] += a_inc[it];
-    a_val[it] = sTab[a_tab[it]];
-  };
-  auto load_b = [&](int d, int it) {
-    rb[d][it] = buffer_load<VB * 2>(rsrc_b, b_cur[it]);
-    b_cur[it] += b_inc[it];
-  };
-  // Ring slot d -> LDS stage buffer `buf`; unused vectors go to the dump slot,
-  // so no store needs a predicate.
-  uint16_t *const s0 = reinterpret_cast<uint16_t *>(sStage);
-  auto store_a = [&](int d, int it, int buf) { *reinterpret_cast<AVec *>(&s0[a_lds[buf][it]]) = ra[d][it]; };
-  auto store_b = [&](int d, int it, int buf) { *reinterpret_cast<BVec *>(&s0[b_lds[buf][it]]) = rb[d][it]; };
+    // stages 0 .. D-1 into the ring, stage 0 on into LDS buffer 0, stage D after it
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+#pragma unroll
+      for (int it = 0; it < G::NA; ++it) load_a(d, it);
+#pragma unroll
+      for (int it = 0; it < G::NB; ++it) load_b(d, it);
+    }
+#pragma unroll
+    for (int it = 0; it < G::NA; ++it) { store_a(0, it, 0); load_a(0, it); }
+#pragma unroll
+    for (int it = 0; it < G::NB; ++it) { store_b(0, it, 0); load_b(0, it); }
+    __syncthreads();
+    // While the multipliers work on stage q (buffer q&1), stage q+1 moves from its
+    // ring slot to the other buffer and the slot is refilled with stage q+1+D.
+    // Many trips round the ring per loop iteration: at the loop header the
+    // compiler's count of loads in flight falls back to a conservative value, so
+    // the first stage of an iteration waits for nearly all of them.
+    constexpr int U = (D % 2 == 0 ? D : 2 * D) * 4;
+    for (int q0 = 0; q0 < nstages; q0 += U) {
+      static_for<U>([&](auto uc) {
+        constexpr int u = decltype(uc)::value;
+        if (q0 + u < nstages) {
+          constexpr int d = (u + 1) % D, buf = (u + 1) & 1;
+#pragma unroll
+          for (int it = 0; it < G::NA; ++it) { store_a(d, it, buf); load_a(d, it); }
+#pragma unroll
+          for (int it = 0; it < G::NB; ++it) { store_b(d, it, buf); load_b(d, it); }
+          __syncthreads();
+        }
+      });
+    }
+    return;
+  }
 
+  // ================= multiplier waves =================
+  const int wk = wave / WN, wn = wave % WN;
   v16f acc[2][G::NTW];
 #pragma unroll
   for (int u = 0; u < 2; ++u)
@@ -369,20 +432,13 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
 #pragma unroll
   for (int w = 0; w < G::NTW; ++w) frag_b[w] = lane_fragment_offset((G::NTW * wn + w) * 32);
 
-  // One stage of the main loop.  Stage q is multiplied out of LDS buffer `buf`
-  // in MSUB steps of 16 activation rows; spread over the same steps, the vectors
-  // of stage q+1 move from ring slot d to the other LDS buffer and the slot is
-  // refilled with stage q+1+D from global memory, one vector at a time, so the
-  // texture path, the LDS and the matrix core are busy side by side instead of
-  // in turn.  The fragments of step ms+1 are requested before the multiplies of
-  // step ms are issued; only the multiplies sit under the wave-uniform skip
-  // branches.  The loop is bound by instruction issue, so everything that can be
-  // tabulated per stage was tabulated in the prologue: the activity bits of 64
-  // stages sit in one register (lane = stage) and reach a scalar register through
-  // one v_readlane.
-  constexpr int NV = G::NA + G::NB;
+  // Stage q out of LDS buffer `buf` in MSUB steps of 16 activation rows.  The
+  // fragments of step ms+1 are requested before the multiplies of step ms are
+  // issued; only the multiplies sit under the wave-uniform skip branches.  The
+  // activity bits of 64 stages sit in one register (lane = stage) and reach a
+  // scalar register through one v_readlane.
   uint32_t pam_reg = 0;
-  auto stage = [&](int d, int q, int buf) {
+  auto multiply = [&](int q, int buf) {
     const uint16_t *sA = reinterpret_cast<const uint16_t *>(sStage + buf * G::STAGE_WORDS);
     const uint16_t *sB = sA + MS * G::LDA;
     if ((q & 63) == 0) pam_reg = sPam[q + lane];
@@ -404,17 +460,6 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
         na0 = read_fragment(sA + frag_a0 + (ms + 1) * 16 * G::LDA, G::LDA);
         na1 = read_fragment(sA + frag_a1 + (ms + 1) * 16 * G::LDA, G::LDA);
       }
-      // this step's share of the data movement
-#pragma unroll
-      for (int v = ms * NV / G::MSUB; v < (ms + 1) * NV / G::MSUB; ++v) {
-        if (v < G::NA) {
-          store_a(d, v, buf ^ 1);
-          load_a(d, v);
-        } else {
-          store_b(d, v - G::NA, buf ^ 1);
-          load_b(d, v - G::NA);
-        }
-      }
       if (pam & (1u << (2 * ms))) {
 #pragma unroll
         for (int w = 0; w < G::NTW; ++w)
@@ -431,48 +476,38 @@ __global__ __launch_bounds__(128 * WN) void dw_mfma_kernel(
     }
   };
 
-  // ---- main loop: stage q is multiplied out of LDS buffer q&1 while stage
-  // q+1 moves from registers to the other buffer and stage q+1+D leaves HBM ----
+  __syncthreads();                           // stage 0 is in LDS buffer 0
+  for (int q0 = 0; q0 < nstages; q0 += 2) {
 #pragma unroll
-  for (int d = 0; d < D; ++d) {
-#pragma unroll
-    for (int it = 0; it < G::NA; ++it) load_a(d, it);
-#pragma unroll
-    for (int it = 0; it < G::NB; ++it) load_b(d, it);
-  }
-#pragma unroll
-  for (int it = 0; it < G::NA; ++it) { store_a(0, it, 0); load_a(0, it); }
-#pragma unroll
-  for (int it = 0; it < G::NB; ++it) { store_b(0, it, 0); load_b(0, it); }
-  __syncthreads();
-  // Several trips round the ring per loop iteration: at the loop header the
-  // compiler's count of loads in flight falls back to a conservative value, so
-  // the first stage of an iteration waits for nearly all of them.
-  constexpr int U = 4 * D;
-  for (int q0 = 0; q0 < nstages; q0 += U) {
-#pragma unroll
-    for (int d = 0; d < U; ++d) {
-      const int q = q0 + d;
-      if (q >= nstages) break;
-      stage((d + 1) % D, q, d & 1);
+    for (int u = 0; u < 2; ++u) {
+      if (q0 + u >= nstages) break;
+      multiply(q0 + u, u);
       __syncthreads();
     }
   }
 
+  // (the branch on `accumulate` is taken once, outside the store loops: inside
+  // them the compiler would read the destination speculatively in both cases)
   float *o = out + (int64_t)split * split_stride;
+  auto write_tile = [&](auto acc_flag) {
+    constexpr bool kAcc = decltype(acc_flag)::value;
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
-    for (int w = 0; w < G::NTW; ++w)
+      for (int w = 0; w < G::NTW; ++w)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t k = k0 + (2 * wk + u) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const int64_t n = n0 + (G::NTW * wn + w) * 32 + (lane & 31);
-        if (k < K && n < N) {
-          float *dst = o + k * ldo + n;
-          *dst = accumulate ? *dst + acc[u][w][r] : acc[u][w][r];
+        for (int r = 0; r < 16; ++r) {
+          const int64_t k = k0 + (2 * wk + u) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          const int64_t n = n0 + (G::NTW * wn + w) * 32 + (lane & 31);
+          if (k < K && n < N) {
+            float *dst = o + k * ldo + n;
+            if (kAcc) *dst += acc[u][w][r];
+            else *dst = acc[u][w][r];
+          }
         }
-      }
+  };
+  if (accumulate) write_tile(std::true_type{});
+  else write_tile(std::false_type{});
 }
 
 struct Plan {
@@ -480,21 +515,41 @@ struct Plan {
   int64_t stages_per_split;
 };
 
+// Number of splits of the contraction.  One workgroup (loader and multiplier
+// waves) runs per compute unit, so the tiles x splits work items are processed in
+// rounds of 256; a round costs its stages plus a fixed part (table build, partial
+// tile write-out), and every split adds one pass over the K x N partial tiles
+// (written once, read once by the reduction).  The constants are measured orders
+// of magnitude on MI355X, in microseconds; only the choice of s depends on them.
 template <int BR, int MS>
 Plan make_plan(int64_t M, int64_t K, int64_t N) {
   constexpr int R = MS / BR;
+  constexpr int kSlots = 256;
   const int64_t nbr = ceil_div(M, BR);
   const int64_t stages = ceil_div(nbr, R);
   const int64_t tiles = ceil_div(K, 128) * ceil_div(N, 128);
-  static const int target = getenv("BSR_DW_TARGET_WGS") ? atoi(getenv("BSR_DW_TARGET_WGS")) : 512;
-  int64_t s = (target + tiles / 2) / (tiles > 0 ? tiles : 1);
-  if (s > stages) s = stages;
-  if (s < 1) s = 1;
-  int64_t sps = stages > 0 ? ceil_div(stages, s) : 1;
-  if (sps * R > kMaxRowsPerSplit) sps = kMaxRowsPerSplit / R;
-  s = stages > 0 ? ceil_div(stages, sps) : 1;
   Plan p;
-  p.splits = (int)s;
+  p.splits = 1;
+  p.stages_per_split = stages > 0 ? stages : 1;
+  if (stages <= 0 || tiles <= 0) return p;
+  static const int forced = getenv("BSR_DW_SPLITS") ? atoi(getenv("BSR_DW_SPLITS")) : 0;   // development knob
+  const double us_stage = 0.42 * MS / 64.0, us_round = 8.0;
+  const double us_split = 2.0 * (double)K * (double)N * 4.0 / 3.0e6;
+  const int64_t s_min = ceil_div(stages * R, (int64_t)kMaxRowsPerSplit);
+  int64_t s_max = stages < 64 ? stages : 64;
+  if (s_max < s_min) s_max = s_min;
+  double best = 0;
+  int64_t best_s = 0;
+  for (int64_t s = s_min; s <= s_max; ++s) {
+    const int64_t sps = ceil_div(stages, s);
+    const int64_t s_eff = ceil_div(stages, sps);
+    const int64_t rounds = ceil_div(tiles * s_eff, (int64_t)kSlots);
+    const double cost = (double)rounds * ((double)sps * us_stage + us_round) + (s_eff > 1 ? (double)s_eff * us_split : 0.0);
+    if (best_s == 0 || cost < best) { best = cost; best_s = s_eff; }
+  }
+  if (forced > 0) best_s = forced < s_min ? s_min : forced;
+  const int64_t sps = ceil_div(stages, best_s);
+  p.splits = (int)ceil_div(stages, sps);
   p.stages_per_split = sps;
   return p;
 }
@@ -519,14 +574,13 @@ int run(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int6
   const uint16_t *y = static_cast<const uint16_t *>(dY);
   // 32-bit buffer offsets: both operands must stay below 4 GiB (checked by dw_mfma_supported)
   const uint32_t values_bytes = (uint32_t)(nbr * nbc * BR * BC * 2);
-  const uint32_t dy_bytes = M > 0 ? (uint32_t)(((M - 1) * lddy + N) * 2) : 0u;
   int vb = 8;
   while (vb > 1 && (N % vb != 0 || lddy % vb != 0 || (uintptr_t)dY % (2 * vb) != 0)) vb >>= 1;
 #define BSR_DW_LAUNCH(VB)                                                                         \
-  hipLaunchKernelGGL((dw_mfma_kernel<BR, BC, MS, VB, D, WN>), grid, dim3(128 * WN), 0, s,          \
+  hipLaunchKernelGGL((dw_mfma_kernel<BR, BC, MS, VB, D, WN>), grid, dim3(256 * WN), 0, s,          \
                      row_ptr, col_idx, v, y, out, M, K, N, lddy, ldo, stride, nbr, nbc,            \
                      p.stages_per_split, acc_direct, tiles_k, tiles_n, p.splits, xcd_map,           \
-                     values_bytes, dy_bytes)
+                     values_bytes)
   if (vb == 8) BSR_DW_LAUNCH(8);
   else if (vb == 4) BSR_DW_LAUNCH(4);
   else if (vb == 2) BSR_DW_LAUNCH(2);
@@ -560,20 +614,10 @@ bool dw_mfma_supported(int dtype, int br, int bc, const void *values, int64_t M,
   return true;
 }
 
-// Tuning knobs (development only): stage rows and prefetch depth of the 32 x 32 kernel.
-static int knob_ms32() {
-  static const int v = getenv("BSR_DW_MS") ? atoi(getenv("BSR_DW_MS")) : 64;
-  return v == 32 ? 32 : 64;
-}
-static int knob_depth() {
-  static const int v = getenv("BSR_DW_DEPTH") ? atoi(getenv("BSR_DW_DEPTH")) : 2;
-  return v;
-}
-
 size_t dw_mfma_ws_bytes(int64_t M, int64_t K, int64_t N, int br, int bc) {
   (void)bc;
   switch (br) {
-    case 32: return knob_ms32() == 32 ? ws_for<32, 32>(M, K, N) : ws_for<32, 64>(M, K, N);
+    case 32: return ws_for<32, 64>(M, K, N);
     case 64: return ws_for<64, 64>(M, K, N);
     case 16: return ws_for<16, 32>(M, K, N);
     case 14: return ws_for<14, 32>(M, K, N);
@@ -586,17 +630,12 @@ int launch_dw_mfma(const int32_t *row_ptr, const int32_t *col_idx, const void *v
                    int64_t lddw, int accumulate, void *ws, size_t ws_bytes, hipStream_t s) {
   if (K == 0 || N == 0) return BSR_OK;
 #define BSR_ARGS row_ptr, col_idx, values, M, K, dY, N, lddy, dW, lddw, accumulate, ws, ws_bytes, s
-  static const int wn = getenv("BSR_DW_WN") ? atoi(getenv("BSR_DW_WN")) : 4;
-  if (br == 32 && bc == 32) {
-    if (wn == 4) return knob_ms32() == 32 ? run<32, 32, 32, 2, 4>(BSR_ARGS) : run<32, 32, 64, 2, 4>(BSR_ARGS);
-    return knob_ms32() == 32 ? run<32, 32, 32, 2, 2>(BSR_ARGS) : run<32, 32, 64, 2, 2>(BSR_ARGS);
-  }
-  if (br == 64 && bc == 64) return wn == 4 ? run<64, 64, 64, 2, 4>(BSR_ARGS) : run<64, 64, 64, 2, 2>(BSR_ARGS);
-  if (br == 16 && bc == 16) return run<16, 16, 32, 4, 2>(BSR_ARGS);
-  if (br == 14 && bc == 14) return wn == 4 ? run<14, 14, 32, 2, 4>(BSR_ARGS) : run<14, 14, 32, 2, 2>(BSR_ARGS);
+  if (br == 32 && bc == 32) return run<32, 32, 64, 2, 4>(BSR_ARGS);
+  if (br == 64 && bc == 64) return run<64, 64, 64, 2, 4>(BSR_ARGS);
+  if (br == 16 && bc == 16) return run<16, 16, 32, 2, 4>(BSR_ARGS);
+  if (br == 14 && bc == 14) return run<14, 14, 32, 2, 4>(BSR_ARGS);
 #undef BSR_ARGS
   return BSR_ERR_SHAPE;
 }
-
 
 }  // namespace bsr
