@@ -146,9 +146,7 @@ int bsr_compress(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, in
       misaligned(row_ptr, 4) || misaligned(col_idx, 4))
     return BSR_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  rc = launch_index_build(keep_mask, g.nbr, g.nbc, n_keep, row_ptr, col_idx, s);
-  if (rc != BSR_OK) return rc;
-  return launch_pack(X, dtype, M, K, ldx, br, bc, row_ptr, col_idx, n_keep, values, s);
+  return launch_compress(keep_mask, X, dtype, M, K, ldx, br, bc, n_keep, row_ptr, col_idx, values, s);
 }
 
 int bsr_decompress(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int dtype,

@@ -32,6 +32,7 @@
 #include <cstdlib>
 #include <utility>
 
+#include "buffer_access.h"
 #include "common.h"
 
 namespace bsr {
@@ -45,15 +46,6 @@ typedef __attribute__((ext_vector_type(16))) float v16f;
 
 constexpr int kMaxRowsPerSplit = 256;   // block-rows of one split: its block table must fit in LDS
 
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-
-template <int BYTES> struct Chunk;
-template <> struct Chunk<16> { typedef u32x4 type; };
-template <> struct Chunk<8> { typedef u32x2 type; };
-template <> struct Chunk<4> { typedef uint32_t type; };
-template <> struct Chunk<2> { typedef uint16_t type; };
-
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose
 // index is a compile-time constant in every trip, whatever its length (register
 // arrays indexed with it never end up in scratch memory).
@@ -66,35 +58,9 @@ __device__ __forceinline__ void static_for(F &&f) {
   static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F &&>(f));
 }
 
-constexpr uint32_t kOutOfRange = 0xFFFFFFFFu;   // buffer offset that reads as zero, touches no memory
 // Table entry of a pruned block: still out of range after a byte offset inside a
 // block is added (the activation values must stay below 2 GiB).
 constexpr uint32_t kDead = 0x80000000u;
-
-// Untyped buffer resource over [base, base + bytes): loads at offsets beyond
-// `bytes` return zero without a memory access, which predicates a load without
-// a branch (the compiler can then count outstanding loads exactly).
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
-}
-
-// off = per-lane byte offset (range-checked against the descriptor), soff =
-// wave-uniform byte offset added to the address.
-template <int BYTES>
-__device__ __forceinline__ typename Chunk<BYTES>::type buffer_load(__amdgpu_buffer_rsrc_t r, uint32_t off,
-                                                                   uint32_t soff = 0);
-template <> __device__ __forceinline__ u32x4 buffer_load<16>(__amdgpu_buffer_rsrc_t r, uint32_t off, uint32_t soff) {
-  return __builtin_amdgcn_raw_buffer_load_b128(r, off, soff, 0);
-}
-template <> __device__ __forceinline__ u32x2 buffer_load<8>(__amdgpu_buffer_rsrc_t r, uint32_t off, uint32_t soff) {
-  return __builtin_amdgcn_raw_buffer_load_b64(r, off, soff, 0);
-}
-template <> __device__ __forceinline__ uint32_t buffer_load<4>(__amdgpu_buffer_rsrc_t r, uint32_t off, uint32_t soff) {
-  return __builtin_amdgcn_raw_buffer_load_b32(r, off, soff, 0);
-}
-template <> __device__ __forceinline__ uint16_t buffer_load<2>(__amdgpu_buffer_rsrc_t r, uint32_t off, uint32_t soff) {
-  return __builtin_amdgcn_raw_buffer_load_b16(r, off, soff, 0);
-}
 
 // 8 contraction elements x 16 rows/columns for this lane's 16-lane group,
 // transposed out of a row-major LDS tile (two 4 x 16 sub-tiles).  `p` already

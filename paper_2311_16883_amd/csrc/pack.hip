@@ -6,6 +6,8 @@
 //   pack        : bit copy of the kept blocks into `values` (HBM-bound gather);
 //   decompress  : BSR -> dense, pruned positions become +0.0.
 // All three are pure data movement / integer work and are bit-exact.
+#include <cstdlib>
+
 #include "common.h"
 
 namespace bsr {
@@ -138,6 +140,110 @@ __global__ __launch_bounds__(256) void pack_kernel(
   }
 }
 
+constexpr int kFusedCols = 4096;   // block-columns per block-row the fused kernel can list in LDS
+
+// Kept blocks in mask[0, n): 16-byte loads, every thread returns the total.
+__device__ __forceinline__ uint32_t count_kept_prefix(const uint8_t *__restrict__ mask, int64_t n,
+                                                      uint32_t *wave_tot, uint32_t *total) {
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  uint32_t cnt = 0;
+  const uintptr_t addr = reinterpret_cast<uintptr_t>(mask);
+  int64_t head = (int64_t)((16 - (addr & 15)) & 15);
+  if (head > n) head = n;
+  const int64_t nvec = (n - head) / 16;
+  const int64_t tail0 = head + nvec * 16;
+  if (t < head) cnt += mask[t] ? 1u : 0u;
+  const uint4 *v = reinterpret_cast<const uint4 *>(mask + head);
+#pragma unroll 4
+  for (int64_t e = t; e < nvec; e += 256) {
+    const uint4 x = v[e];
+    cnt += nonzero_bytes(x.x) + nonzero_bytes(x.y) + nonzero_bytes(x.z) + nonzero_bytes(x.w);
+  }
+  if (tail0 + t < n) cnt += mask[tail0 + t] ? 1u : 0u;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d, 64);
+  if (lane == 0) wave_tot[wave] = cnt;
+  __syncthreads();
+  if (t == 0) *total = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+  __syncthreads();
+  const uint32_t r = *total;
+  __syncthreads();
+  return r;
+}
+
+// Mask -> BSR in one launch: workgroup i owns block-row i.  It counts the kept
+// blocks in front of its row (the mask prefix comes from L2: a few dozen KB), lists
+// the row's kept block-columns (row_ptr / col_idx and an LDS copy), then copies the
+// kept blocks.  Thread -> (row, vector) inside a block is fixed up front, so the
+// copy loops do no division.  Positions at or beyond n_keep are never written.
+template <int VB>
+__global__ __launch_bounds__(256) void compress_kernel(
+    const uint8_t *__restrict__ mask, const uint8_t *__restrict__ X, int64_t M, int64_t kb, int64_t ldb,
+    int br, int64_t bcb, int64_t nbr, int64_t nbc, int64_t n_keep, int32_t *__restrict__ row_ptr,
+    int32_t *__restrict__ col_idx, uint8_t *__restrict__ values) {
+  typedef typename BytesOf<VB>::type V;
+  __shared__ uint32_t wave_tot[4];
+  __shared__ uint32_t total;
+  __shared__ int32_t kept_j[kFusedCols];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int64_t i = blockIdx.x;
+  const uint32_t prefix = count_kept_prefix(mask, i * nbc, wave_tot, &total);
+
+  // ---- this row's kept block-columns, in order ----
+  uint32_t row_kept = 0;
+  const uint8_t *mrow = mask + i * nbc;
+  for (int64_t c0 = 0; c0 < nbc; c0 += 256) {
+    const int64_t j = c0 + t;
+    const bool flag = j < nbc && mrow[j] != 0;
+    const unsigned long long ball = __ballot(flag);
+    if (lane == 0) wave_tot[wave] = (uint32_t)__popcll(ball);
+    __syncthreads();
+    uint32_t before = row_kept;
+    for (int w = 0; w < wave; ++w) before += wave_tot[w];
+    const uint32_t pos = before + (uint32_t)__popcll(ball & ((1ull << lane) - 1ull));
+    if (flag) {
+      kept_j[pos] = (int32_t)j;
+      if ((int64_t)prefix + pos < n_keep) col_idx[prefix + pos] = (int32_t)j;
+    }
+    row_kept += wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+    __syncthreads();
+  }
+  if (t == 0) {
+    row_ptr[i] = (int32_t)prefix;
+    if (i == nbr - 1) row_ptr[nbr] = (int32_t)(prefix + row_kept);
+  }
+  int64_t nk = row_kept;                                   // blocks of this row that have a place in `values`
+  if ((int64_t)prefix + nk > n_keep) nk = n_keep > (int64_t)prefix ? n_keep - prefix : 0;
+  if (nk == 0) return;
+
+  // ---- copy ----
+  const int vpb = (int)(bcb / VB);
+  const int S = br * vpb;                                  // vectors per block
+  const uint8_t *xrow = X + i * br * ldb;
+  uint8_t *vrow = values + (int64_t)prefix * S * VB;
+  const int64_t rows_left = M - i * br;
+  auto copy = [&](int q, int r, int v, int e) {
+    const int64_t cb = (int64_t)kept_j[q] * bcb + (int64_t)v * VB;
+    V val = zero_bytes<VB>();
+    if (r < rows_left && cb < kb) val = *reinterpret_cast<const V *>(xrow + (int64_t)r * ldb + cb);
+    *reinterpret_cast<V *>(vrow + ((int64_t)q * S + e) * VB) = val;
+  };
+  if (S <= 256) {
+    const int G = 256 / S, g = t / S, e = t - g * S;      // G blocks per pass
+    if (g < G) {
+      const int r = e / vpb, v = e - r * vpb;
+#pragma unroll 4
+      for (int q = g; q < (int)nk; q += G) copy(q, r, v, e);
+    }
+  } else {
+    for (int e = t; e < S; e += 256) {
+      const int r = e / vpb, v = e - r * vpb;
+#pragma unroll 4
+      for (int q = 0; q < (int)nk; ++q) copy(q, r, v, e);
+    }
+  }
+}
+
 constexpr int kMapCols = 1024;   // block-columns per workgroup in decompress
 
 // Scatter: a workgroup owns block-row i and a chunk of kMapCols block-columns;
@@ -228,6 +334,37 @@ int launch_pack(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int
     default: BSR_PACK(2); break;
   }
 #undef BSR_PACK
+  return check_launch();
+}
+
+int launch_compress(const uint8_t *keep_mask, const void *X, int dtype, int64_t M, int64_t K, int64_t ldx,
+                    int br, int bc, int64_t n_keep, int32_t *row_ptr, int32_t *col_idx, void *values,
+                    hipStream_t s) {
+  const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
+  // one fused launch when a block-row's columns fit its LDS list and re-reading the
+  // mask prefix in every workgroup stays cheap (nbr * nblocks / 2 bytes out of L2)
+  const bool fused = nbr > 0 && nbc > 0 && nbc <= kFusedCols && nbr <= 65535 &&
+                     nbr * nbr * nbc <= (int64_t(1) << 31);
+  static const bool allow = !(getenv("BSR_COMPRESS_FUSED") && atoi(getenv("BSR_COMPRESS_FUSED")) == 0);   // development knob
+  if (!fused || !allow) {
+    int rc = launch_index_build(keep_mask, nbr, nbc, n_keep, row_ptr, col_idx, s);
+    if (rc != BSR_OK) return rc;
+    return launch_pack(X, dtype, M, K, ldx, br, bc, row_ptr, col_idx, n_keep, values, s);
+  }
+  const int e = elem_bytes(dtype);
+  const int vb = pick_bytes(e, bc, K, ldx, X, values);
+  const uint8_t *x = static_cast<const uint8_t *>(X);
+  uint8_t *v = static_cast<uint8_t *>(values);
+#define BSR_COMPRESS(VB)                                                                            \
+  hipLaunchKernelGGL((compress_kernel<VB>), dim3((unsigned)nbr), dim3(256), 0, s, keep_mask, x, M,  \
+                     K * e, ldx * e, br, (int64_t)bc * e, nbr, nbc, n_keep, row_ptr, col_idx, v)
+  switch (vb) {
+    case 16: BSR_COMPRESS(16); break;
+    case 8: BSR_COMPRESS(8); break;
+    case 4: BSR_COMPRESS(4); break;
+    default: BSR_COMPRESS(2); break;
+  }
+#undef BSR_COMPRESS
   return check_launch();
 }
 

@@ -15,18 +15,22 @@
 // ties through the index part of C.
 //
 // Large inputs: two grid-wide passes.
-//   pass 1  every workgroup draws the same 256-key sample, takes from it two
-//           order statistics lo <= hi that bracket the rank of the threshold,
-//           and counts its slice of the keys into 256 buckets: bucket 0 below
-//           lo, the last bucket above hi, equal-width buckets in between (any
-//           monotone bucketing keeps the selection exact; a good bracket only
-//           makes the threshold bucket small).  Each workgroup stores its own
-//           counts: no atomics, nothing to clear.
+//   pass 1  every workgroup draws the same small sample, takes from it two order
+//           statistics lo <= hi that bracket the rank of the threshold, and
+//           counts its slice of the keys into 256 buckets: bucket 0 below lo, the
+//           last bucket above hi, equal-width buckets in between (any monotone
+//           bucketing keeps the selection exact; a good bracket only makes the
+//           threshold bucket small).  Each workgroup stores its own counts: no
+//           atomics, nothing to clear.
 //   pass 2  every workgroup adds up the counts, finds the bucket that holds the
 //           n_keep-th largest key, keeps the buckets above it, prunes the ones
-//           below and appends the keys inside it to a candidate list; the last
-//           workgroup to finish ranks the candidates exactly (radix select as
-//           above if they do not fit in LDS) and writes their mask bytes.
+//           below and appends the keys inside it to a candidate list (one atomic
+//           per workgroup); the last workgroup to finish stages the candidates in
+//           LDS and selects among them exactly, with the bucket's key range as a
+//           bracket: 32-bit codes linear in the key, one 8-bit radix pass as a
+//           rule, then a ranking of the handful that share the threshold's code
+//           through lane reads.  The general radix select remains the fallback
+//           when a bracket misses or too many keys are equal.
 #include "common.h"
 
 namespace bsr {
@@ -39,6 +43,7 @@ constexpr int kCap = 1024;       // candidates ranked in LDS
 constexpr int kSample = 256;
 constexpr int kGridThreads = 256;
 constexpr int kBuckets = 256;    // buckets of the grid-wide passes (one per thread)
+constexpr int kStage = 1024;     // candidates the last workgroup stages in LDS
 
 typedef unsigned __int128 u128;
 
@@ -89,6 +94,10 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *w
   __syncthreads();
   return base + incl - v;
 }
+
+template <int THREADS>
+__device__ __forceinline__ void rank_candidates(SelectShared &sh, uint32_t m, uint32_t want,
+                                                uint8_t *__restrict__ mask);
 
 // One workgroup marks the `want` best of the n elements of `src` in mask
 // (1 = kept, 0 = pruned); every element of src gets its byte written.
@@ -160,18 +169,7 @@ __device__ void radix_select(const Source &src, uint32_t n, uint32_t want, uint3
     }
   }
   __syncthreads();
-  const uint32_t m = sh.n;
-  for (uint32_t c = t; c < m; c += THREADS) {
-    const uint64_t key = sh.ckey[c];
-    const uint32_t idx = sh.cidx[c];
-    uint32_t better = 0;   // candidates that rank strictly before this one
-#pragma unroll 8
-    for (uint32_t o = 0; o < m; ++o) {
-      const uint64_t ok = sh.ckey[o];
-      better += (ok > key || (ok == key && sh.cidx[o] < idx)) ? 1u : 0u;
-    }
-    mask[idx] = better < want ? 1 : 0;
-  }
+  rank_candidates<THREADS>(sh, sh.n, want, mask);
 }
 
 __global__ __launch_bounds__(1024) void select_small_kernel(const double *__restrict__ scores,
@@ -180,6 +178,170 @@ __global__ __launch_bounds__(1024) void select_small_kernel(const double *__rest
   __shared__ SelectShared sh;
   AllScores src{scores};
   radix_select<1024>(src, nblocks, n_keep, nblocks, mask, sh);
+}
+
+// Selection with a bracket.  The caller knows (or hopes) that the want-th best
+// of the n elements of `src` has its key inside [lo, hi].  Keys above hi are only
+// counted; keys inside get a 32-bit code, 1 + ((key - lo) >> shift), that stays
+// in registers (KPT per thread, n <= KPT * THREADS) for the radix passes that
+// find the code of the threshold: the codes spread evenly over the bracket, so
+// usually one 12-bit pass with next to no bin shared.  key -> code is monotone, so
+// a larger (smaller) code than the threshold's means kept (pruned) for certain;
+// the few elements that share the threshold's code are ranked exactly on their
+// full keys and indices.  If the bracket misses the threshold or more than kCap
+// elements share its code (e.g. very many all-zero blocks), the general radix
+// select takes over.  Every element of src gets its mask byte written.
+struct BracketShared {
+  uint32_t wave_cnt[2][16];
+};
+
+// Exact ranking of the m candidates listed in sh.ckey / sh.cidx: the `want` best
+// in (key descending, index ascending) order are kept.  Up to 64 candidates sit
+// one per lane of the first wave and are compared through lane reads (no LDS
+// round trip per comparison); longer lists (many equal keys) go through LDS.
+template <int THREADS>
+__device__ __forceinline__ void rank_candidates(SelectShared &sh, uint32_t m, uint32_t want,
+                                                uint8_t *__restrict__ mask) {
+  const int t = threadIdx.x;
+  if (m <= 64u) {
+    if (t < 64) {
+      const bool live = (uint32_t)t < m;
+      const uint64_t k = live ? sh.ckey[t] : 0ull;
+      const uint32_t idx = live ? sh.cidx[t] : 0u;
+      const uint32_t klo = (uint32_t)k, khi = (uint32_t)(k >> 32);
+      uint32_t better = 0;   // candidates that rank strictly before this one
+      for (uint32_t o = 0; o < m; ++o) {
+        const uint64_t ok = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)khi, (int)o) << 32) |
+                            (uint32_t)__builtin_amdgcn_readlane((int)klo, (int)o);
+        const uint32_t oidx = (uint32_t)__builtin_amdgcn_readlane((int)idx, (int)o);
+        better += (ok > k || (ok == k && oidx < idx)) ? 1u : 0u;
+      }
+      if (live) mask[idx] = better < want ? 1 : 0;
+    }
+    return;
+  }
+  for (uint32_t c = t; c < m; c += THREADS) {
+    const uint64_t k = sh.ckey[c];
+    const uint32_t idx = sh.cidx[c];
+    uint32_t better = 0;
+#pragma unroll 8
+    for (uint32_t o = 0; o < m; ++o) {
+      const uint64_t ok = sh.ckey[o];
+      better += (ok > k || (ok == k && sh.cidx[o] < idx)) ? 1u : 0u;
+    }
+    mask[idx] = better < want ? 1 : 0;
+  }
+}
+
+// DB = bits per radix pass: the pass costs one histogram of 2^DB bins (zeroed,
+// filled, scanned by THREADS threads), so small workgroups take small digits.
+template <int THREADS, int KPT, int DB, typename Source>
+__device__ void bracketed_select(const Source &src, uint32_t n, uint32_t want_total, uint64_t lo, uint64_t hi,
+                                 uint32_t nblocks, uint8_t *__restrict__ mask, SelectShared &sh,
+                                 BracketShared &bs) {
+  constexpr int kLocalBins = 1 << DB;
+  constexpr int kPerThread = kLocalBins / THREADS;
+  static_assert(kPerThread >= 1 && kLocalBins <= kBins, "one bin per thread at least");
+  constexpr uint32_t kAbove = 0xFFFFFFFFu, kBelow = 0u;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  // element i of this thread is number t + i * THREADS of src; the first cnt exist
+  const int cnt = (uint32_t)t < n ? (int)((n - 1u - (uint32_t)t) / THREADS) + 1 : 0;
+  const uint64_t range = hi - lo;
+  // smallest shift with 1 + (range >> shift) <= 0xFFFFFFFE
+  int shift = range == 0 ? 0 : 64 - __clzll((long long)range);          // bit length of range
+  shift = shift > 31 ? shift - 31 : 0;
+
+  uint32_t code[KPT];
+  uint32_t n_above = 0, n_inside = 0;
+#pragma unroll
+  for (int i = 0; i < KPT; ++i) {
+    const uint32_t e = (uint32_t)(t + i * THREADS);
+    const uint64_t key = src.key(e < n ? e : 0u);
+    uint32_t c = 1u + (uint32_t)((key - lo) >> shift);
+    c = key > hi ? kAbove : (key < lo ? kBelow : c);
+    if (i >= cnt) c = kBelow;
+    n_above += c == kAbove ? 1u : 0u;
+    n_inside += (c != kAbove && c != kBelow) ? 1u : 0u;
+    code[i] = c;
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    n_above += __shfl_xor(n_above, d, 64);
+    n_inside += __shfl_xor(n_inside, d, 64);
+  }
+  if (lane == 0) { bs.wave_cnt[0][wave] = n_above; bs.wave_cnt[1][wave] = n_inside; }
+  __syncthreads();
+  n_above = 0;
+  n_inside = 0;
+#pragma unroll
+  for (int w = 0; w < THREADS / 64; ++w) { n_above += bs.wave_cnt[0][w]; n_inside += bs.wave_cnt[1][w]; }
+
+  // bits [ctop, 32) of the threshold's code are settled and equal cprefix
+  int ctop = 32;
+  uint32_t cprefix = 0, want = want_total - n_above, n_cand = n_inside;
+  const bool bracketed = want_total > n_above && want <= n_inside;
+  while (bracketed && n_cand > 64u && ctop > 0) {
+    const int dshift = ctop > DB ? ctop - DB : 0;
+    const uint32_t dmask = (1u << (ctop - dshift)) - 1u;
+    for (int b = t; b < kLocalBins; b += THREADS) sh.hist[b] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      const uint32_t c = code[i];
+      if (c != kAbove && c != kBelow && (ctop == 32 || (c >> ctop) == cprefix))
+        atomicAdd(&sh.hist[(c >> dshift) & dmask], 1u);
+    }
+    __syncthreads();
+    uint32_t h[kPerThread], own = 0;
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) {
+      h[u] = sh.hist[kLocalBins - 1 - (kPerThread * t + u)];
+      own += h[u];
+    }
+    uint32_t above = block_exclusive_scan<THREADS>(own, sh.wave_tot);
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) {
+      if (above < want && want <= above + h[u]) {
+        sh.digit = (uint32_t)(kLocalBins - 1 - (kPerThread * t + u));
+        sh.above = above;
+        sh.count = h[u];
+      }
+      above += h[u];
+    }
+    __syncthreads();
+    cprefix = ctop == 32 ? sh.digit : ((cprefix << (ctop - dshift)) | sh.digit);
+    want -= sh.above;
+    n_cand = sh.count;
+    ctop = dshift;
+    __syncthreads();
+  }
+  if (!bracketed || n_cand > (uint32_t)kCap) {
+    radix_select<THREADS>(src, n, want_total, nblocks, mask, sh);
+    return;
+  }
+
+  // larger code: kept; smaller: pruned; equal: ranked exactly on the full keys
+  if (t == 0) sh.n = 0;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < KPT; ++i) {
+    if (i < cnt) {
+      const uint32_t e = (uint32_t)(t + i * THREADS);
+      const uint32_t c = code[i];
+      const bool inside = c != kAbove && c != kBelow;
+      // with no pass run (ctop == 32) every element inside the bracket is a candidate
+      const uint32_t chi = ctop == 32 ? 0u : c >> ctop;
+      if (inside && chi == cprefix) {
+        const uint32_t pos = atomicAdd(&sh.n, 1u);
+        sh.ckey[pos] = src.key(e);
+        sh.cidx[pos] = src.idx(e);
+      } else {
+        mask[src.idx(e)] = (c == kAbove || (inside && chi > cprefix)) ? 1 : 0;
+      }
+    }
+  }
+  __syncthreads();
+  rank_candidates<THREADS>(sh, sh.n, want, mask);
 }
 
 // Control block shared by the two grid-wide passes (lives in the workspace;
@@ -195,6 +357,10 @@ __device__ __forceinline__ uint32_t bucket_of(uint64_t key, uint64_t lo, uint64_
   return 1u + (uint32_t)((key - lo) >> shift);
 }
 
+// NS = sample size: 64 (ranked inside one wave through lane reads, no LDS round
+// trips) or kSample = 256 (ranked through LDS; a tighter bracket for very large
+// inputs, where the threshold bucket must still fit the candidate ranking).
+template <int NS>
 __global__ __launch_bounds__(kGridThreads) void select_count_kernel(
     const double *__restrict__ scores, uint32_t nblocks, uint32_t n_keep, uint32_t per_wg,
     uint32_t *__restrict__ counts, SelectCtrl *__restrict__ ctrl) {
@@ -202,27 +368,53 @@ __global__ __launch_bounds__(kGridThreads) void select_count_kernel(
   __shared__ uint64_t sample[kSample];
   __shared__ uint64_t bracket[2];
   const int t = threadIdx.x;
+  constexpr int kKeys = 4;                        // keys per thread held in registers (per_wg <= 1024)
 
-  // the same sample in every workgroup: kSample evenly spaced keys
-  sample[t] = score_key(scores[(uint64_t)t * nblocks / kSample]);
+  // this workgroup's slice (loads in flight while the sample is ranked)
+  const uint32_t e0 = blockIdx.x * per_wg;
+  const uint32_t e1 = (e0 + per_wg) < nblocks ? (e0 + per_wg) : nblocks;
+  double raw[kKeys];
+#pragma unroll
+  for (int i = 0; i < kKeys; ++i) {
+    const uint32_t e = e0 + t + i * kGridThreads;
+    raw[i] = scores[e < e1 ? e : e0];
+  }
+
+  // the same sample in every workgroup: NS evenly spaced keys
+  uint64_t mine = 0;
+  if (t < NS) mine = score_key(scores[(uint64_t)t * nblocks / NS]);
   hist[t] = 0;
-  if (t < 2) bracket[t] = t == 0 ? 0ull : ~0ull;
-  __syncthreads();
-  {
-    // ascending rank of my sample key (ties by position), then the two order
-    // statistics around the threshold's expected position
-    const uint64_t mine = sample[t];
+  const double frac = 1.0 - (double)n_keep / (double)nblocks;       // threshold's quantile from below
+  const int pos = (int)(frac * NS);
+  const int delta = 3 + (int)(3.5 * sqrt(NS * frac * (1.0 - frac)));
+  const int rlo = pos - delta < 0 ? 0 : pos - delta;
+  const int rhi = pos + delta > NS - 1 ? NS - 1 : pos + delta;
+  if (NS == 64) {
+    if (t < 64) {
+      // ascending rank of my sample key (ties by position) from the other lanes' keys
+      int rank = 0;
+      const uint32_t mlo = (uint32_t)mine, mhi = (uint32_t)(mine >> 32);
+#pragma unroll 16
+      for (int o = 0; o < 64; ++o) {
+        const uint64_t k = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mhi, o) << 32) |
+                           (uint32_t)__builtin_amdgcn_readlane((int)mlo, o);
+        rank += (k < mine || (k == mine && o < t)) ? 1 : 0;
+      }
+      // the two order statistics around the threshold's expected position
+      if (rank == rlo) bracket[0] = mine;
+      if (rank == rhi) bracket[1] = mine;
+    }
+  } else {
+    sample[t] = mine;
+    __syncthreads();
     int rank = 0;
 #pragma unroll 16
-    for (int o = 0; o < kSample; ++o) {
+    for (int o = 0; o < NS; ++o) {
       const uint64_t k = sample[o];
       rank += (k < mine || (k == mine && o < t)) ? 1 : 0;
     }
-    const double frac = 1.0 - (double)n_keep / (double)nblocks;       // threshold's quantile from below
-    const int pos = (int)(frac * kSample);
-    const int delta = 4 + (int)(4.0 * sqrt(kSample * frac * (1.0 - frac)));
-    if (rank == pos - delta) bracket[0] = mine;     // stays 0 if pos - delta < 0
-    if (rank == pos + delta) bracket[1] = mine;     // stays max if pos + delta >= kSample
+    if (rank == rlo) bracket[0] = mine;
+    if (rank == rhi) bracket[1] = mine;
   }
   __syncthreads();
   const uint64_t lo = bracket[0], hi = bracket[1];
@@ -238,10 +430,10 @@ __global__ __launch_bounds__(kGridThreads) void select_count_kernel(
     ctrl->lo = lo;
     ctrl->hi = hi;
   }
-
-  const uint32_t e0 = blockIdx.x * per_wg;
-  const uint32_t e1 = (e0 + per_wg) < nblocks ? (e0 + per_wg) : nblocks;
-  for (uint32_t e = e0 + t; e < e1; e += kGridThreads)
+#pragma unroll
+  for (int i = 0; i < kKeys; ++i)
+    if (e0 + t + i * kGridThreads < e1) atomicAdd(&hist[bucket_of(score_key(raw[i]), lo, hi, shift)], 1u);
+  for (uint32_t e = e0 + t + kKeys * kGridThreads; e < e1; e += kGridThreads)
     atomicAdd(&hist[bucket_of(score_key(scores[e]), lo, hi, shift)], 1u);
   __syncthreads();
   counts[blockIdx.x * kBuckets + t] = hist[t];
@@ -252,16 +444,34 @@ __global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
     const uint32_t *__restrict__ counts, SelectCtrl *__restrict__ ctrl,
     uint64_t *__restrict__ cand_key, uint32_t *__restrict__ cand_idx, uint8_t *__restrict__ mask) {
   __shared__ SelectShared sh;
-  __shared__ uint32_t is_last;
+  __shared__ BracketShared bs;
+  __shared__ uint32_t is_last, wg_cand, wg_base;
   const int t = threadIdx.x;
   const uint32_t shift = ctrl->shift;
   const uint64_t lo = ctrl->lo, hi = ctrl->hi;
+  constexpr int kKeys = 4;                        // keys per thread loaded up front (per_wg <= 1024 as a rule)
+
+  const uint32_t e0 = blockIdx.x * per_wg;
+  const uint32_t e1 = (e0 + per_wg) < nblocks ? (e0 + per_wg) : nblocks;
+  double raw[kKeys];
+#pragma unroll
+  for (int i = 0; i < kKeys; ++i) {
+    const uint32_t e = e0 + t + i * kGridThreads;
+    raw[i] = scores[e < e1 ? e : e0];
+  }
+  if (t == 0) wg_cand = 0;
 
   // the bucket that holds the n_keep-th largest key (same answer in every workgroup):
   // thread t owns bucket kBuckets-1-t, the scan runs from the top
   uint32_t own = 0;
-#pragma unroll 8
-  for (uint32_t w = 0; w < gridDim.x; ++w) own += counts[w * kBuckets + (kBuckets - 1 - t)];
+  for (uint32_t w0 = 0; w0 < gridDim.x; w0 += 64) {       // 64 independent loads in flight per round
+    uint32_t part[64];
+#pragma unroll
+    for (uint32_t w = 0; w < 64; ++w)
+      part[w] = w0 + w < gridDim.x ? counts[(w0 + w) * kBuckets + (kBuckets - 1 - t)] : 0u;
+#pragma unroll
+    for (uint32_t w = 0; w < 64; ++w) own += part[w];
+  }
   const uint32_t above_me = block_exclusive_scan<kGridThreads>(own, sh.wave_tot);
   if (above_me < n_keep && n_keep <= above_me + own) {
     sh.digit = (uint32_t)(kBuckets - 1 - t);
@@ -271,18 +481,37 @@ __global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
   const uint32_t bucket = sh.digit, above = sh.above;
   __syncthreads();
 
-  const uint32_t e0 = blockIdx.x * per_wg;
-  const uint32_t e1 = (e0 + per_wg) < nblocks ? (e0 + per_wg) : nblocks;
-  for (uint32_t e = e0 + t; e < e1; e += kGridThreads) {
-    const uint64_t key = score_key(scores[e]);
+  // other buckets: mask bytes; the threshold's bucket: this workgroup's candidates
+  // go to LDS first, so the global list takes one atomic per workgroup
+  auto classify = [&](uint32_t e, uint64_t key) {
     const uint32_t b = bucket_of(key, lo, hi, shift);
     if (b != bucket) {
       mask[e] = b > bucket ? 1 : 0;
     } else {
-      const uint32_t pos = atomicAdd(&ctrl->n_cand, 1u);
-      cand_key[pos] = key;
-      cand_idx[pos] = e;
+      const uint32_t pos = atomicAdd(&wg_cand, 1u);
+      if (pos < (uint32_t)kCap) {
+        sh.ckey[pos] = key;
+        sh.cidx[pos] = e;
+      } else {                                   // more than the LDS list holds: straight to the global list
+        const uint32_t g = atomicAdd(&ctrl->n_cand, 1u);
+        cand_key[g] = key;
+        cand_idx[g] = e;
+      }
     }
+  };
+#pragma unroll
+  for (int i = 0; i < kKeys; ++i) {
+    const uint32_t e = e0 + t + i * kGridThreads;
+    if (e < e1) classify(e, score_key(raw[i]));
+  }
+  for (uint32_t e = e0 + t + kKeys * kGridThreads; e < e1; e += kGridThreads) classify(e, score_key(scores[e]));
+  __syncthreads();
+  const uint32_t mine = wg_cand < (uint32_t)kCap ? wg_cand : (uint32_t)kCap;
+  if (t == 0 && mine > 0) wg_base = atomicAdd(&ctrl->n_cand, mine);
+  __syncthreads();
+  for (uint32_t c = t; c < mine; c += kGridThreads) {
+    cand_key[wg_base + c] = sh.ckey[c];
+    cand_idx[wg_base + c] = sh.cidx[c];
   }
   __threadfence();
   __syncthreads();
@@ -291,10 +520,36 @@ __global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
   if (!is_last) return;
   __threadfence();
 
-  // last workgroup: exact ranking of the candidates
+  // last workgroup: the candidates all lie in the threshold bucket's key range,
+  // which serves as the bracket of their exact selection
   const uint32_t n = __hip_atomic_load(&ctrl->n_cand, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   Candidates src{cand_key, cand_idx};
-  radix_select<kGridThreads>(src, n, n_keep - above, nblocks, mask, sh);
+  uint64_t blo, bhi;
+  if (bucket == 0) {
+    blo = 0;
+    bhi = lo - 1;                  // (bucket 0 is empty if lo == 0: never the threshold's)
+  } else if (bucket == (uint32_t)kBuckets - 1) {
+    blo = hi + 1;
+    bhi = ~0ull;
+  } else {
+    blo = lo + ((uint64_t)(bucket - 1) << shift);
+    bhi = blo + ((1ull << shift) - 1ull);
+    if (bhi > hi) bhi = hi;
+  }
+  if (n <= (uint32_t)kStage) {
+    // one trip to memory: the candidates move to LDS and are selected from there
+    __shared__ uint64_t skey[kStage];
+    __shared__ uint32_t sidx[kStage];
+    for (uint32_t c = t; c < n; c += kGridThreads) {
+      skey[c] = cand_key[c];
+      sidx[c] = cand_idx[c];
+    }
+    __syncthreads();
+    Candidates staged{skey, sidx};
+    bracketed_select<kGridThreads, kStage / kGridThreads, 8>(staged, n, n_keep - above, blo, bhi, nblocks, mask, sh, bs);
+  } else {
+    radix_select<kGridThreads>(src, n, n_keep - above, nblocks, mask, sh);
+  }
 }
 
 __global__ void fill_u8_kernel(uint8_t *p, int64_t n, uint8_t v) {
@@ -303,7 +558,7 @@ __global__ void fill_u8_kernel(uint8_t *p, int64_t n, uint8_t v) {
     p[i] = v;
 }
 
-constexpr int64_t kSmallLimit = 8192;      // one workgroup up to here
+constexpr int64_t kSmallLimit = 8192;      // one workgroup, keys re-read from memory per pass
 
 constexpr int kMaxGridWgs = 256;
 
@@ -350,8 +605,12 @@ int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t
   int64_t wgs = ceil_div(nblocks, 1024);
   if (wgs > kMaxGridWgs) wgs = kMaxGridWgs;
   const uint32_t per_wg = (uint32_t)ceil_div(nblocks, wgs);
-  hipLaunchKernelGGL(select_count_kernel, dim3((unsigned)wgs), dim3(kGridThreads), 0, s, scores,
-                     (uint32_t)nblocks, (uint32_t)n_keep, per_wg, counts, ctrl);
+  if (nblocks <= 262144)
+    hipLaunchKernelGGL(select_count_kernel<64>, dim3((unsigned)wgs), dim3(kGridThreads), 0, s, scores,
+                       (uint32_t)nblocks, (uint32_t)n_keep, per_wg, counts, ctrl);
+  else
+    hipLaunchKernelGGL(select_count_kernel<kSample>, dim3((unsigned)wgs), dim3(kGridThreads), 0, s, scores,
+                       (uint32_t)nblocks, (uint32_t)n_keep, per_wg, counts, ctrl);
   int rc = check_launch();
   if (rc != BSR_OK) return rc;
   hipLaunchKernelGGL(select_classify_kernel, dim3((unsigned)wgs), dim3(kGridThreads), 0, s, scores,

@@ -91,6 +91,9 @@ FORWARD_CASES = [
     (96, 8192, 8, 4096, "bf16", 0.5),        # a block row wider than one workgroup pass
     (50, 3, 64, 64, "f32", 0.5),             # a single ragged block
     (4096, 384, 16, 16, "bf16", 0.9),        # > 4096 blocks: several radix levels
+    (48, 40008, 8, 8, "bf16", 0.3),          # 5001 block-columns: index build and pack as two launches
+    (2100, 264, 2, 8, "f32", 0.6),           # 1050 block-rows of 33 blocks: fused conversion, 2-row blocks
+    (640, 1024, 64, 64, "f32", 0.4),         # 1024 vectors per block: several per thread in the fused copy
 ]
 
 
@@ -144,11 +147,10 @@ def test_ties_go_to_the_lowest_index(M, K, br, bc, dtype):
         check_forward(Xi, br, bc, keep, "integers")
 
 
-@pytest.mark.parametrize("keep", [0.5, 0.1, 0.9, 0.999])
-def test_grid_wide_selection_paths(keep):
-    """More than 8192 blocks: sampled bracket, bucket histogram, candidate ranking."""
-    M, K, br, bc = 8192, 512, 16, 16            # 16384 blocks
-    rng = np.random.default_rng(5)
+def selection_stress(M, K, br, bc, keep, seed):
+    """Distributions that stress the selection: continuous, heavy tails with dead blocks and
+    NaN / huge outliers, thousands of exact ties around the threshold, every block equal."""
+    rng = np.random.default_rng(seed)
     X = synth.f32_to_bf16_bits(rng.standard_normal((M, K), dtype=np.float32))
     check_forward(X, br, bc, keep, "normal")
     # heavy tails and dead blocks: a third of the blocks are exactly zero, a few are huge / NaN
@@ -156,14 +158,33 @@ def test_grid_wide_selection_paths(keep):
     dead = rng.random((M // br, K // bc)) < 0.33
     Xo *= ~np.kron(dead, np.ones((br, bc), dtype=bool))
     Xo[17, 5] = 1e30
-    Xo[4000, 100] = np.nan
+    Xo[M // 2, 100] = np.nan
     check_forward(Xo, br, bc, keep, "outliers f32")
-    # small integers: thousands of exact ties inside the threshold bucket
+    # small integers: thousands of exact ties at the threshold
     Xi = synth.f32_to_bf16_bits(rng.integers(-1, 2, size=(M, K)).astype(np.float32))
     check_forward(Xi, br, bc, keep, "integer ties")
     # every block ties
     Xc = synth.f32_to_bf16_bits(np.full((M, K), 0.5, dtype=np.float32))
     check_forward(Xc, br, bc, keep, "all equal")
+
+
+@pytest.mark.parametrize("keep", [0.5, 0.1, 0.9, 0.999])
+@pytest.mark.parametrize("M,K,br,bc", [(8192, 512, 16, 16),      # 16384 blocks
+                                       (2048, 1536, 8, 8),       # 49152 blocks
+                                       (2040, 2048, 8, 8)])      # 65280 blocks, ragged per-thread counts
+def test_grid_wide_selection_sizes(M, K, br, bc, keep):
+    """More than 8192 blocks: sampled bracket, bucket histogram, candidates selected by the last
+    workgroup (linear 32-bit codes, lane-read ranking, general radix select when too many tie)."""
+    selection_stress(M, K, br, bc, keep, seed=5)
+
+
+@pytest.mark.parametrize("keep", [0.5, 0.1, 0.9, 0.999])
+def test_grid_wide_selection_large(keep):
+    """Slices longer than the keys a thread preloads, and (second case) the 256-key sample."""
+    selection_stress(4096, 1536, 8, 8, keep, seed=6)            # 98304 blocks
+    rng = np.random.default_rng(7)
+    X = synth.f32_to_bf16_bits(rng.standard_normal((8192, 1024), dtype=np.float32))
+    check_forward(X, 4, 4, keep, "524288 blocks")
 
 
 def test_nan_inf_and_signed_zero_blocks():
