@@ -247,7 +247,10 @@ __global__ __launch_bounds__(256) void compress_kernel(
 constexpr int kMapCols = 1024;   // block-columns per workgroup in decompress
 
 // Scatter: a workgroup owns block-row i and a chunk of kMapCols block-columns;
-// an LDS table maps block-column -> position in `values` (or -1 = pruned).
+// an LDS table maps block-column -> position in `values` (or -1 = pruned).  The
+// 64 lanes of a wave run along the matrix row (1 KB stores), the four waves take
+// every fourth row; a lane looks its vector's block up once and then walks down
+// the rows with all loads of a batch in flight: no division in the copy loop.
 template <int VB>
 __global__ __launch_bounds__(256) void decompress_kernel(
     const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
@@ -255,31 +258,44 @@ __global__ __launch_bounds__(256) void decompress_kernel(
     int64_t nbr, int64_t nbc, uint8_t *__restrict__ X_out) {
   typedef typename BytesOf<VB>::type V;
   __shared__ int32_t slot[kMapCols];
+  const int t = threadIdx.x, lane = t & 63, rg = t >> 6;
   const int64_t j0 = (int64_t)blockIdx.x * kMapCols;
   const int ncols = (int)((nbc - j0) < kMapCols ? (nbc - j0) : kMapCols);
   const int vpb = (int)(bcb / VB);
+  const int vrow = ncols * vpb;                            // vectors per matrix row in the chunk
+  const int64_t block_bytes = (int64_t)br * bcb;
+  constexpr int kInFlight = 8;
   for (int64_t i = blockIdx.y; i < nbr; i += gridDim.y) {
-    for (int c = threadIdx.x; c < ncols; c += blockDim.x) slot[c] = -1;
+    for (int c = t; c < ncols; c += 256) slot[c] = -1;
     __syncthreads();
     const int64_t p0 = row_ptr[i], p1 = row_ptr[i + 1];
-    for (int64_t p = p0 + threadIdx.x; p < p1; p += blockDim.x) {
+    for (int64_t p = p0 + t; p < p1; p += 256) {
       const int64_t j = col_idx[p];
       if (j >= j0 && j < j0 + ncols) slot[j - j0] = (int32_t)p;
     }
     __syncthreads();
     const int rows = (int)((M - i * br) < br ? (M - i * br) : br);
-    const int64_t vrow = (int64_t)ncols * vpb;          // vectors per matrix row in the chunk
-    const int64_t work = (int64_t)rows * vrow;
-    for (int64_t f = threadIdx.x; f < work; f += blockDim.x) {
-      const int r = (int)(f / vrow);
-      const int64_t w = f % vrow;
-      const int c = (int)(w / vpb), v = (int)(w % vpb);
-      const int64_t cb = (j0 + c) * bcb + (int64_t)v * VB;
-      if (cb >= kb) continue;
-      V val = zero_bytes<VB>();
+    uint8_t *orow = X_out + i * br * ldb + j0 * bcb;
+    for (int w = lane; w < vrow; w += 64) {
+      const int c = w / vpb, v = w - c * vpb;
+      const int64_t cb = (int64_t)c * bcb + (int64_t)v * VB;      // byte column inside the chunk
+      if (j0 * bcb + cb >= kb) continue;
       const int32_t p = slot[c];
-      if (p >= 0) val = *reinterpret_cast<const V *>(values + ((int64_t)p * br + r) * bcb + (int64_t)v * VB);
-      *reinterpret_cast<V *>(X_out + (i * br + r) * ldb + cb) = val;
+      const uint8_t *src = values + (int64_t)(p < 0 ? 0 : p) * block_bytes + (int64_t)v * VB;
+      for (int r0 = rg; r0 < rows; r0 += 4 * kInFlight) {
+        V val[kInFlight];
+#pragma unroll
+        for (int b = 0; b < kInFlight; ++b) {
+          const int r = r0 + 4 * b;
+          val[b] = zero_bytes<VB>();
+          if (p >= 0 && r < rows) val[b] = *reinterpret_cast<const V *>(src + (int64_t)r * bcb);
+        }
+#pragma unroll
+        for (int b = 0; b < kInFlight; ++b) {
+          const int r = r0 + 4 * b;
+          if (r < rows) *reinterpret_cast<V *>(orow + (int64_t)r * ldb + cb) = val[b];
+        }
+      }
     }
     __syncthreads();
   }

@@ -48,13 +48,26 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
         const int64_t col = col0 + (int64_t)u * V;
         if (col >= K) break;
         const T *p = X + m0 * ldx + col;
-#pragma unroll 4
-        for (int r = gr; r < rows; r += g.gb) {
-          const Vec<T, V> v = *reinterpret_cast<const Vec<T, V> *>(p + (int64_t)r * ldx);
+        // kInFlight loads are issued before the first of them is consumed (the
+        // kernel is bound by memory latency, not arithmetic); the order of the
+        // additions stays r ascending, whatever the batching
+        constexpr int kInFlight = 8;
+        for (int r0 = gr; r0 < rows; r0 += kInFlight * g.gb) {
+          Vec<T, V> v[kInFlight];
 #pragma unroll
-          for (int q = 0; q < V; ++q) {
-            const double x = (double)elem_to_float<T>(v.e[q]);
-            acc = fma(x, x, acc);
+          for (int b = 0; b < kInFlight; ++b) {
+            const int r = r0 + b * g.gb;
+            if (r < rows) v[b] = *reinterpret_cast<const Vec<T, V> *>(p + (int64_t)r * ldx);
+          }
+#pragma unroll
+          for (int b = 0; b < kInFlight; ++b) {
+            if (r0 + b * g.gb < rows) {
+#pragma unroll
+              for (int q = 0; q < V; ++q) {
+                const double x = (double)elem_to_float<T>(v[b].e[q]);
+                acc = fma(x, x, acc);
+              }
+            }
           }
         }
       }
@@ -83,8 +96,12 @@ int run_score(const void *X, int64_t M, int64_t K, int64_t ldx, int br, int bc, 
   ScoreGeom g;
   const int vpb = bc / V;
   g.vpbt = vpb < kScoreThreads ? vpb : kScoreThreads;
-  g.jc = kScoreThreads / g.vpbt;
-  if (g.jc > nbc) g.jc = (int)nbc;
+  // about one wave across the chunk (a 1 KB row segment per load instruction), the
+  // other waves of the workgroup as row groups: many workgroups, few rows per
+  // thread, so that all of a thread's loads are in flight at once
+  // (a matrix row of at most two waves stays in one piece)
+  g.jc = g.vpbt >= 64 ? 1 : 64 / g.vpbt;
+  if (nbc * g.vpbt <= 128 || g.jc > nbc) g.jc = (int)nbc;
   g.vct = g.jc * g.vpbt;
   const int groups = kScoreThreads / g.vct;      // >= 1
   g.gb = groups < br ? groups : br;
