@@ -42,7 +42,10 @@ def parse():
     p.add_argument("--batch", type=int, default=128)
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--phase-reps", type=int, default=5)
-    p.add_argument("--streams", type=int, default=4,
+    p.add_argument("--graph", action="store_true",
+                   help="capture the step once into a HIP graph and replay it in the timed region "
+                        "(same work; measured equal to eager enqueue: the step is GPU-bound)")
+    p.add_argument("--streams", type=int, default=6,
                    help="HIP streams (default priority) the independent tensors of a step are spread over")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run a plain 256 MiB device copy (known traffic) for scaling rocprofv3 byte counters")
@@ -129,10 +132,10 @@ def main():
     # short dependent kernels of one tensor overlap with the others'.  Stream i waits for
     # the main stream at the start of a step and the main stream waits for every stream
     # at its end, so the step is still one unit of work on the main stream.
-    main_stream = torch.cuda.current_stream()
     side = [torch.cuda.Stream() for _ in range(max(args.streams, 1))] if args.streams > 1 else []
 
     def step():
+        main_stream = torch.cuda.current_stream()
         if not side:
             for t in tensors:
                 for _, f in phases:
@@ -158,12 +161,28 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # About 250 kernel launches behind 144 calls through ctypes per step: the host needs about
+    # 2 ms to enqueue them, less than the GPU needs to run them, so the step is GPU-bound.
+    # --graph replays a captured HIP graph of the step instead (the library only launches
+    # kernels on the stream it is given, so every call is capturable); same work, same time.
+    step()                                       # eager once: library loaded, workspaces touched
+    torch.cuda.synchronize()
+    h0 = time.perf_counter()
+    step()
+    host_enqueue_ms = (time.perf_counter() - h0) * 1e3     # host side of one eager step (enqueue only)
+    torch.cuda.synchronize()
+    run_step = step
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run_step = graph.replay
     for _ in range(args.warmup):
-        step()
+        run_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -243,6 +262,7 @@ def main():
         "config": {"workload": f"ResMLP-S12 full activation set, batch {args.batch}, {args.layers} layers x "
                                "(xpatch 14x14, fc1 32x32, fc2 32x32), bf16, keep 0.5",
                    "tensors_per_step": len(tensors), "keep": keep, "streams": max(args.streams, 1),
+                   "launch": "hip graph replay" if args.graph else "eager",
                    "step": "score+select -> compress -> decompress -> dW for every tensor"},
         "phases": {
             "compress_GBps": round(comp_alg_bytes / (comp_ms * 1e-3) / 1e9, 2),
@@ -261,6 +281,7 @@ def main():
                               "bytes_per_step": comp_alg_bytes},
         "activation_memory": {"dense_MiB": round(dense_bytes / 2 ** 20, 2), "bsr_MiB": round(bsr_bytes / 2 ** 20, 2),
                               "saved_frac": round(1.0 - bsr_bytes / dense_bytes, 4)},
+        "host_enqueue_ms": round(host_enqueue_ms, 3),
         "input_generation_s": round(t_gen, 1),
     }
 
