@@ -202,6 +202,21 @@ def main():
     for name, f in phases:
         phase_ms[name] = timed(lambda: [f(t) for t in tensors], args.phase_reps)
 
+    # ---- next row: the paper's local ranking (groups of block-rows select on their own) ----
+    # One sample has 196 rows: 14 block-rows of 14 for the cross-patch input; 32 does not divide
+    # 196, so fc1 / fc2 use groups of 8 samples = 49 block-rows.  Not part of the timed step.
+    mask_g = torch.empty(max(t["spec"].nblocks for t in tensors), dtype=torch.uint8, device=dev)
+
+    def group_rows(s):
+        return 14 if s.br == 14 else 49
+
+    def score_select_grouped(t):
+        s = t["spec"]
+        B.bsr_score_select_grouped(t["X"], s.br, s.bc, group_rows(s), s.keep, keep_mask=mask_g[:s.nblocks],
+                                   ws=t["ws"])
+
+    grouped_ms = timed(lambda: [score_select_grouped(t) for t in tensors], args.phase_reps)
+
     # ---- the dominant kernel: one event pair around every dW launch ----
     def per_launch_ms(fn, group):
         pairs = []
@@ -279,6 +294,9 @@ def main():
                               "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                               "frac": round(comp_alg_bytes / (comp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 5),
                               "bytes_per_step": comp_alg_bytes},
+        "next_rows": {"per_sample_score_select": {"ms_per_step": round(grouped_ms, 4),
+                                                 "group_block_rows": {"xpatch": 14, "fc1": 49, "fc2": 49},
+                                                 "vs_whole_matrix_ms": round(phase_ms["score_select"], 4)}},
         "activation_memory": {"dense_MiB": round(dense_bytes / 2 ** 20, 2), "bsr_MiB": round(bsr_bytes / 2 ** 20, 2),
                               "saved_frac": round(1.0 - bsr_bytes / dense_bytes, 4)},
         "host_enqueue_ms": round(host_enqueue_ms, 3),

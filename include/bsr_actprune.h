@@ -117,6 +117,34 @@ int bsr_score_select(const void *X, int dtype, int64_t M, int64_t K,
                      void *stream);
 
 /*
+ * Host, pure.  Total number of kept blocks when the blocks are ranked in
+ * groups of `group_rows` consecutive block-rows (Sec. IV: blocks are compared
+ * only inside one activation of the mini-batch, so every activation keeps the
+ * same number of blocks): the sum over the groups of
+ * bsr_keep_count(blocks of the group, keep); the last group may have fewer
+ * block-rows.  nbr, nbc = block-rows / block-columns of the matrix.  Returns -1
+ * on invalid arguments (group_rows < 1, negative sizes, keep outside [0,1]).
+ */
+int64_t bsr_grouped_keep_count(int64_t nbr, int64_t nbc, int64_t group_rows,
+                               double keep);
+
+/*
+ * Sec. IV, local ranking: like bsr_score_select, but the matrix is cut into
+ * ranking groups of `group_rows` consecutive block-rows (for instance the
+ * block-rows of one sample, or of a few samples when a sample's rows are not a
+ * multiple of br) and every group keeps the bsr_keep_count(its blocks, keep)
+ * best of its own blocks; ties go to the lower linear block index.  The mask
+ * then holds bsr_grouped_keep_count(nbr, nbc, group_rows, keep) ones and feeds
+ * bsr_compress unchanged.  group_rows >= nbr is the ungrouped selection.
+ * Workspace: bsr_workspace_bytes(BSR_OP_SCORE_SELECT, ...).  Same argument
+ * rules and error codes as bsr_score_select; group_rows < 1 -> BSR_ERR_SHAPE.
+ */
+int bsr_score_select_grouped(const void *X, int dtype, int64_t M, int64_t K,
+                             int64_t ldx, int br, int bc, int64_t group_rows,
+                             double keep, double *scores, uint8_t *keep_mask,
+                             void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Sec. III / Sec. II-A: "the activation tensor is converted to the BSR
  * format".  From X and a keep mask with exactly n_keep ones build
  *   row_ptr [nbr+1] : running count of kept blocks per block-row (crow);

@@ -53,6 +53,8 @@ def _load():
         lib.oracle_block_scores.argtypes = [vp, i32, i64, i64, i64, i32, i32, vp]
         lib.oracle_select.restype = i32
         lib.oracle_select.argtypes = [vp, i64, i64, vp]
+        lib.oracle_select_grouped.argtypes = [vp, i64, i64, i64, dbl, vp]
+        lib.oracle_select_grouped.restype = i64
         lib.oracle_mask_dense.restype = None
         lib.oracle_mask_dense.argtypes = [vp, i32, i64, i64, i64, i32, i32, vp, vp, i64]
         lib.oracle_bsr_from_mask.restype = None
@@ -124,6 +126,20 @@ def select(scores: np.ndarray, n_keep: int) -> np.ndarray:
     if _load().oracle_select(_p(scores), scores.size, int(n_keep), _p(mask)) != 0:
         raise MemoryError
     return mask
+
+
+def select_grouped(scores: np.ndarray, nbr: int, nbc: int, group_rows: int, keep: float):
+    """Per-group selection (groups of `group_rows` block-rows) -> (mask, total kept)."""
+    scores = np.ascontiguousarray(scores, dtype=np.float64)
+    if scores.size != nbr * nbc:
+        raise ValueError("scores must have nbr * nbc entries")
+    mask = np.empty(scores.size, dtype=np.uint8)
+    total = int(_load().oracle_select_grouped(_p(scores), int(nbr), int(nbc), int(group_rows), float(keep), _p(mask)))
+    if total == -1:
+        raise MemoryError
+    if total < 0:
+        raise ValueError("bad group size or keep ratio")
+    return mask, total
 
 
 def mask_dense(X: np.ndarray, br: int, bc: int, mask: np.ndarray) -> np.ndarray:

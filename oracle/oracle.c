@@ -160,6 +160,30 @@ int oracle_select(const double *scores, int64_t nblocks, int64_t n_keep,
   return 0;
 }
 
+/* Sec. IV, locality of the selection: the paper ranks the blocks of each
+ * activation of the mini-batch on their own, not the whole batch at once.  Here
+ * a ranking group is `group_rows` consecutive block-rows (the block-rows of one
+ * sample, or of a few samples); every group keeps the
+ * ceil(keep * blocks of the group) best of its own blocks, ties to the lowest
+ * linear index as everywhere.  The last group may have fewer block-rows.
+ * Returns the total number of kept blocks, -1 when out of memory, -2 for a bad
+ * argument. */
+int64_t oracle_select_grouped(const double *scores, int64_t nbr, int64_t nbc,
+                              int64_t group_rows, double keep, uint8_t *mask) {
+  if (group_rows <= 0 || nbr < 0 || nbc < 0) return -2;
+  int64_t total = 0;
+  for (int64_t i0 = 0; i0 < nbr; i0 += group_rows) {
+    int64_t rows = nbr - i0 < group_rows ? nbr - i0 : group_rows;
+    int64_t blocks = rows * nbc;
+    int64_t n_keep = oracle_keep_count(blocks, keep);
+    if (n_keep < 0) return -2;
+    if (oracle_select(scores + i0 * nbc, blocks, n_keep, mask + i0 * nbc) != 0)
+      return -1;
+    total += n_keep;
+  }
+  return total;
+}
+
 /* Sec. III: the selected (lowest) blocks are forced to zero.  Xhat gets the
  * bits of X inside kept blocks and +0.0 elsewhere. */
 void oracle_mask_dense(const void *X, int dtype, int64_t M, int64_t K,

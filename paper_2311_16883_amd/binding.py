@@ -28,7 +28,7 @@ LIB_PATH = _PKG / "libbsr_actprune.so"
 EXPORTS = (
     "bsr_version", "bsr_error_string", "bsr_last_hip_error", "bsr_keep_count",
     "bsr_storage_bytes", "bsr_workspace_bytes", "bsr_score_select", "bsr_compress",
-    "bsr_decompress", "bsr_t_dense_matmul",
+    "bsr_decompress", "bsr_t_dense_matmul", "bsr_grouped_keep_count", "bsr_score_select_grouped",
 )
 
 
@@ -65,6 +65,10 @@ def lib() -> C.CDLL:
     l.bsr_storage_bytes.argtypes = [i64, i64, i32, i32, i64, i32]
     l.bsr_workspace_bytes.restype = sz
     l.bsr_workspace_bytes.argtypes = [i32, i64, i64, i64, i32, i32, i32]
+    l.bsr_grouped_keep_count.restype = i64
+    l.bsr_grouped_keep_count.argtypes = [i64, i64, i64, dbl]
+    l.bsr_score_select_grouped.restype = i32
+    l.bsr_score_select_grouped.argtypes = [vp, i32, i64, i64, i64, i32, i32, i64, dbl, vp, vp, vp, sz, vp]
     l.bsr_score_select.restype = i32
     l.bsr_score_select.argtypes = [vp, i32, i64, i64, i64, i32, i32, dbl, vp, vp, vp, sz, vp]
     l.bsr_compress.restype = i32
@@ -174,6 +178,33 @@ def bsr_score_select(X: torch.Tensor, br: int, bc: int, keep: float, *,
                                 _ptr(keep_mask), _ptr(ws), ws.numel() if ws is not None else 0,
                                 _stream(stream))
     _check(rc, "bsr_score_select")
+    return (keep_mask, scores) if scores is not None else keep_mask
+
+
+def bsr_grouped_keep_count(nbr: int, nbc: int, group_rows: int, keep: float) -> int:
+    n = int(lib().bsr_grouped_keep_count(int(nbr), int(nbc), int(group_rows), float(keep)))
+    if n < 0:
+        raise BsrError(BSR_ERR_KEEP, "bsr_grouped_keep_count")
+    return n
+
+
+def bsr_score_select_grouped(X: torch.Tensor, br: int, bc: int, group_rows: int, keep: float, *,
+                             scores: Optional[torch.Tensor] = None, want_scores: bool = False,
+                             keep_mask: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+                             stream=None):
+    """-> keep_mask (uint8 [nblocks]) or (keep_mask, scores); ranking groups of group_rows block-rows."""
+    M, K, ldx = _dense2d(X, "X")
+    nblocks = (-(-M // br)) * (-(-K // bc)) if br > 0 and bc > 0 else 0
+    if scores is None and want_scores:
+        scores = torch.empty(nblocks, dtype=torch.float64, device=X.device)
+    if keep_mask is None:
+        keep_mask = torch.empty(nblocks, dtype=torch.uint8, device=X.device)
+    code = dtype_code(X.dtype)
+    ws = _workspace(bsr_workspace_bytes(BSR_OP_SCORE_SELECT, M, K, 0, br, bc, code), X.device, ws)
+    rc = lib().bsr_score_select_grouped(_ptr(X), code, M, K, ldx, br, bc, int(group_rows), float(keep),
+                                        _ptr(scores), _ptr(keep_mask), _ptr(ws),
+                                        ws.numel() if ws is not None else 0, _stream(stream))
+    _check(rc, "bsr_score_select_grouped")
     return (keep_mask, scores) if scores is not None else keep_mask
 
 

@@ -130,6 +130,41 @@ int bsr_score_select(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx
   return launch_select(sc, g.nblocks, n_keep, keep_mask, static_cast<char *>(ws) + scores_bytes(g.nblocks), s);
 }
 
+int64_t bsr_grouped_keep_count(int64_t nbr, int64_t nbc, int64_t group_rows, double keep) {
+  if (nbr < 0 || nbc < 0 || group_rows < 1 || !(keep >= 0.0 && keep <= 1.0)) return -1;
+  if (nbr == 0 || nbc == 0) return 0;
+  const int64_t groups = (nbr + group_rows - 1) / group_rows;
+  const int64_t last_rows = nbr - (groups - 1) * group_rows;
+  const int64_t full = groups > 1 ? bsr_keep_count(group_rows * nbc, keep) : 0;
+  return (groups - 1) * full + bsr_keep_count(last_rows * nbc, keep);
+}
+
+int bsr_score_select_grouped(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int br, int bc,
+                             int64_t group_rows, double keep, double *scores, uint8_t *keep_mask,
+                             void *ws, size_t ws_bytes, void *stream) {
+  Geometry g;
+  int rc = check_shape(dtype, M, K, ldx, br, bc, &g);
+  if (rc != BSR_OK) return rc;
+  if (group_rows < 1) return BSR_ERR_SHAPE;
+  if (!(keep >= 0.0 && keep <= 1.0)) return BSR_ERR_KEEP;
+  if (g.nblocks == 0) return BSR_OK;
+  if (X == nullptr || keep_mask == nullptr) return BSR_ERR_NULL;
+  if (misaligned(X, elem_bytes(dtype)) || misaligned(scores, 8) || misaligned(ws, 16)) return BSR_ERR_ALIGN;
+  const size_t need = score_select_ws(g.nblocks);
+  if (ws == nullptr || ws_bytes < need) return BSR_ERR_WORKSPACE;
+  if (group_rows > g.nbr) group_rows = g.nbr;
+  const int64_t groups = (g.nbr + group_rows - 1) / group_rows;
+  const int64_t last_rows = g.nbr - (groups - 1) * group_rows;
+  const int64_t n_keep_group = bsr_keep_count(group_rows * g.nbc, keep);
+  const int64_t n_keep_last = bsr_keep_count(last_rows * g.nbc, keep);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  double *sc = scores != nullptr ? scores : static_cast<double *>(ws);
+  rc = launch_score(X, dtype, M, K, ldx, br, bc, sc, s);
+  if (rc != BSR_OK) return rc;
+  return launch_select_grouped(sc, g.nbr, g.nbc, group_rows, n_keep_group, n_keep_last, keep_mask,
+                               static_cast<char *>(ws) + scores_bytes(g.nblocks), s);
+}
+
 int bsr_compress(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int br, int bc,
                  const uint8_t *keep_mask, int64_t n_keep, int32_t *row_ptr, int32_t *col_idx,
                  void *values, void *ws, size_t ws_bytes, void *stream) {

@@ -46,6 +46,11 @@ size_t select_ws_bytes(int64_t nblocks);
 int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t *keep_mask, void *ws,
                   hipStream_t s);
 
+// per-group selection: groups of group_rows block-rows, n_keep_group kept per full group
+int launch_select_grouped(const double *scores, int64_t nbr, int64_t nbc, int64_t group_rows,
+                          int64_t n_keep_group, int64_t n_keep_last, uint8_t *keep_mask, void *ws,
+                          hipStream_t s);
+
 // pack.hip
 int launch_index_build(const uint8_t *keep_mask, int64_t nbr, int64_t nbc, int64_t n_keep,
                        int32_t *row_ptr, int32_t *col_idx, hipStream_t s);

@@ -7,12 +7,17 @@
 // becomes one quiet-NaN pattern above +inf), so all arithmetic is integer and
 // the result is the same on every run.
 //
-// Small inputs: one workgroup runs a most-significant-digit-first radix select
-// (12-bit digits) on the 96-bit rank value C = key * 2^32 + (nblocks-1-index):
-// histogram of the current digit over the blocks that still match the chosen
-// prefix, suffix scan for the digit holding the n_keep-th element, repeat; once
-// the matching set fits in LDS it is ranked exactly by counting, which settles
-// ties through the index part of C.
+// Building blocks.  radix_select: one workgroup, most-significant-digit-first
+// radix select (12-bit digits) on the 96-bit rank value
+// C = key * 2^32 + (nblocks-1-index): histogram of the current digit over the
+// elements that still match the chosen prefix, suffix scan for the digit holding
+// the n_keep-th element, repeat; once the matching set fits in LDS it is ranked
+// exactly by counting, which settles ties through the index part of C.  It works
+// for any input and is the fallback of bracketed_select, which is much faster
+// when the caller can bracket the threshold's key (see there).
+//
+// Small inputs (<= 8192 blocks) and per-group selection: one workgroup per
+// ranking group, bracketed_select between the group's smallest and largest key.
 //
 // Large inputs: two grid-wide passes.
 //   pass 1  every workgroup draws the same small sample, takes from it two order
@@ -172,14 +177,6 @@ __device__ void radix_select(const Source &src, uint32_t n, uint32_t want, uint3
   rank_candidates<THREADS>(sh, sh.n, want, mask);
 }
 
-__global__ __launch_bounds__(1024) void select_small_kernel(const double *__restrict__ scores,
-                                                            uint32_t nblocks, uint32_t n_keep,
-                                                            uint8_t *__restrict__ mask) {
-  __shared__ SelectShared sh;
-  AllScores src{scores};
-  radix_select<1024>(src, nblocks, n_keep, nblocks, mask, sh);
-}
-
 // Selection with a bracket.  The caller knows (or hopes) that the want-th best
 // of the n elements of `src` has its key inside [lo, hi].  Keys above hi are only
 // counted; keys inside get a 32-bit code, 1 + ((key - lo) >> shift), that stays
@@ -218,6 +215,29 @@ __device__ __forceinline__ void rank_candidates(SelectShared &sh, uint32_t m, ui
       }
       if (live) mask[idx] = better < want ? 1 : 0;
     }
+    return;
+  }
+  if (m <= (uint32_t)THREADS) {
+    // the m x m comparisons are spread over all threads: `parts` threads share one
+    // candidate, each counts over its own range of opponents
+    const uint32_t parts = (uint32_t)THREADS / m, chunk = (m + parts - 1) / parts;
+    for (uint32_t c = t; c < m; c += THREADS) sh.hist[c] = 0;
+    __syncthreads();
+    const uint32_t c = (uint32_t)t % m, part = (uint32_t)t / m;
+    if (part < parts) {
+      const uint64_t k = sh.ckey[c];
+      const uint32_t idx = sh.cidx[c];
+      const uint32_t o0 = part * chunk, o1 = (o0 + chunk) < m ? (o0 + chunk) : m;
+      uint32_t better = 0;
+#pragma unroll 4
+      for (uint32_t o = o0; o < o1; ++o) {
+        const uint64_t ok = sh.ckey[o];
+        better += (ok > k || (ok == k && sh.cidx[o] < idx)) ? 1u : 0u;
+      }
+      if (better) atomicAdd(&sh.hist[c], better);
+    }
+    __syncthreads();
+    if ((uint32_t)t < m) mask[sh.cidx[t]] = sh.hist[t] < want ? 1 : 0;
     return;
   }
   for (uint32_t c = t; c < m; c += THREADS) {
@@ -342,6 +362,57 @@ __device__ void bracketed_select(const Source &src, uint32_t n, uint32_t want_to
   }
   __syncthreads();
   rank_candidates<THREADS>(sh, sh.n, want, mask);
+}
+
+// Per-group selection (paper Sec. IV: blocks are only compared inside one
+// activation of the mini-batch): a ranking group is `group_blocks` consecutive
+// blocks in linear order (whole block-rows); workgroup g selects inside group g
+// with indices local to the group.  The group's smallest and largest key serve
+// as the bracket of bracketed_select: codes linear in the key, a radix pass or
+// two, exact ranking of what shares the threshold's code.  The last group may be
+// shorter (last_blocks, keeping n_keep_last).
+template <int THREADS, int KPT, int DB>
+__global__ __launch_bounds__(THREADS) void select_groups_kernel(
+    const double *__restrict__ scores, uint32_t group_blocks, uint32_t n_keep_group, uint32_t last_blocks,
+    uint32_t n_keep_last, uint8_t *__restrict__ mask) {
+  __shared__ SelectShared sh;
+  __shared__ BracketShared bs;
+  __shared__ uint64_t wave_min[THREADS / 64], wave_max[THREADS / 64];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const bool last = blockIdx.x == gridDim.x - 1;
+  const uint32_t n = last ? last_blocks : group_blocks;
+  const uint32_t want = last ? n_keep_last : n_keep_group;
+  const size_t off = (size_t)blockIdx.x * group_blocks;
+  uint8_t *gmask = mask + off;
+  if (want == 0 || want >= n) {
+    for (uint32_t e = t; e < n; e += THREADS) gmask[e] = want > 0 ? 1 : 0;
+    return;
+  }
+  AllScores src{scores + off};
+  uint64_t mn = ~0ull, mx = 0ull;
+#pragma unroll
+  for (int i = 0; i < KPT; ++i) {
+    const uint32_t e = (uint32_t)(t + i * THREADS);
+    if (e < n) {
+      const uint64_t k = src.key(e);
+      mn = k < mn ? k : mn;
+      mx = k > mx ? k : mx;
+    }
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    const uint64_t a = __shfl_xor(mn, d, 64), b = __shfl_xor(mx, d, 64);
+    mn = a < mn ? a : mn;
+    mx = b > mx ? b : mx;
+  }
+  if (lane == 0) { wave_min[wave] = mn; wave_max[wave] = mx; }
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < THREADS / 64; ++w) {
+    mn = wave_min[w] < mn ? wave_min[w] : mn;
+    mx = wave_max[w] > mx ? wave_max[w] : mx;
+  }
+  bracketed_select<THREADS, KPT, DB>(src, n, want, mn, mx, n, gmask, sh, bs);
 }
 
 // Control block shared by the two grid-wide passes (lives in the workspace;
@@ -558,7 +629,7 @@ __global__ void fill_u8_kernel(uint8_t *p, int64_t n, uint8_t v) {
     p[i] = v;
 }
 
-constexpr int64_t kSmallLimit = 8192;      // one workgroup, keys re-read from memory per pass
+constexpr int64_t kSmallLimit = 8192;      // one workgroup (8 keys per thread)
 
 constexpr int kMaxGridWgs = 256;
 
@@ -592,8 +663,13 @@ int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t
     return check_launch();
   }
   if (nblocks <= kSmallLimit) {
-    hipLaunchKernelGGL(select_small_kernel, dim3(1), dim3(1024), 0, s, scores, (uint32_t)nblocks,
-                       (uint32_t)n_keep, keep_mask);
+    // one workgroup: the per-group kernel with a single group
+    if (nblocks <= 1024)
+      hipLaunchKernelGGL((select_groups_kernel<256, 4, 8>), dim3(1), dim3(256), 0, s, scores, (uint32_t)nblocks,
+                         (uint32_t)n_keep, (uint32_t)nblocks, (uint32_t)n_keep, keep_mask);
+    else
+      hipLaunchKernelGGL((select_groups_kernel<1024, 8, kDigitBits>), dim3(1), dim3(1024), 0, s, scores,
+                         (uint32_t)nblocks, (uint32_t)n_keep, (uint32_t)nblocks, (uint32_t)n_keep, keep_mask);
     return check_launch();
   }
   const SelectPlan p = select_plan(nblocks);
@@ -616,6 +692,35 @@ int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t
   hipLaunchKernelGGL(select_classify_kernel, dim3((unsigned)wgs), dim3(kGridThreads), 0, s, scores,
                      (uint32_t)nblocks, (uint32_t)n_keep, per_wg, counts, ctrl, cand_key, cand_idx,
                      keep_mask);
+  return check_launch();
+}
+
+int launch_select_grouped(const double *scores, int64_t nbr, int64_t nbc, int64_t group_rows,
+                          int64_t n_keep_group, int64_t n_keep_last, uint8_t *keep_mask, void *ws,
+                          hipStream_t s) {
+  if (nbr == 0 || nbc == 0) return BSR_OK;
+  const int64_t groups = ceil_div(nbr, group_rows);
+  const int64_t group_blocks = group_rows * nbc;
+  const int64_t last_blocks = (nbr - (groups - 1) * group_rows) * nbc;
+  if (groups == 1) return launch_select(scores, last_blocks, n_keep_last, keep_mask, ws, s);
+  if (group_blocks > kSmallLimit) {
+    // large groups: the grid-wide selection, one group after the other on the stream
+    for (int64_t g = 0; g < groups; ++g) {
+      const bool last = g == groups - 1;
+      const int rc = launch_select(scores + g * group_blocks, last ? last_blocks : group_blocks,
+                                   last ? n_keep_last : n_keep_group, keep_mask + g * group_blocks, ws, s);
+      if (rc != BSR_OK) return rc;
+    }
+    return BSR_OK;
+  }
+  if (group_blocks <= 1024)
+    hipLaunchKernelGGL((select_groups_kernel<256, 4, 8>), dim3((unsigned)groups), dim3(256), 0, s, scores,
+                       (uint32_t)group_blocks, (uint32_t)n_keep_group, (uint32_t)last_blocks,
+                       (uint32_t)n_keep_last, keep_mask);
+  else
+    hipLaunchKernelGGL((select_groups_kernel<1024, 8, kDigitBits>), dim3((unsigned)groups), dim3(1024), 0, s,
+                       scores, (uint32_t)group_blocks, (uint32_t)n_keep_group, (uint32_t)last_blocks,
+                       (uint32_t)n_keep_last, keep_mask);
   return check_launch();
 }
 

@@ -94,3 +94,26 @@ def test_s24_sweep_samples(name):
 @pytest.mark.parametrize("hot_first", [False, True])
 def test_b24_fc2_skewed_norms(hot_first):
     run_case(synth.b24_fc2(hot_first=hot_first)[0], 50 + int(hot_first), samples=128)
+
+
+def test_s12_layer_per_sample_selection():
+    """The paper's local ranking at the benchmark's shapes: one group per sample for the cross-patch
+    input (14 block-rows of 14), groups of 8 samples (49 block-rows of 32) for fc1 / fc2."""
+    for i, spec in enumerate(synth.s12_layer(128)):
+        g = 14 if spec.br == 14 else 49
+        X, _ = synth.make_pair(spec, 60 + i)
+        o_scores = oracle.block_scores(X, spec.br, spec.bc)
+        o_mask, total = oracle.select_grouped(o_scores, spec.nbr, spec.nbc, g, spec.keep)
+        Xd = to_dev(X)
+        mask = B.bsr_score_select_grouped(Xd, spec.br, spec.bc, g, spec.keep)
+        row_ptr, col_idx, values = B.bsr_compress(Xd, spec.br, spec.bc, mask, total)
+        torch.cuda.synchronize()
+        assert B.bsr_grouped_keep_count(spec.nbr, spec.nbc, g, spec.keep) == total
+        assert np.array_equal(mask.cpu().numpy(), o_mask)
+        o_rp, o_ci, o_val = oracle.bsr_from_mask(X, spec.br, spec.bc, o_mask)
+        assert np.array_equal(row_ptr.cpu().numpy(), o_rp)
+        assert np.array_equal(col_idx.cpu().numpy(), o_ci)
+        assert to_host(values).tobytes() == o_val.tobytes()
+        # every full group keeps the same number of blocks (equal nnz per sample)
+        per_group = o_mask[: (spec.nbr // g) * g * spec.nbc].reshape(-1, g * spec.nbc).sum(axis=1)
+        assert len(set(per_group.tolist())) == 1

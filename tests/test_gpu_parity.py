@@ -187,6 +187,40 @@ def test_grid_wide_selection_large(keep):
     check_forward(X, 4, 4, keep, "524288 blocks")
 
 
+@pytest.mark.parametrize("M,K,br,bc,group_rows,keep", [
+    (2744, 196, 14, 14, 14, 0.5),        # 14 samples of 196 patches, one group per sample (196 blocks each)
+    (6272, 384, 32, 32, 49, 0.5),        # groups of 8 samples (1568 rows = 49 block-rows, 588 blocks)
+    (6272, 1536, 32, 32, 49, 0.25),      # 2352 blocks per group: the 1024-thread workgroups
+    (1000, 200, 8, 8, 7, 0.3),           # ragged rows / columns, ragged last group
+    (8192, 512, 16, 16, 300, 0.5),       # 9600 blocks per group: grid-wide selection group after group
+    (512, 128, 16, 16, 64, 0.6),         # one group: the ungrouped selection
+])
+def test_grouped_selection_parity(M, K, br, bc, group_rows, keep):
+    """Sec. IV, local ranking: groups of block-rows select on their own; mask, counts and the BSR
+    built from the mask against the oracle, plus constant and small-integer inputs for the ties."""
+    rng = np.random.default_rng(M + K + group_rows)
+    nbr, nbc = oracle.grid(M, K, br, bc)
+    inputs = [synth.f32_to_bf16_bits(rng.standard_normal((M, K), dtype=np.float32)),
+              synth.f32_to_bf16_bits(rng.integers(-1, 2, size=(M, K)).astype(np.float32)),
+              synth.f32_to_bf16_bits(np.full((M, K), 0.75, dtype=np.float32))]
+    for X in inputs:
+        o_scores = oracle.block_scores(X, br, bc)
+        o_mask, total = oracle.select_grouped(o_scores, nbr, nbc, group_rows, keep)
+        assert B.bsr_grouped_keep_count(nbr, nbc, group_rows, keep) == total
+        Xd = to_dev(X)
+        mask = B.bsr_score_select_grouped(Xd, br, bc, group_rows, keep)
+        row_ptr, col_idx, values = B.bsr_compress(Xd, br, bc, mask, total)
+        torch.cuda.synchronize()
+        g_mask = mask.cpu().numpy()
+        if not np.array_equal(g_mask, o_mask):
+            d = np.flatnonzero(g_mask != o_mask)
+            raise AssertionError(f"grouped selection differs at blocks {d[:6]}; oracle scores {o_scores[d[:6]]}")
+        o_rp, o_ci, o_val = oracle.bsr_from_mask(X, br, bc, o_mask)
+        assert np.array_equal(row_ptr.cpu().numpy(), o_rp)
+        assert np.array_equal(col_idx.cpu().numpy(), o_ci)
+        assert to_host(values).tobytes() == o_val.tobytes()
+
+
 def test_nan_inf_and_signed_zero_blocks():
     X, _ = rand_pair(128, 128, 8, "f32", seed=3)
     X[5, 5] = np.nan

@@ -5,6 +5,7 @@ import ctypes as C
 import re
 from pathlib import Path
 
+import numpy as np
 import pytest
 
 import oracle
@@ -22,7 +23,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     syms = declared_symbols()
-    assert set(syms) == set(B.EXPORTS) and len(syms) == 10
+    assert set(syms) == set(B.EXPORTS) and len(syms) == 12
     lib = B.lib()
     for s in syms:
         assert getattr(lib, s) is not None
@@ -36,6 +37,19 @@ def test_keep_count_agrees_with_oracle():
     for bad in (-1e-9, 1.0000001, float("nan"), float("inf")):
         assert B.lib().bsr_keep_count(10, bad) == -1
     assert B.lib().bsr_keep_count(-1, 0.5) == -1
+
+
+def test_grouped_keep_count_agrees_with_oracle():
+    rng = np.random.default_rng(0)
+    for nbr, nbc, g in [(7, 5, 3), (784, 12, 49), (3511, 14, 14), (784, 48, 7), (1, 1, 1), (10, 3, 100)]:
+        for keep in (0.0, 0.1, 0.25, 1 / 3, 0.5, 0.9, 1.0):
+            _, total = oracle.select_grouped(rng.random(nbr * nbc), nbr, nbc, g, keep)
+            assert B.bsr_grouped_keep_count(nbr, nbc, g, keep) == total
+    lib = B.lib()
+    assert lib.bsr_grouped_keep_count(10, 10, 0, 0.5) == -1
+    assert lib.bsr_grouped_keep_count(-1, 10, 2, 0.5) == -1
+    assert lib.bsr_grouped_keep_count(10, 10, 2, 1.5) == -1
+    assert lib.bsr_grouped_keep_count(0, 10, 2, 0.5) == 0
 
 
 def test_storage_bytes_agree_with_oracle_and_table_2():
@@ -89,6 +103,17 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert ss(M=1 << 41) == B.BSR_ERR_SHAPE
     assert ss(M=1 << 30, K=1 << 30, ldx=1 << 30, br=1, bc=1) == B.BSR_ERR_SHAPE   # nblocks >= 2^31
     assert ss(M=0) == B.BSR_OK and ss(K=0, ldx=0) == B.BSR_OK                    # empty: nothing to do
+
+    sg = lambda **k: lib.bsr_score_select_grouped(
+        k.get("X", fake), k.get("dtype", 0), k.get("M", 64), 64, 64, 16, 16, k.get("group_rows", 2),
+        k.get("keep", 0.5), None, k.get("mask", fake), k.get("ws", fake), k.get("ws_bytes", 1 << 20), None)
+    assert sg(group_rows=0) == B.BSR_ERR_SHAPE
+    assert sg(group_rows=-3) == B.BSR_ERR_SHAPE
+    assert sg(keep=-0.5) == B.BSR_ERR_KEEP
+    assert sg(dtype=7) == B.BSR_ERR_DTYPE
+    assert sg(X=None) == B.BSR_ERR_NULL
+    assert sg(ws_bytes=8) == B.BSR_ERR_WORKSPACE
+    assert sg(M=0) == B.BSR_OK
 
     cp = lambda **k: lib.bsr_compress(
         k.get("X", fake), k.get("dtype", 1), 64, 64, 64, 16, 16, k.get("mask", fake),

@@ -173,6 +173,60 @@ def test_select_nan_and_inf_rank_highest():
     assert np.flatnonzero(oracle.select(s, 5)).tolist() == [1, 2, 3, 5, 6]
 
 
+# ----------------------------------------------------------------------------
+# per-group selection (Sec. IV: blocks are compared only inside one activation
+# of the mini-batch; every activation keeps the same number of blocks)
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(4))
+def test_grouped_select_brute_force_per_group(seed):
+    rng = np.random.default_rng(100 + seed)
+    nbc = int(rng.integers(2, 5))
+    group_rows = int(rng.integers(1, 4))
+    nbr = int(rng.integers(group_rows, 3 * group_rows + 2))      # usually a ragged last group
+    scores = rng.integers(0, 5, size=nbr * nbc).astype(np.float64)
+    for keep in (0.0, 0.3, 0.5, 1.0):
+        mask, total = oracle.select_grouped(scores, nbr, nbc, group_rows, keep)
+        assert int(mask.sum()) == total
+        for i0 in range(0, nbr, group_rows):
+            lo, hi = i0 * nbc, min(nbr, i0 + group_rows) * nbc
+            n = hi - lo
+            n_keep = oracle.keep_count(n, keep)
+            assert n_keep == int(np.ceil(keep * n))             # keeps here are exact in binary
+            got = tuple(np.flatnonzero(mask[lo:hi]))
+            assert len(got) == n_keep
+            best, best_set = -1.0, None
+            for comb in itertools.combinations(range(n), n_keep):  # lexicographic: ties -> lowest indices
+                tot = float(scores[lo:hi][list(comb)].sum())
+                if tot > best:
+                    best, best_set = tot, comb
+            assert got == best_set
+
+
+def test_grouped_select_special_cases():
+    rng = np.random.default_rng(21)
+    nbr, nbc = 13, 6
+    s = rng.random(nbr * nbc)
+    # one group (group_rows >= nbr) is the ungrouped selection
+    for g in (nbr, nbr + 5, 1000):
+        m, total = oracle.select_grouped(s, nbr, nbc, g, 0.4)
+        assert np.array_equal(m, oracle.select(s, oracle.keep_count(nbr * nbc, 0.4))) and total == int(m.sum())
+    # equal groups keep equal numbers of blocks; a group never sees the others' scores
+    m, total = oracle.select_grouped(s[:72], 12, nbc, 3, 0.5)
+    assert [int(m[g * 18:(g + 1) * 18].sum()) for g in range(4)] == [9, 9, 9, 9] and total == 36
+    s2 = s[:72].copy()
+    s2[18:36] += 10.0                                            # a "brighter" second group: same order inside it
+    m2, _ = oracle.select_grouped(s2, 12, nbc, 3, 0.5)
+    assert np.array_equal(m2, m[:72])
+    # the ungrouped selection would instead keep all of the bright group
+    assert oracle.select(s2, 36)[18:36].all()
+    # ties inside a group go to its lowest indices; rows of one block-row each
+    mt, _ = oracle.select_grouped(np.full(20, 2.0), 4, 5, 1, 0.5)
+    assert np.flatnonzero(mt).tolist() == [0, 1, 2, 5, 6, 7, 10, 11, 12, 15, 16, 17]
+    with pytest.raises(ValueError):
+        oracle.select_grouped(s, nbr, nbc, 0, 0.5)
+
+
 def test_kept_count_equals_ceil_keep_nblocks_end_to_end():
     spec = synth.tiny()[0]
     X = synth.make_x(spec, 0)
