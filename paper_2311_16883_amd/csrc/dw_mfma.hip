@@ -29,7 +29,6 @@
 // the time.  One barrier per stage hands LDS buffer q&1 from the loaders to the
 // multipliers.  With more than one split the partial tiles go to the workspace
 // and a second kernel adds them in a fixed order.
-#include <cstdlib>
 #include <utility>
 
 #include "buffer_access.h"
@@ -498,7 +497,6 @@ Plan make_plan(int64_t M, int64_t K, int64_t N) {
   p.splits = 1;
   p.stages_per_split = stages > 0 ? stages : 1;
   if (stages <= 0 || tiles <= 0) return p;
-  static const int forced = getenv("BSR_DW_SPLITS") ? atoi(getenv("BSR_DW_SPLITS")) : 0;   // development knob
   const double us_stage = 0.42 * MS / 64.0, us_round = 8.0;
   const double us_split = 2.0 * (double)K * (double)N * 4.0 / 3.0e6;
   const int64_t s_min = ceil_div(stages * R, (int64_t)kMaxRowsPerSplit);
@@ -513,7 +511,6 @@ Plan make_plan(int64_t M, int64_t K, int64_t N) {
     const double cost = (double)rounds * ((double)sps * us_stage + us_round) + (s_eff > 1 ? (double)s_eff * us_split : 0.0);
     if (best_s == 0 || cost < best) { best = cost; best_s = s_eff; }
   }
-  if (forced > 0) best_s = forced < s_min ? s_min : forced;
   const int64_t sps = ceil_div(stages, best_s);
   p.splits = (int)ceil_div(stages, sps);
   p.stages_per_split = sps;
@@ -533,7 +530,7 @@ int run(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int6
   const int64_t stride = p.splits > 1 ? K * N : 0;
   const int acc_direct = p.splits > 1 ? 0 : accumulate;
   const int tiles_k = (int)ceil_div(K, 128), tiles_n = (int)ceil_div(N, 128);
-  static const int xcd_map = getenv("BSR_DW_XCD_MAP") ? atoi(getenv("BSR_DW_XCD_MAP")) : 1;
+  const int xcd_map = 1;      // XCD-aware work item order (0 = plain order, kept for measurements)
   const int64_t n_items = (int64_t)p.splits * tiles_k * tiles_n;
   dim3 grid((unsigned)(xcd_map ? 8 * ceil_div(n_items, 8) : n_items));
   const uint16_t *v = static_cast<const uint16_t *>(values);

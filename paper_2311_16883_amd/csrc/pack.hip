@@ -6,8 +6,6 @@
 //   pack        : bit copy of the kept blocks into `values` (HBM-bound gather);
 //   decompress  : BSR -> dense, pruned positions become +0.0.
 // All three are pure data movement / integer work and are bit-exact.
-#include <cstdlib>
-
 #include "common.h"
 
 namespace bsr {
@@ -361,8 +359,7 @@ int launch_compress(const uint8_t *keep_mask, const void *X, int dtype, int64_t 
   // mask prefix in every workgroup stays cheap (nbr * nblocks / 2 bytes out of L2)
   const bool fused = nbr > 0 && nbc > 0 && nbc <= kFusedCols && nbr <= 65535 &&
                      nbr * nbr * nbc <= (int64_t(1) << 31);
-  static const bool allow = !(getenv("BSR_COMPRESS_FUSED") && atoi(getenv("BSR_COMPRESS_FUSED")) == 0);   // development knob
-  if (!fused || !allow) {
+  if (!fused) {
     int rc = launch_index_build(keep_mask, nbr, nbc, n_keep, row_ptr, col_idx, s);
     if (rc != BSR_OK) return rc;
     return launch_pack(X, dtype, M, K, ldx, br, bc, row_ptr, col_idx, n_keep, values, s);
