@@ -101,7 +101,7 @@ size_t bsr_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int br, int 
       {
         size_t a = dw_generic_ws_bytes(M, K, N, br, bc);
         if (dw_mfma_supported(dtype, br, bc, nullptr, M, K, N, N)) {
-          const size_t b = dw_mfma_ws_bytes(M, K, N, br, bc);
+          const size_t b = dw_mfma_ws_bytes(dtype, M, K, N, br, bc);
           if (b > a) a = b;
         }
         return align_up(a, 256);
@@ -215,7 +215,7 @@ int bsr_t_dense_matmul(const int32_t *row_ptr, const int32_t *col_idx, const voi
   const size_t need = bsr_workspace_bytes(BSR_OP_T_DENSE_MATMUL, M, K, N, br, bc, dtype);
   if (need > 0 && (ws == nullptr || ws_bytes < need)) return BSR_ERR_WORKSPACE;
   if (dw_mfma_supported(dtype, br, bc, values, M, K, N, lddy))
-    return launch_dw_mfma(row_ptr, col_idx, values, M, K, br, bc, dY, N, lddy, dW, lddw, accumulate,
+    return launch_dw_mfma(dtype, row_ptr, col_idx, values, M, K, br, bc, dY, N, lddy, dW, lddw, accumulate,
                           ws, ws_bytes, static_cast<hipStream_t>(stream));
   return launch_dw_generic(row_ptr, col_idx, values, dtype, M, K, br, bc, dY, N, lddy, dW, lddw,
                            accumulate, ws, ws_bytes, static_cast<hipStream_t>(stream));

@@ -71,11 +71,11 @@ int launch_dw_generic(const int32_t *row_ptr, const int32_t *col_idx, const void
                       float *dW, int64_t lddw, int accumulate, void *ws, size_t ws_bytes,
                       hipStream_t s);
 
-// dw_mfma.hip: bfloat16 on the matrix cores, block shapes 32x32, 64x64, 16x16, 14x14.
+// dw_mfma.hip: bfloat16 and binary32 on the matrix cores, block shapes 32x32, 64x64, 16x16, 14x14.
 bool dw_mfma_supported(int dtype, int br, int bc, const void *values, int64_t M, int64_t K, int64_t N,
                        int64_t lddy);
-size_t dw_mfma_ws_bytes(int64_t M, int64_t K, int64_t N, int br, int bc);
-int launch_dw_mfma(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int64_t M,
+size_t dw_mfma_ws_bytes(int dtype, int64_t M, int64_t K, int64_t N, int br, int bc);
+int launch_dw_mfma(int dtype, const int32_t *row_ptr, const int32_t *col_idx, const void *values, int64_t M,
                    int64_t K, int br, int bc, const void *dY, int64_t N, int64_t lddy, float *dW,
                    int64_t lddw, int accumulate, void *ws, size_t ws_bytes, hipStream_t s);
 

@@ -1,5 +1,7 @@
 // Weight gradient from a BSR activation on the matrix cores (paper Sec. III,
-// Fig. 2: dW = Xhat^T * dY, "BSpMM"), bfloat16 inputs, binary32 accumulation.
+// Fig. 2: dW = Xhat^T * dY, "BSpMM"), bfloat16 or binary32 inputs, binary32
+// accumulation.  The description below is for bfloat16; binary32 differs only in
+// the fragment reads (see multiply_f32).
 //
 // Both operands are stored with the contraction index m (activation rows) as
 // the slow axis -- a kept block is [r][c] with c = output row of dW, dY is
@@ -74,15 +76,19 @@ __device__ __forceinline__ v8bf read_fragment(const uint16_t *p, int ld) {
   return __builtin_bit_cast(v8bf, r);
 }
 
-// LDS tiles are 128 elements (256 bytes, all 64 banks) wide and unpadded.  The
-// transposing read fetches four consecutive rows per 16-lane group, which
-// would all hit the same banks; so the 32-byte chunk index of every element
-// is XOR-ed with twice the row's low two bits: four consecutive rows of one
-// chunk, and of the neighbouring chunk read by the next lane group, then land
-// on eight different bank groups.
+// LDS tiles are 128 elements wide and unpadded.  Two-byte elements (256-byte
+// rows, all 64 banks): the transposing read fetches four consecutive rows per
+// 16-lane group, which would all hit the same banks; so the 32-byte chunk index
+// of every element is XOR-ed with twice the row's low two bits: four consecutive
+// rows of one chunk, and of the neighbouring chunk read by the next lane group,
+// then land on eight different bank groups.  Four-byte elements (512-byte rows):
+// a fragment read takes 32 consecutive columns of two consecutive rows, which
+// would share their banks; odd rows swap their 32-column halves.
 constexpr int kLd = 128;
+template <int E>
 __device__ __forceinline__ int swizzled(int row, int col) {
-  return row * kLd + ((((col >> 4) ^ ((row & 3) << 1)) << 4) | (col & 15));
+  if (E == 2) return row * kLd + ((((col >> 4) ^ ((row & 3) << 1)) << 4) | (col & 15));
+  return row * kLd + (col ^ ((row & 1) << 5));
 }
 
 // Element offset of this lane's part of the 16-row x 32-column fragment whose
@@ -91,13 +97,14 @@ __device__ __forceinline__ int swizzled(int row, int col) {
 // 4 rows keeps the swizzle valid.
 __device__ __forceinline__ int lane_fragment_offset(int col0) {
   const int l = threadIdx.x & 63, g = l >> 4, L = l & 15;
-  return swizzled(8 * (g >> 1) + (L >> 2), col0 + 16 * (g & 1) + 4 * (L & 3));
+  return swizzled<2>(8 * (g >> 1) + (L >> 2), col0 + 16 * (g & 1) + 4 * (L & 3));
 }
 
 
 constexpr int KT = 128, NT = 128;   // dW tile of one workgroup: 2 x WN waves, 64 x (128 / WN) each
 
-template <int BR, int BC, int MS, int VB, int WN>
+// E = bytes per element of the inputs (2: bfloat16, 4: binary32).
+template <int E, int BR, int BC, int MS, int VB, int WN>
 struct Geo {
   static constexpr int THREADS = 128 * WN;                // threads per role: 2 x WN waves
   static constexpr int NTW = NT / (32 * WN);               // 32-column pieces of dW per wave along N
@@ -108,7 +115,8 @@ struct Geo {
   // every 16 x 32 piece of the activation tile lies inside one block: pruned
   // blocks are skipped outright and their LDS content is never read
   static constexpr bool SKIP_ONLY = (BC % 32 == 0) && (BR % 16 == 0) && KALIGNED;
-  static constexpr int VA = (BC % 8 == 0) ? 8 : ((BC % 4 == 0) ? 4 : ((BC % 2 == 0) ? 2 : 1));
+  // elements per activation vector: at most 16 bytes, inside one block row
+  static constexpr int VA = (E == 2 && BC % 8 == 0) ? 8 : ((BC % 4 == 0) ? 4 : ((BC % 2 == 0) ? 2 : 1));
   static constexpr int VPB = BR * BC / VA;                // vectors per block
   static constexpr int NA = (R * JT * VPB + THREADS - 1) / THREADS;
   static constexpr int NB = (ROWS * (NT / VB) + THREADS - 1) / THREADS;
@@ -117,7 +125,7 @@ struct Geo {
   // a wave-wide activation load (64 vectors) never straddles two blocks: the keep
   // decision and the block address are wave-uniform and live in scalar registers
   static constexpr bool UNIFORM_A = (VPB % 64 == 0);
-  static constexpr int STAGE_WORDS = (MS * LDA + MS * LDB) / 2;   // 32-bit words of one stage (A tile, B tile)
+  static constexpr int STAGE_WORDS = (MS * LDA + MS * LDB) * E / 4;   // 32-bit words of one stage (A tile, B tile)
   static_assert(MS % 16 == 0 && R >= 1 && MSUB <= 8, "stage shape");
   static_assert(JT <= 32, "tile index is a 32-bit mask");
 };
@@ -125,18 +133,20 @@ struct Geo {
 // D = stages whose global loads are in flight (register ring of the loaders).
 // WN = multiplier waves along N (2: 64 x 64 per wave, 4: 64 x 32 per wave); the
 // workgroup has 2 x WN multiplier waves and as many loader waves.
-template <int BR, int BC, int MS, int VB, int D, int WN>
+// T = uint16_t (bfloat16 bits) or float.
+template <typename T, int BR, int BC, int MS, int VB, int D, int WN>
 __global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(
     const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-    const uint16_t *__restrict__ values, const uint16_t *__restrict__ dY, float *__restrict__ out,
+    const T *__restrict__ values, const T *__restrict__ dY, float *__restrict__ out,
     int64_t M, int64_t K, int64_t N, int64_t lddy, int64_t ldo, int64_t split_stride, int64_t nbr,
     int64_t nbc, int64_t stages_per_split, int accumulate, int tiles_k, int tiles_n, int splits,
     int xcd_map, uint32_t values_bytes) {
-  typedef Geo<BR, BC, MS, VB, WN> G;
+  constexpr int E = (int)sizeof(T);
+  typedef Geo<E, BR, BC, MS, VB, WN> G;
   constexpr int kRole = G::THREADS;              // threads per role
   constexpr int kThreads = 2 * kRole;            // workgroup
-  typedef typename Chunk<G::VA * 2>::type AVec;
-  typedef typename Chunk<VB * 2>::type BVec;
+  typedef typename Chunk<G::VA * E>::type AVec;
+  typedef typename Chunk<VB * E>::type BVec;
 
   // Workgroup ids are dealt to the 8 XCDs round-robin (id % 8).  All tiles of one
   // split of the contraction read the same activation rows and dY rows, so the
@@ -225,7 +235,7 @@ __global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(
 #pragma unroll
     for (int jl = 0; jl < G::JT; ++jl)
       sTab[t * G::JT + jl] = ((my_mask >> jl) & 1u)
-                                 ? (uint32_t)(my_base + __popc(my_mask & ((1u << jl) - 1u))) * (uint32_t)(BR * BC * 2)
+                                 ? (uint32_t)(my_base + __popc(my_mask & ((1u << jl) - 1u))) * (uint32_t)(BR * BC * E)
                                  : kDead;
   }
   for (int e = t; e < kTail * G::JT; e += kThreads) sTab[nrows * G::JT + e] = kDead;
@@ -285,11 +295,11 @@ __global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(
       const int r = (off * G::VA) / BC, c = (off * G::VA) % BC;
       const int col = (int)((jfirst + jl) * BC - k0) + c;
       const bool used = slot < G::R * G::JT && jl < jt && col >= 0 && col + G::VA <= KT;
-      a_src[it] = (uint32_t)(off * G::VA * 2);
+      a_src[it] = (uint32_t)(off * G::VA * E);
       a_tab[it] = used ? (uint32_t)(rbk * G::JT + jl) : (uint32_t)(nrows * G::JT);
       a_inc[it] = used ? (uint32_t)(G::R * G::JT) : 0u;
       a_val[it] = sTab[a_tab[it]];
-      a_dst[it] = used ? swizzled(rbk * BR + r, col) : -1;
+      a_dst[it] = used ? swizzled<E>(rbk * BR + r, col) : -1;
     }
     // dY is addressed through one descriptor that covers exactly the rows of this
     // split (from the tile's first column on): rows past the split or the matrix
@@ -301,29 +311,30 @@ __global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(
       const int v = tg + it * kRole;
       const int r = v / (NT / VB), c = (v % (NT / VB)) * VB;
       const bool used = r < G::ROWS && n0 + c < N;
-      b_cur[it] = used ? (uint32_t)(((int64_t)r * lddy + c) * 2) : kOutOfRange;
-      b_inc[it] = used ? (uint32_t)((int64_t)G::ROWS * lddy * 2) : 0u;
-      b_dst[it] = used ? swizzled(r, c) : -1;
+      b_cur[it] = used ? (uint32_t)(((int64_t)r * lddy + c) * E) : kOutOfRange;
+      b_inc[it] = used ? (uint32_t)((int64_t)G::ROWS * lddy * E) : 0u;
+      b_dst[it] = used ? swizzled<E>(r, c) : -1;
     }
     // element offsets of the LDS stores relative to stage buffer 0 (>= kDump: the dump slot)
-    constexpr int kDump = 2 * G::STAGE_WORDS * 2;
+    constexpr int kStageElems = G::STAGE_WORDS * 4 / E;       // elements of one stage buffer
+    constexpr int kDump = 2 * kStageElems;
     int a_lds[2][G::NA], b_lds[2][G::NB];
 #pragma unroll
     for (int buf = 0; buf < 2; ++buf) {
 #pragma unroll
       for (int it = 0; it < G::NA; ++it)
-        a_lds[buf][it] = a_dst[it] >= 0 ? buf * G::STAGE_WORDS * 2 + a_dst[it] : kDump + lane * 8;
+        a_lds[buf][it] = a_dst[it] >= 0 ? buf * kStageElems + a_dst[it] : kDump + lane * (16 / E);
 #pragma unroll
       for (int it = 0; it < G::NB; ++it)
-        b_lds[buf][it] = b_dst[it] >= 0 ? buf * G::STAGE_WORDS * 2 + MS * G::LDA + b_dst[it] : kDump + lane * 8;
+        b_lds[buf][it] = b_dst[it] >= 0 ? buf * kStageElems + MS * G::LDA + b_dst[it] : kDump + lane * (16 / E);
     }
     const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(values, values_bytes);
     int64_t split_rows = (i_begin + nrows) * BR;
     if (split_rows > M) split_rows = M;
     split_rows -= i_begin * BR;                                                // dY rows of this split
-    const int64_t dy_split = split_rows > 0 ? ((split_rows - 1) * lddy + (N - n0)) * 2 : 0;
+    const int64_t dy_split = split_rows > 0 ? ((split_rows - 1) * lddy + (N - n0)) * E : 0;
     const __amdgpu_buffer_rsrc_t rsrc_b =
-        make_rsrc(reinterpret_cast<const char *>(dY) + (i_begin * BR * lddy + n0) * 2, (uint32_t)dy_split);
+        make_rsrc(reinterpret_cast<const char *>(dY) + (i_begin * BR * lddy + n0) * E, (uint32_t)dy_split);
 
     AVec ra[D][G::NA];
     BVec rb[D][G::NB];
@@ -333,17 +344,17 @@ __global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(
     // of loads in flight is known at compile time.  Each call moves the vector's
     // state on by one stage.
     auto load_a = [&](int d, int it) {
-      ra[d][it] = buffer_load<G::VA * 2>(rsrc_a, a_val[it] + a_src[it]);
+      ra[d][it] = buffer_load<G::VA * E>(rsrc_a, a_val[it] + a_src[it]);
       a_tab[it] += a_inc[it];
       a_val[it] = sTab[a_tab[it]];
     };
     auto load_b = [&](int d, int it) {
-      rb[d][it] = buffer_load<VB * 2>(rsrc_b, b_cur[it]);
+      rb[d][it] = buffer_load<VB * E>(rsrc_b, b_cur[it]);
       b_cur[it] += b_inc[it];
     };
     // Ring slot d -> LDS stage buffer `buf`; unused vectors go to the dump slot,
     // so no store needs a predicate.
-    uint16_t *const s0 = reinterpret_cast<uint16_t *>(sStage);
+    T *const s0 = reinterpret_cast<T *>(sStage);
     auto store_a = [&](int d, int it, int buf) { *reinterpret_cast<AVec *>(&s0[a_lds[buf][it]]) = ra[d][it]; };
     auto store_b = [&](int d, int it, int buf) { *reinterpret_cast<BVec *>(&s0[b_lds[buf][it]]) = rb[d][it]; };
 
@@ -392,23 +403,32 @@ __global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[u][w][r] = 0.f;
 
-  const int frag_a0 = lane_fragment_offset((2 * wk) * 32), frag_a1 = lane_fragment_offset((2 * wk + 1) * 32);
-  int frag_b[G::NTW];
-#pragma unroll
-  for (int w = 0; w < G::NTW; ++w) frag_b[w] = lane_fragment_offset((G::NTW * wn + w) * 32);
-
-  // Stage q out of LDS buffer `buf` in MSUB steps of 16 activation rows.  The
-  // fragments of step ms+1 are requested before the multiplies of step ms are
-  // issued; only the multiplies sit under the wave-uniform skip branches.  The
-  // activity bits of 64 stages sit in one register (lane = stage) and reach a
-  // scalar register through one v_readlane.
+  // Stage q out of LDS buffer `buf` in MSUB steps of 16 activation rows; only the
+  // multiplies (and for binary32 their fragment reads) sit under the wave-uniform
+  // skip branches.  The activity bits of 64 stages sit in one register (lane =
+  // stage) and reach a scalar register through one v_readlane.
   uint32_t pam_reg = 0;
-  auto multiply = [&](int q, int buf) {
-    const uint16_t *sA = reinterpret_cast<const uint16_t *>(sStage + buf * G::STAGE_WORDS);
-    const uint16_t *sB = sA + MS * G::LDA;
+  auto stage_pam = [&](int q) {
     if ((q & 63) == 0) pam_reg = sPam[q + lane];
     uint32_t pam = (uint32_t)__builtin_amdgcn_readlane((int)pam_reg, q & 63) >> (16 * wk);
     asm volatile("" : "+s"(pam));           // one scalar register, tested bit by bit below
+    return pam;
+  };
+
+  // ---- bfloat16: v_mfma_f32_32x32x16_bf16, fragments through transposing LDS reads ----
+  int frag_a0 = 0, frag_a1 = 0, frag_b[G::NTW];
+  if constexpr (E == 2) {
+    frag_a0 = lane_fragment_offset((2 * wk) * 32);
+    frag_a1 = lane_fragment_offset((2 * wk + 1) * 32);
+#pragma unroll
+    for (int w = 0; w < G::NTW; ++w) frag_b[w] = lane_fragment_offset((G::NTW * wn + w) * 32);
+  }
+  // The fragments of step ms+1 are requested before the multiplies of step ms
+  // are issued.
+  auto multiply_bf16 = [&](int q, int buf) {
+    const uint16_t *sA = reinterpret_cast<const uint16_t *>(sStage + buf * G::STAGE_WORDS);
+    const uint16_t *sB = sA + MS * G::LDA;
+    const uint32_t pam = stage_pam(q);
     v8bf fb[G::NTW], fa0, fa1;
 #pragma unroll
     for (int w = 0; w < G::NTW; ++w) fb[w] = read_fragment(sB + frag_b[w], G::LDB);
@@ -439,6 +459,56 @@ __global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(
       for (int w = 0; w < G::NTW; ++w) fb[w] = nb[w];
       fa0 = na0; fa1 = na1;
     }
+  };
+
+  // ---- binary32: v_mfma_f32_32x32x2_f32.  One instruction contracts two
+  // activation rows: lane l supplies column l % 32 of row l / 32 of the pair for
+  // both operands, which is how the row-major LDS tiles are laid out already (no
+  // transposition); a 16-row step is 8 instructions per 32 x 32 piece.  The
+  // kernel is bound by the matrix core here (16 passes per 4096 multiply-adds).
+  // this lane's element of a row pair: row lane / 32, column lane % 32 of a 32-column piece; odd rows
+  // have their 32-column halves swapped (see swizzled), so lanes 32-63 read the other half
+  const int pair_row = (lane >> 5) * kLd, pair_col = lane & 31, pair_swap = (lane >> 5) << 5;
+  auto multiply_f32 = [&](int q, int buf) {
+    const float *sA = reinterpret_cast<const float *>(sStage + buf * G::STAGE_WORDS);
+    const float *sB = sA + MS * G::LDA;
+    const uint32_t pam = stage_pam(q);
+    const int offA0 = pair_row + ((((2 * wk) * 32) ^ pair_swap) + pair_col);
+    const int offA1 = pair_row + ((((2 * wk + 1) * 32) ^ pair_swap) + pair_col);
+#pragma unroll
+    for (int ms = 0; ms < G::MSUB; ++ms) {
+      if ((pam >> (2 * ms)) & 3u) {
+        float fb[G::NTW][8];
+#pragma unroll
+        for (int w = 0; w < G::NTW; ++w) {
+          const int offB = pair_row + ((((G::NTW * wn + w) * 32) ^ pair_swap) + pair_col);
+#pragma unroll
+          for (int p = 0; p < 8; ++p) fb[w][p] = sB[(16 * ms + 2 * p) * kLd + offB];
+        }
+        if (pam & (1u << (2 * ms))) {
+#pragma unroll
+          for (int p = 0; p < 8; ++p) {
+            const float a = sA[(16 * ms + 2 * p) * kLd + offA0];
+#pragma unroll
+            for (int w = 0; w < G::NTW; ++w)
+              acc[0][w] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, fb[w][p], acc[0][w], 0, 0, 0);
+          }
+        }
+        if (pam & (2u << (2 * ms))) {
+#pragma unroll
+          for (int p = 0; p < 8; ++p) {
+            const float a = sA[(16 * ms + 2 * p) * kLd + offA1];
+#pragma unroll
+            for (int w = 0; w < G::NTW; ++w)
+              acc[1][w] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, fb[w][p], acc[1][w], 0, 0, 0);
+          }
+        }
+      }
+    }
+  };
+  auto multiply = [&](int q, int buf) {
+    if constexpr (E == 2) multiply_bf16(q, buf);
+    else multiply_f32(q, buf);
   };
 
   __syncthreads();                           // stage 0 is in LDS buffer 0
@@ -486,7 +556,7 @@ struct Plan {
 // tile write-out), and every split adds one pass over the K x N partial tiles
 // (written once, read once by the reduction).  The constants are measured orders
 // of magnitude on MI355X, in microseconds; only the choice of s depends on them.
-template <int BR, int MS>
+template <int E, int BR, int MS>
 Plan make_plan(int64_t M, int64_t K, int64_t N) {
   constexpr int R = MS / BR;
   constexpr int kSlots = 256;
@@ -497,7 +567,8 @@ Plan make_plan(int64_t M, int64_t K, int64_t N) {
   p.splits = 1;
   p.stages_per_split = stages > 0 ? stages : 1;
   if (stages <= 0 || tiles <= 0) return p;
-  const double us_stage = 0.42 * MS / 64.0, us_round = 8.0;
+  // (binary32 stages are bound by the matrix core: 16 times the passes per multiply-add)
+  const double us_stage = (E == 4 ? 1.3 : 0.42) * MS / 64.0, us_round = 8.0;
   const double us_split = 2.0 * (double)K * (double)N * 4.0 / 3.0e6;
   const int64_t s_min = ceil_div(stages * R, (int64_t)kMaxRowsPerSplit);
   int64_t s_max = stages < 64 ? stages : 64;
@@ -517,11 +588,12 @@ Plan make_plan(int64_t M, int64_t K, int64_t N) {
   return p;
 }
 
-template <int BR, int BC, int MS, int D, int WN>
+template <typename T, int BR, int BC, int MS, int D, int WN>
 int run(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int64_t M, int64_t K,
         const void *dY, int64_t N, int64_t lddy, float *dW, int64_t lddw, int accumulate, void *ws,
         size_t ws_bytes, hipStream_t s) {
-  const Plan p = make_plan<BR, MS>(M, K, N);
+  constexpr int E = (int)sizeof(T);
+  const Plan p = make_plan<E, BR, MS>(M, K, N);
   const size_t need = p.splits > 1 ? (size_t)p.splits * K * N * sizeof(float) : 0;
   if (need > 0 && (ws == nullptr || ws_bytes < need)) return BSR_ERR_WORKSPACE;
   const int64_t nbr = ceil_div(M, BR), nbc = ceil_div(K, BC);
@@ -533,18 +605,21 @@ int run(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int6
   const int xcd_map = 1;      // XCD-aware work item order (0 = plain order, kept for measurements)
   const int64_t n_items = (int64_t)p.splits * tiles_k * tiles_n;
   dim3 grid((unsigned)(xcd_map ? 8 * ceil_div(n_items, 8) : n_items));
-  const uint16_t *v = static_cast<const uint16_t *>(values);
-  const uint16_t *y = static_cast<const uint16_t *>(dY);
+  const T *v = static_cast<const T *>(values);
+  const T *y = static_cast<const T *>(dY);
   // 32-bit buffer offsets: both operands must stay below 4 GiB (checked by dw_mfma_supported)
-  const uint32_t values_bytes = (uint32_t)(nbr * nbc * BR * BC * 2);
-  int vb = 8;
-  while (vb > 1 && (N % vb != 0 || lddy % vb != 0 || (uintptr_t)dY % (2 * vb) != 0)) vb >>= 1;
+  const uint32_t values_bytes = (uint32_t)(nbr * nbc * BR * BC * E);
+  int vb = 16 / E;                                  // elements per dY vector: 16 bytes at most
+  while (vb > 1 && (N % vb != 0 || lddy % vb != 0 || (uintptr_t)dY % (E * vb) != 0)) vb >>= 1;
 #define BSR_DW_LAUNCH(VB)                                                                         \
-  hipLaunchKernelGGL((dw_mfma_kernel<BR, BC, MS, VB, D, WN>), grid, dim3(256 * WN), 0, s,          \
+  hipLaunchKernelGGL((dw_mfma_kernel<T, BR, BC, MS, VB, D, WN>), grid, dim3(256 * WN), 0, s,       \
                      row_ptr, col_idx, v, y, out, M, K, N, lddy, ldo, stride, nbr, nbc,            \
                      p.stages_per_split, acc_direct, tiles_k, tiles_n, p.splits, xcd_map,           \
                      values_bytes)
-  if (vb == 8) BSR_DW_LAUNCH(8);
+  if constexpr (E == 2) {
+    if (vb == 8) { BSR_DW_LAUNCH(8); vb = 0; }
+  }
+  if (vb == 0) {}
   else if (vb == 4) BSR_DW_LAUNCH(4);
   else if (vb == 2) BSR_DW_LAUNCH(2);
   else BSR_DW_LAUNCH(1);
@@ -554,9 +629,9 @@ int run(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int6
   return launch_splitk_reduce(out, p.splits, K, N, dW, lddw, accumulate, s);
 }
 
-template <int BR, int MS>
+template <int E, int BR, int MS>
 size_t ws_for(int64_t M, int64_t K, int64_t N) {
-  const Plan p = make_plan<BR, MS>(M, K, N);
+  const Plan p = make_plan<E, BR, MS>(M, K, N);
   return p.splits > 1 ? (size_t)p.splits * K * N * sizeof(float) : 0;
 }
 
@@ -564,7 +639,7 @@ size_t ws_for(int64_t M, int64_t K, int64_t N) {
 
 bool dw_mfma_supported(int dtype, int br, int bc, const void *values, int64_t M, int64_t K, int64_t N,
                        int64_t lddy) {
-  if (dtype != BSR_BF16) return false;
+  if (dtype != BSR_BF16 && dtype != BSR_F32) return false;
   if ((uintptr_t)values % 16 != 0) return false;
   const bool shape = (br == 32 && bc == 32) || (br == 64 && bc == 64) || (br == 16 && bc == 16) ||
                      (br == 14 && bc == 14);
@@ -572,31 +647,40 @@ bool dw_mfma_supported(int dtype, int br, int bc, const void *values, int64_t M,
   // the kernel addresses both operands with 32-bit byte offsets; offsets of
   // activation values at or above 2 GiB mean "pruned", and the dY offsets of the
   // stages fetched ahead past the end of a split must not wrap
-  if (ceil_div(M, br) * br * ceil_div(K, bc) * bc * 2 >= (int64_t(1) << 31)) return false;
-  if ((M + 8 * 64) * lddy * 2 >= (int64_t(1) << 32) - 64 || N > lddy) return false;
+  const int64_t e = elem_bytes(dtype);
+  if (ceil_div(M, br) * br * ceil_div(K, bc) * bc * e >= (int64_t(1) << 31)) return false;
+  if ((M + 8 * 64) * lddy * e >= (int64_t(1) << 32) - 64 || N > lddy) return false;
   return true;
 }
 
-size_t dw_mfma_ws_bytes(int64_t M, int64_t K, int64_t N, int br, int bc) {
+size_t dw_mfma_ws_bytes(int dtype, int64_t M, int64_t K, int64_t N, int br, int bc) {
   (void)bc;
+  const bool f32 = dtype == BSR_F32;
   switch (br) {
-    case 32: return ws_for<32, 64>(M, K, N);
-    case 64: return ws_for<64, 64>(M, K, N);
-    case 16: return ws_for<16, 32>(M, K, N);
-    case 14: return ws_for<14, 32>(M, K, N);
+    case 32: return f32 ? ws_for<4, 32, 64>(M, K, N) : ws_for<2, 32, 64>(M, K, N);
+    case 64: return f32 ? ws_for<4, 64, 64>(M, K, N) : ws_for<2, 64, 64>(M, K, N);
+    case 16: return f32 ? ws_for<4, 16, 32>(M, K, N) : ws_for<2, 16, 32>(M, K, N);
+    case 14: return f32 ? ws_for<4, 14, 32>(M, K, N) : ws_for<2, 14, 32>(M, K, N);
     default: return 0;
   }
 }
 
-int launch_dw_mfma(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int64_t M,
+int launch_dw_mfma(int dtype, const int32_t *row_ptr, const int32_t *col_idx, const void *values, int64_t M,
                    int64_t K, int br, int bc, const void *dY, int64_t N, int64_t lddy, float *dW,
                    int64_t lddw, int accumulate, void *ws, size_t ws_bytes, hipStream_t s) {
   if (K == 0 || N == 0) return BSR_OK;
 #define BSR_ARGS row_ptr, col_idx, values, M, K, dY, N, lddy, dW, lddw, accumulate, ws, ws_bytes, s
-  if (br == 32 && bc == 32) return run<32, 32, 64, 2, 4>(BSR_ARGS);
-  if (br == 64 && bc == 64) return run<64, 64, 64, 2, 4>(BSR_ARGS);
-  if (br == 16 && bc == 16) return run<16, 16, 32, 2, 4>(BSR_ARGS);
-  if (br == 14 && bc == 14) return run<14, 14, 32, 2, 4>(BSR_ARGS);
+  if (dtype == BSR_F32) {
+    if (br == 32 && bc == 32) return run<float, 32, 32, 64, 2, 4>(BSR_ARGS);
+    if (br == 64 && bc == 64) return run<float, 64, 64, 64, 2, 4>(BSR_ARGS);
+    if (br == 16 && bc == 16) return run<float, 16, 16, 32, 2, 4>(BSR_ARGS);
+    if (br == 14 && bc == 14) return run<float, 14, 14, 32, 2, 4>(BSR_ARGS);
+    return BSR_ERR_SHAPE;
+  }
+  if (br == 32 && bc == 32) return run<uint16_t, 32, 32, 64, 2, 4>(BSR_ARGS);
+  if (br == 64 && bc == 64) return run<uint16_t, 64, 64, 64, 2, 4>(BSR_ARGS);
+  if (br == 16 && bc == 16) return run<uint16_t, 16, 16, 32, 2, 4>(BSR_ARGS);
+  if (br == 14 && bc == 14) return run<uint16_t, 14, 14, 32, 2, 4>(BSR_ARGS);
 #undef BSR_ARGS
   return BSR_ERR_SHAPE;
 }
