@@ -263,6 +263,9 @@ DW_CASES = [
     (1024, 256, 64, 64, 64, "bf16", 0.75),
     (640, 384, 100, 16, 16, "bf16", 0.1),
     (260, 72, 40, 1, 8, "f32", 0.5),
+    (1100, 196, 150, 14, 14, "f32", 0.5),    # binary32 on the matrix cores: zero-filled tiles, ragged everything
+    (4100, 384, 260, 64, 64, "f32", 0.4),    # binary32, 64x64 blocks, several splits
+    (2048, 256, 192, 16, 16, "f32", 0.9),
     (300, 70, 33, 7, 5, "bf16", 0.6),
 ]
 
