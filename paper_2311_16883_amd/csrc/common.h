@@ -83,7 +83,34 @@ int launch_dw_mfma(int dtype, const int32_t *row_ptr, const int32_t *col_idx, co
 int launch_splitk_reduce(const float *partial, int splits, int64_t K, int64_t N, float *dW,
                          int64_t lddw, int accumulate, hipStream_t s);
 
+// Geometry of the kernels that stage whole block-rows in LDS (score.hip, pack.hip).
+// They serve blocks whose rows are narrower than a 16-byte vector (14x14 patches:
+// 28-byte rows) when the matrix rows are contiguous (ld == K), so that the rows of
+// `rb` consecutive block-rows form one contiguous span that is read or written with
+// wide linear accesses and re-ordered through LDS.  Sizes are in 32-bit words.
+constexpr int kSpanBytes = 16384;   // LDS span of one workgroup
+constexpr int kSpanList = 1024;     // kept blocks one workgroup can list
+struct SpanGeom {
+  int rb;          // block-rows per workgroup
+  int br;          // rows per block
+  int nbc;         // block-columns
+  int row_words;   // K * e / 4
+  int seg_words;   // bc * e / 4
+  int blk_words;   // br * seg_words
+  int vb;          // bytes per linear access (16, 8 or 4): divides the row pitch
+  uint32_t magic_blk, magic_seg, magic_nbc, magic_br;   // see span_div
+};
+// True (and *g filled) when the shape qualifies; p0 / p1 are the dense matrices
+// involved (16-byte alignment needed), either may be null.
+bool span_geometry(int dtype, int64_t M, int64_t K, int64_t ld, int br, int bc, const void *p0,
+                   const void *p1, SpanGeom *g);
+
 // ---- device helpers ----
+
+// w / d for w * d < 2^32, with magic = ceil(2^32 / d) (d == 1 has no 32-bit magic)
+__device__ __forceinline__ uint32_t span_div(uint32_t w, uint32_t d, uint32_t magic) {
+  return d == 1 ? w : __umulhi(w, magic);
+}
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t h) {
   return __uint_as_float((uint32_t)h << 16);

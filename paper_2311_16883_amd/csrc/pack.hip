@@ -299,6 +299,167 @@ __global__ __launch_bounds__(256) void decompress_kernel(
   }
 }
 
+// ---- narrow blocks: whole block-rows staged in LDS ----
+//
+// A workgroup owns g.rb consecutive block-rows, whose matrix rows are one contiguous
+// span of memory.  The dense side is moved with wide linear accesses (every byte of
+// a cache line used by one instruction), the BSR side as one contiguous run of
+// 32-bit words (the kept blocks of consecutive block-rows follow each other in
+// `values`), and the re-ordering between the two happens in LDS.  Word w of the run
+// belongs to kept block q = w / blk_words, row r and word c of that row; base[q] is
+// the block's first word in the span, lim[q] its valid rows and words (ragged edges).
+// LDS layout: span | base | lim, sized by the launcher.
+
+__device__ __forceinline__ void span_decode(const SpanGeom &g, uint32_t w, uint32_t *q, uint32_t *r, uint32_t *c) {
+  *q = span_div(w, (uint32_t)g.blk_words, g.magic_blk);
+  const uint32_t rem = w - *q * (uint32_t)g.blk_words;
+  *r = span_div(rem, (uint32_t)g.seg_words, g.magic_seg);
+  *c = rem - *r * (uint32_t)g.seg_words;
+}
+
+__device__ __forceinline__ uint32_t span_lim(const SpanGeom &g, int rows, uint32_t b, uint32_t j) {
+  const int rv = rows - (int)b * g.br < g.br ? rows - (int)b * g.br : g.br;
+  const int cv = g.row_words - (int)j * g.seg_words < g.seg_words ? g.row_words - (int)j * g.seg_words : g.seg_words;
+  return ((uint32_t)rv << 16) | (uint32_t)cv;
+}
+
+inline size_t span_lds_words(const SpanGeom &g) { return align_up((size_t)g.rb * g.br * g.row_words, 4); }
+
+template <int VB>
+__global__ __launch_bounds__(256) void compress_span_kernel(
+    const uint8_t *__restrict__ mask, const uint8_t *__restrict__ X, int64_t M, int64_t nbr, int64_t n_keep,
+    SpanGeom g, size_t span_words, int32_t *__restrict__ row_ptr, int32_t *__restrict__ col_idx,
+    uint32_t *__restrict__ values) {
+  typedef typename BytesOf<VB>::type V;
+  constexpr int kVecs = kSpanBytes / VB / 256;
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  uint32_t *span = lds, *base = lds + span_words, *lim = base + g.rb * g.nbc;
+  __shared__ uint32_t wave_tot[4];
+  __shared__ uint32_t total;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int64_t i0 = (int64_t)blockIdx.x * g.rb;
+  const int nb = (int)((nbr - i0) < g.rb ? (nbr - i0) : g.rb);
+  const int64_t m0 = i0 * g.br;
+  const int rows = (int)((M - m0) < (int64_t)nb * g.br ? (M - m0) : (int64_t)nb * g.br);
+  const int nvec = rows * g.row_words * 4 / VB;
+  // the span's loads go out first: the mask work below hides their latency
+  const V *src = reinterpret_cast<const V *>(X + m0 * g.row_words * 4);
+  V reg[kVecs];
+#pragma unroll
+  for (int k = 0; k < kVecs; ++k) {
+    reg[k] = zero_bytes<VB>();
+    if (t + 256 * k < nvec) reg[k] = src[t + 256 * k];
+  }
+  const uint32_t prefix = count_kept_prefix(mask, i0 * g.nbc, wave_tot, &total);
+
+  // ---- kept blocks of these block-rows, in order ----
+  const int nblk = nb * g.nbc;
+  const uint8_t *mrow = mask + i0 * g.nbc;
+  uint32_t kept = 0;
+  for (int c0 = 0; c0 < nblk; c0 += 256) {
+    const int idx = c0 + t;
+    const bool flag = idx < nblk && mrow[idx] != 0;
+    const unsigned long long ball = __ballot(flag);
+    if (lane == 0) wave_tot[wave] = (uint32_t)__popcll(ball);
+    __syncthreads();
+    uint32_t before = kept;
+    for (int w = 0; w < wave; ++w) before += wave_tot[w];
+    const uint32_t pos = before + (uint32_t)__popcll(ball & ((1ull << lane) - 1ull));
+    if (idx < nblk) {
+      const uint32_t b = span_div((uint32_t)idx, (uint32_t)g.nbc, g.magic_nbc), j = (uint32_t)idx - b * g.nbc;
+      if (j == 0) row_ptr[i0 + b] = (int32_t)(prefix + pos);
+      if (flag) {
+        base[pos] = b * g.br * g.row_words + j * g.seg_words;
+        lim[pos] = span_lim(g, rows, b, j);
+        if ((int64_t)prefix + pos < n_keep) col_idx[prefix + pos] = (int32_t)j;
+      }
+    }
+    kept += wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+    __syncthreads();
+  }
+  if (t == 0 && i0 + nb == nbr) row_ptr[nbr] = (int32_t)(prefix + kept);
+  V *sv = reinterpret_cast<V *>(span);
+#pragma unroll
+  for (int k = 0; k < kVecs; ++k)
+    if (t + 256 * k < nvec) sv[t + 256 * k] = reg[k];
+  __syncthreads();
+  int64_t nk = kept;                                       // blocks that have a place in `values`
+  if ((int64_t)prefix + nk > n_keep) nk = n_keep > (int64_t)prefix ? n_keep - prefix : 0;
+  const uint32_t total_w = (uint32_t)nk * (uint32_t)g.blk_words;
+  uint32_t *out = values + (int64_t)prefix * g.blk_words;
+#pragma unroll 4
+  for (uint32_t w = t; w < total_w; w += 256) {
+    uint32_t q, r, c;
+    span_decode(g, w, &q, &r, &c);
+    const uint32_t l = lim[q];
+    uint32_t val = 0;
+    if (r < (l >> 16) && c < (l & 0xFFFFu)) val = span[base[q] + r * g.row_words + c];
+    out[w] = val;
+  }
+}
+
+template <int VB>
+__global__ __launch_bounds__(256) void decompress_span_kernel(
+    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+    const uint32_t *__restrict__ values, int64_t M, int64_t nbr, SpanGeom g, size_t span_words,
+    uint8_t *__restrict__ X_out) {
+  typedef typename BytesOf<VB>::type V;
+  constexpr int kVecs = kSpanBytes / VB / 256;
+  constexpr int kWords = kSpanBytes / 4 / 256;
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  uint32_t *span = lds, *base = lds + span_words, *lim = base + g.rb * g.nbc;
+  __shared__ int32_t rp[16];
+  const int t = threadIdx.x;
+  const int64_t i0 = (int64_t)blockIdx.x * g.rb;
+  const int nb = (int)((nbr - i0) < g.rb ? (nbr - i0) : g.rb);
+  const int64_t m0 = i0 * g.br;
+  const int rows = (int)((M - m0) < (int64_t)nb * g.br ? (M - m0) : (int64_t)nb * g.br);
+  const int nvec = rows * g.row_words * 4 / VB;
+  if (t <= nb) rp[t] = row_ptr[i0 + t];
+  __syncthreads();
+  const int64_t p0 = rp[0];
+  int nk = rp[nb] - rp[0];
+  if (nk < 0) nk = 0;
+  if (nk > nb * g.nbc) nk = nb * g.nbc;                    // a well-formed row_ptr never exceeds this
+  // the kept blocks of these block-rows: one contiguous run, all loads in flight
+  const uint32_t total_w = (uint32_t)nk * (uint32_t)g.blk_words;
+  const uint32_t *vsrc = values + p0 * g.blk_words;
+  uint32_t reg[kWords];
+#pragma unroll
+  for (int k = 0; k < kWords; ++k) {
+    reg[k] = 0;
+    if ((uint32_t)(t + 256 * k) < total_w) reg[k] = vsrc[t + 256 * k];
+  }
+  uint4 *s4 = reinterpret_cast<uint4 *>(span);
+  for (int v = t; v < (rows * g.row_words + 3) / 4; v += 256) s4[v] = make_uint4(0, 0, 0, 0);
+  for (int q = t; q < nk; q += 256) {
+    const int64_t p = p0 + q;
+    uint32_t b = 0;
+    while ((int)b + 1 < nb && p >= rp[b + 1]) ++b;
+    const int32_t j = col_idx[p];
+    const bool ok = j >= 0 && j < g.nbc;
+    base[q] = ok ? b * g.br * g.row_words + (uint32_t)j * g.seg_words : 0u;
+    lim[q] = ok ? span_lim(g, rows, b, (uint32_t)j) : 0u;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kWords; ++k) {
+    const uint32_t w = (uint32_t)(t + 256 * k);
+    if (w < total_w) {
+      uint32_t q, r, c;
+      span_decode(g, w, &q, &r, &c);
+      const uint32_t l = lim[q];
+      if (r < (l >> 16) && c < (l & 0xFFFFu)) span[base[q] + r * g.row_words + c] = reg[k];
+    }
+  }
+  __syncthreads();
+  const V *sv = reinterpret_cast<const V *>(span);
+  V *dst = reinterpret_cast<V *>(X_out + m0 * g.row_words * 4);
+#pragma unroll
+  for (int k = 0; k < kVecs; ++k)
+    if (t + 256 * k < nvec) dst[t + 256 * k] = sv[t + 256 * k];
+}
+
 // Widest byte vector that divides every extent and alignment involved.
 int pick_bytes(int esize, int bc, int64_t K, int64_t ld, const void *a, const void *b) {
   int vb = 16;
@@ -312,6 +473,37 @@ int pick_bytes(int esize, int bc, int64_t K, int64_t ld, const void *a, const vo
 }
 
 }  // namespace
+
+bool span_geometry(int dtype, int64_t M, int64_t K, int64_t ld, int br, int bc, const void *p0,
+                   const void *p1, SpanGeom *g) {
+  const int e = elem_bytes(dtype);
+  if (M <= 0 || K <= 0 || ld != K) return false;
+  const int64_t rowb = K * e, segb = (int64_t)bc * e;
+  if (rowb % 4 != 0 || segb % 4 != 0) return false;
+  if (segb % 16 == 0 && rowb % 16 == 0) return false;      // 16-byte vectors fit the block rows: direct kernels
+  if ((uintptr_t)p0 % 16 != 0 || (uintptr_t)p1 % 16 != 0) return false;
+  const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
+  // a block-row padded to whole blocks must fit the span (bounds the BSR run of a workgroup as well)
+  const int64_t brow_bytes = (int64_t)br * nbc * segb;
+  if (brow_bytes > kSpanBytes || nbc > kSpanList) return false;
+  int64_t rb = kSpanBytes / brow_bytes;
+  if (rb > 8) rb = 8;
+  if (rb > kSpanList / nbc) rb = kSpanList / nbc;
+  if (rb > nbr) rb = nbr;
+  g->rb = (int)rb;
+  g->br = br;
+  g->nbc = (int)nbc;
+  g->row_words = (int)(rowb / 4);
+  g->seg_words = (int)(segb / 4);
+  g->blk_words = br * g->seg_words;
+  g->vb = rowb % 16 == 0 ? 16 : rowb % 8 == 0 ? 8 : 4;
+  auto magic = [](uint32_t d) { return (uint32_t)(((uint64_t(1) << 32) + d - 1) / d); };
+  g->magic_blk = magic((uint32_t)g->blk_words);
+  g->magic_seg = magic((uint32_t)g->seg_words);
+  g->magic_nbc = magic((uint32_t)g->nbc);
+  g->magic_br = magic((uint32_t)br);
+  return true;
+}
 
 int launch_index_build(const uint8_t *keep_mask, int64_t nbr, int64_t nbc, int64_t n_keep,
                        int32_t *row_ptr, int32_t *col_idx, hipStream_t s) {
@@ -365,9 +557,25 @@ int launch_compress(const uint8_t *keep_mask, const void *X, int dtype, int64_t 
     return launch_pack(X, dtype, M, K, ldx, br, bc, row_ptr, col_idx, n_keep, values, s);
   }
   const int e = elem_bytes(dtype);
-  const int vb = pick_bytes(e, bc, K, ldx, X, values);
   const uint8_t *x = static_cast<const uint8_t *>(X);
   uint8_t *v = static_cast<uint8_t *>(values);
+  SpanGeom g;
+  if ((uintptr_t)values % 4 == 0 && span_geometry(dtype, M, K, ldx, br, bc, X, nullptr, &g)) {
+    const size_t span_words = span_lds_words(g);
+    const size_t lds = (span_words + 2 * (size_t)g.rb * g.nbc) * 4;
+    const dim3 grid((unsigned)ceil_div(nbr, g.rb));
+#define BSR_COMPRESS_SPAN(VB)                                                                          \
+  hipLaunchKernelGGL((compress_span_kernel<VB>), grid, dim3(256), lds, s, keep_mask, x, M, nbr, n_keep, \
+                     g, span_words, row_ptr, col_idx, reinterpret_cast<uint32_t *>(v))
+    switch (g.vb) {
+      case 16: BSR_COMPRESS_SPAN(16); break;
+      case 8: BSR_COMPRESS_SPAN(8); break;
+      default: BSR_COMPRESS_SPAN(4); break;
+    }
+#undef BSR_COMPRESS_SPAN
+    return check_launch();
+  }
+  const int vb = pick_bytes(e, bc, K, ldx, X, values);
 #define BSR_COMPRESS(VB)                                                                            \
   hipLaunchKernelGGL((compress_kernel<VB>), dim3((unsigned)nbr), dim3(256), 0, s, keep_mask, x, M,  \
                      K * e, ldx * e, br, (int64_t)bc * e, nbr, nbc, n_keep, row_ptr, col_idx, v)
@@ -386,6 +594,23 @@ int launch_decompress(const int32_t *row_ptr, const int32_t *col_idx, const void
   if (M == 0 || K == 0) return BSR_OK;
   const int e = elem_bytes(dtype);
   const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
+  SpanGeom g;
+  if ((uintptr_t)values % 4 == 0 && span_geometry(dtype, M, K, ldx, br, bc, X_out, nullptr, &g)) {
+    const size_t span_words = span_lds_words(g);
+    const size_t lds = (span_words + 2 * (size_t)g.rb * g.nbc) * 4;
+    const dim3 grid((unsigned)ceil_div(nbr, g.rb));
+#define BSR_UNPACK_SPAN(VB)                                                                        \
+  hipLaunchKernelGGL((decompress_span_kernel<VB>), grid, dim3(256), lds, s, row_ptr, col_idx,      \
+                     static_cast<const uint32_t *>(values), M, nbr, g, span_words,                \
+                     static_cast<uint8_t *>(X_out))
+    switch (g.vb) {
+      case 16: BSR_UNPACK_SPAN(16); break;
+      case 8: BSR_UNPACK_SPAN(8); break;
+      default: BSR_UNPACK_SPAN(4); break;
+    }
+#undef BSR_UNPACK_SPAN
+    return check_launch();
+  }
   const int vb = pick_bytes(e, bc, K, ldx, X_out, values);
   const unsigned gx = (unsigned)ceil_div(nbc, kMapCols);
   int64_t gy = nbr;

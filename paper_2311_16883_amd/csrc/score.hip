@@ -89,6 +89,79 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
   }
 }
 
+// Narrow blocks (rows shorter than a 16-byte vector, e.g. 14x14 patches) on
+// contiguous matrix rows: a workgroup reads the rows of g.rb block-rows as one
+// linear span into LDS, then a thread per (matrix row, block-column) adds that
+// row segment's squares left to right, and a thread per block adds the row sums
+// top to bottom.  LDS layout: span | row sums (binary64).
+template <typename T, typename V>
+__global__ __launch_bounds__(256) void score_span_kernel(const uint8_t *__restrict__ X, int64_t M, int64_t K,
+                                                         int bc, int64_t nbr, SpanGeom g, size_t span_words,
+                                                         double *__restrict__ scores) {
+  constexpr int kVecs = kSpanBytes / (int)sizeof(V) / 256;
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  double *part = reinterpret_cast<double *>(lds + span_words);
+  const int t = threadIdx.x;
+  const int64_t i0 = (int64_t)blockIdx.x * g.rb;
+  const int nb = (int)((nbr - i0) < g.rb ? (nbr - i0) : g.rb);
+  const int64_t m0 = i0 * g.br;
+  const int rows = (int)((M - m0) < (int64_t)nb * g.br ? (M - m0) : (int64_t)nb * g.br);
+  const int nvec = rows * g.row_words * 4 / (int)sizeof(V);
+  const V *src = reinterpret_cast<const V *>(X + m0 * g.row_words * 4);
+  V reg[kVecs];
+#pragma unroll
+  for (int k = 0; k < kVecs; ++k)
+    if (t + 256 * k < nvec) reg[k] = src[t + 256 * k];
+  V *sv = reinterpret_cast<V *>(lds);
+#pragma unroll
+  for (int k = 0; k < kVecs; ++k)
+    if (t + 256 * k < nvec) sv[t + 256 * k] = reg[k];
+  __syncthreads();
+  const T *sp = reinterpret_cast<const T *>(lds);
+  const int kk = (int)K;
+  for (int pair = t; pair < rows * g.nbc; pair += 256) {
+    const uint32_t row = span_div((uint32_t)pair, (uint32_t)g.nbc, g.magic_nbc), j = (uint32_t)pair - row * g.nbc;
+    const int c0 = (int)j * bc, c1 = c0 + bc < kk ? c0 + bc : kk;
+    const T *p = sp + (int)row * kk;
+    double acc = 0.0;
+    for (int c = c0; c < c1; ++c) {
+      const double x = (double)elem_to_float<T>(p[c]);
+      acc = fma(x, x, acc);
+    }
+    part[pair] = acc;
+  }
+  __syncthreads();
+  for (int bj = t; bj < nb * g.nbc; bj += 256) {
+    const uint32_t b = span_div((uint32_t)bj, (uint32_t)g.nbc, g.magic_nbc), j = (uint32_t)bj - b * g.nbc;
+    const int r1 = rows - (int)b * g.br < g.br ? rows - (int)b * g.br : g.br;
+    double sum = 0.0;
+    for (int r = 0; r < r1; ++r) sum += part[((int)b * g.br + r) * g.nbc + (int)j];
+    scores[(i0 + b) * g.nbc + j] = sum;
+  }
+}
+
+template <typename T>
+int run_score_span(const void *X, int64_t M, int64_t K, int bc, const SpanGeom &g, double *scores,
+                   hipStream_t s) {
+  const int64_t nbr = ceil_div(M, g.br);
+  const size_t span_words = align_up((size_t)g.rb * g.br * g.row_words, 4);
+  const size_t lds = span_words * 4 + (size_t)g.rb * g.br * g.nbc * sizeof(double);
+  const dim3 grid((unsigned)ceil_div(nbr, g.rb));
+  const uint8_t *x = static_cast<const uint8_t *>(X);
+  switch (g.vb) {
+    case 16:
+      hipLaunchKernelGGL((score_span_kernel<T, uint4>), grid, dim3(256), lds, s, x, M, K, bc, nbr, g, span_words, scores);
+      break;
+    case 8:
+      hipLaunchKernelGGL((score_span_kernel<T, uint2>), grid, dim3(256), lds, s, x, M, K, bc, nbr, g, span_words, scores);
+      break;
+    default:
+      hipLaunchKernelGGL((score_span_kernel<T, uint32_t>), grid, dim3(256), lds, s, x, M, K, bc, nbr, g, span_words, scores);
+      break;
+  }
+  return check_launch();
+}
+
 template <typename T, int V>
 int run_score(const void *X, int64_t M, int64_t K, int64_t ldx, int br, int bc, double *scores,
               hipStream_t s) {
@@ -126,6 +199,11 @@ int run_score(const void *X, int64_t M, int64_t K, int64_t ldx, int br, int bc, 
 int launch_score(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int br, int bc,
                  double *scores, hipStream_t s) {
   if (M == 0 || K == 0) return BSR_OK;
+  SpanGeom g;
+  // row sums in LDS: at most 48 KB of binary64 beside the span
+  if (span_geometry(dtype, M, K, ldx, br, bc, X, nullptr, &g) && (int64_t)g.rb * br * g.nbc <= 6144)
+    return dtype == BSR_F32 ? run_score_span<float>(X, M, K, bc, g, scores, s)
+                            : run_score_span<uint16_t>(X, M, K, bc, g, scores, s);
   if (dtype == BSR_F32) {
     switch (pick_vector(4, 4, bc, K, ldx, X)) {
       case 4: return run_score<float, 4>(X, M, K, ldx, br, bc, scores, s);

@@ -94,6 +94,11 @@ FORWARD_CASES = [
     (48, 40008, 8, 8, "bf16", 0.3),          # 5001 block-columns: index build and pack as two launches
     (2100, 264, 2, 8, "f32", 0.6),           # 1050 block-rows of 33 blocks: fused conversion, 2-row blocks
     (640, 1024, 64, 64, "f32", 0.4),         # 1024 vectors per block: several per thread in the fused copy
+    # block rows narrower than 16 bytes on contiguous rows: block-rows staged through LDS
+    (1001, 196, 14, 14, "f32", 0.5),         # 56-byte segments, ragged rows, 3 block-rows per workgroup
+    (333, 60, 3, 6, "bf16", 0.7),            # 8 block-rows per workgroup, the last workgroup has 7
+    (64, 2046, 4, 6, "bf16", 0.5),           # 341 block-columns: one block-row fills the LDS span
+    (1030, 130, 8, 8, "bf16", 0.35),         # 16-byte segments on rows that are not 16-byte aligned; ragged columns
 ]
 
 
