@@ -133,6 +133,17 @@ def main():
     # the main stream at the start of a step and the main stream waits for every stream
     # at its end, so the step is still one unit of work on the main stream.
     side = [torch.cuda.Stream() for _ in range(max(args.streams, 1))] if args.streams > 1 else []
+    # Tensors are dealt to the streams largest first, each to the stream with the least bytes so
+    # far (the three tensor shapes of a layer differ 4x in size; a plain stride would put all
+    # the large ones on the same two streams).
+    per_stream = [[] for _ in side]
+    if side:
+        weight = lambda t: t["spec"].M * (2 * t["spec"].K + t["spec"].N)
+        load = [0] * len(side)
+        for t in sorted(tensors, key=weight, reverse=True):
+            i = load.index(min(load))
+            per_stream[i].append(t)
+            load[i] += weight(t)
 
     def step():
         main_stream = torch.cuda.current_stream()
@@ -143,12 +154,16 @@ def main():
             return
         fork = torch.cuda.Event()
         fork.record(main_stream)
-        for i, st in enumerate(side):
+        for st in side:
             st.wait_event(fork)
-            with torch.cuda.stream(st):
-                for t in tensors[i::len(side)]:
-                    for _, f in phases:
-                        f(t)
+        # enqueue round-robin, one tensor per stream at a time, so that every stream has work early
+        for k in range(max(len(l) for l in per_stream)):
+            for st, l in zip(side, per_stream):
+                if k < len(l):
+                    with torch.cuda.stream(st):
+                        for _, f in phases:
+                            f(l[k])
+        for st in side:
             done = torch.cuda.Event()
             done.record(st)
             main_stream.wait_event(done)
