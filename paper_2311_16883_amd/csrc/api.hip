@@ -103,6 +103,9 @@ size_t bsr_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int br, int 
         if (dw_mfma_supported(dtype, br, bc, nullptr, M, K, N, N)) {
           const size_t b = dw_mfma_ws_bytes(dtype, M, K, N, br, bc);
           if (b > a) a = b;
+        } else if (dw_reblock_supported(dtype, br, bc, M, K, N, N)) {
+          const size_t b = dw_reblock_ws_bytes(dtype, M, K, N);
+          if (b > a) a = b;
         }
         return align_up(a, 256);
       }
@@ -217,6 +220,12 @@ int bsr_t_dense_matmul(const int32_t *row_ptr, const int32_t *col_idx, const voi
   if (dw_mfma_supported(dtype, br, bc, values, M, K, N, lddy))
     return launch_dw_mfma(dtype, row_ptr, col_idx, values, M, K, br, bc, dY, N, lddy, dW, lddw, accumulate,
                           ws, ws_bytes, static_cast<hipStream_t>(stream));
+  // other block shapes: re-tiled into 32x32 blocks for the matrix-core kernel, unless the
+  // problem is so small that the single launch of the general kernel is the faster way
+  if (M * K > 65536 && dw_reblock_supported(dtype, br, bc, M, K, N, lddy) &&
+      ws_bytes >= dw_reblock_ws_bytes(dtype, M, K, N))
+    return launch_dw_reblocked(dtype, row_ptr, col_idx, values, M, K, br, bc, dY, N, lddy, dW, lddw,
+                               accumulate, ws, ws_bytes, static_cast<hipStream_t>(stream));
   return launch_dw_generic(row_ptr, col_idx, values, dtype, M, K, br, bc, dY, N, lddy, dW, lddw,
                            accumulate, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }

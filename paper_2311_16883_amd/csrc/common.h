@@ -79,6 +79,13 @@ int launch_dw_mfma(int dtype, const int32_t *row_ptr, const int32_t *col_idx, co
                    int64_t K, int br, int bc, const void *dY, int64_t N, int64_t lddy, float *dW,
                    int64_t lddw, int accumulate, void *ws, size_t ws_bytes, hipStream_t s);
 
+// reblock.hip: any block shape re-tiled into 32x32 blocks in the workspace, then dw_mfma.
+bool dw_reblock_supported(int dtype, int br, int bc, int64_t M, int64_t K, int64_t N, int64_t lddy);
+size_t dw_reblock_ws_bytes(int dtype, int64_t M, int64_t K, int64_t N);
+int launch_dw_reblocked(int dtype, const int32_t *row_ptr, const int32_t *col_idx, const void *values, int64_t M,
+                        int64_t K, int br, int bc, const void *dY, int64_t N, int64_t lddy, float *dW,
+                        int64_t lddw, int accumulate, void *ws, size_t ws_bytes, hipStream_t s);
+
 // dw_generic.hip: dW = (accumulate ? dW : 0) + sum_s partial[s], s ascending.
 int launch_splitk_reduce(const float *partial, int splits, int64_t K, int64_t N, float *dW,
                          int64_t lddw, int accumulate, hipStream_t s);

@@ -272,6 +272,14 @@ DW_CASES = [
     (4100, 384, 260, 64, 64, "f32", 0.4),    # binary32, 64x64 blocks, several splits
     (2048, 256, 192, 16, 16, "f32", 0.9),
     (300, 70, 33, 7, 5, "bf16", 0.6),
+    # shapes without a matrix-core variant of their own: re-tiled into 32x32 blocks first
+    (2000, 384, 200, 1, 32, "bf16", 0.5),    # row segments (the block shape Table II's overheads imply)
+    (1024, 128, 64, 1, 4, "bf16", 0.5),      # the smallest segments of Table II
+    (1500, 200, 130, 1, 8, "f32", 0.3),      # K not a multiple of 32
+    (1000, 384, 96, 1, 384, "bf16", 0.5),    # b = K: whole rows pruned
+    (777, 300, 100, 7, 5, "bf16", 0.6),      # blocks that straddle the 32-row tiles
+    (640, 512, 64, 128, 128, "bf16", 0.3),   # blocks larger than a tile
+    (900, 1200, 40, 3, 100, "bf16", 0.5),    # several column chunks, blocks across their borders
 ]
 
 
