@@ -92,11 +92,14 @@ int launch_splitk_reduce(const float *partial, int splits, int64_t K, int64_t N,
 
 // Geometry of the kernels that stage whole block-rows in LDS (score.hip, pack.hip).
 // They serve blocks whose rows are narrower than a 16-byte vector (14x14 patches:
-// 28-byte rows) when the matrix rows are contiguous (ld == K), so that the rows of
-// `rb` consecutive block-rows form one contiguous span that is read or written with
-// wide linear accesses and re-ordered through LDS.  Sizes are in 32-bit words.
+// 28-byte rows) and blocks of few rows (1 x b row segments: a block-row is too
+// little work for a workgroup) when the matrix rows are contiguous (ld == K), so
+// that the rows of `rb` consecutive block-rows form one contiguous span that is
+// read or written with wide linear accesses and re-ordered through LDS.  Sizes are
+// in 32-bit words.
 constexpr int kSpanBytes = 16384;   // LDS span of one workgroup
 constexpr int kSpanList = 1024;     // kept blocks one workgroup can list
+constexpr int kSpanRows = 32;       // block-rows one workgroup can take
 struct SpanGeom {
   int rb;          // block-rows per workgroup
   int br;          // rows per block

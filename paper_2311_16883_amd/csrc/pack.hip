@@ -323,6 +323,20 @@ __device__ __forceinline__ uint32_t span_lim(const SpanGeom &g, int rows, uint32
   return ((uint32_t)rv << 16) | (uint32_t)cv;
 }
 
+// BSR side of a workgroup: word w of the run comes from the span (0 outside the matrix)
+__device__ __forceinline__ void span_write_run(const SpanGeom &g, const uint32_t *span, const uint32_t *base,
+                                               const uint32_t *lim, uint32_t total_w, uint32_t *__restrict__ out) {
+#pragma unroll 4
+  for (uint32_t w = threadIdx.x; w < total_w; w += 256) {
+    uint32_t q, r, c;
+    span_decode(g, w, &q, &r, &c);
+    const uint32_t l = lim[q];
+    uint32_t val = 0;
+    if (r < (l >> 16) && c < (l & 0xFFFFu)) val = span[base[q] + r * g.row_words + c];
+    out[w] = val;
+  }
+}
+
 inline size_t span_lds_words(const SpanGeom &g) { return align_up((size_t)g.rb * g.br * g.row_words, 4); }
 
 template <int VB>
@@ -385,17 +399,55 @@ __global__ __launch_bounds__(256) void compress_span_kernel(
   __syncthreads();
   int64_t nk = kept;                                       // blocks that have a place in `values`
   if ((int64_t)prefix + nk > n_keep) nk = n_keep > (int64_t)prefix ? n_keep - prefix : 0;
-  const uint32_t total_w = (uint32_t)nk * (uint32_t)g.blk_words;
-  uint32_t *out = values + (int64_t)prefix * g.blk_words;
-#pragma unroll 4
-  for (uint32_t w = t; w < total_w; w += 256) {
-    uint32_t q, r, c;
-    span_decode(g, w, &q, &r, &c);
-    const uint32_t l = lim[q];
-    uint32_t val = 0;
-    if (r < (l >> 16) && c < (l & 0xFFFFu)) val = span[base[q] + r * g.row_words + c];
-    out[w] = val;
+  span_write_run(g, span, base, lim, (uint32_t)nk * (uint32_t)g.blk_words, values + (int64_t)prefix * g.blk_words);
+}
+
+// The same copy with the index arrays already built (shapes whose mask prefix is too
+// long to recount in every workgroup): the mirror image of decompress_span_kernel.
+template <int VB>
+__global__ __launch_bounds__(256) void pack_span_kernel(
+    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, const uint8_t *__restrict__ X,
+    int64_t M, int64_t nbr, int64_t n_keep, SpanGeom g, size_t span_words, uint32_t *__restrict__ values) {
+  typedef typename BytesOf<VB>::type V;
+  constexpr int kVecs = kSpanBytes / VB / 256;
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  uint32_t *span = lds, *base = lds + span_words, *lim = base + g.rb * g.nbc;
+  __shared__ int32_t rp[kSpanRows + 2];
+  const int t = threadIdx.x;
+  const int64_t i0 = (int64_t)blockIdx.x * g.rb;
+  const int nb = (int)((nbr - i0) < g.rb ? (nbr - i0) : g.rb);
+  const int64_t m0 = i0 * g.br;
+  const int rows = (int)((M - m0) < (int64_t)nb * g.br ? (M - m0) : (int64_t)nb * g.br);
+  const int nvec = rows * g.row_words * 4 / VB;
+  const V *src = reinterpret_cast<const V *>(X + m0 * g.row_words * 4);
+  V reg[kVecs];
+#pragma unroll
+  for (int k = 0; k < kVecs; ++k) {
+    reg[k] = zero_bytes<VB>();
+    if (t + 256 * k < nvec) reg[k] = src[t + 256 * k];
   }
+  if (t <= nb) rp[t] = row_ptr[i0 + t];
+  __syncthreads();
+  const int64_t p0 = rp[0];
+  int64_t nk = (int64_t)rp[nb] - p0;
+  if (nk > (int64_t)nb * g.nbc) nk = (int64_t)nb * g.nbc;
+  if (p0 + nk > n_keep) nk = n_keep - p0;                  // blocks that have a place in `values`
+  if (nk < 0) nk = 0;
+  for (int q = t; q < (int)nk; q += 256) {
+    const int64_t p = p0 + q;
+    uint32_t b = 0;
+    while ((int)b + 1 < nb && p >= rp[b + 1]) ++b;
+    const int32_t j = col_idx[p];
+    const bool ok = j >= 0 && j < g.nbc;
+    base[q] = ok ? b * g.br * g.row_words + (uint32_t)j * g.seg_words : 0u;
+    lim[q] = ok ? span_lim(g, rows, b, (uint32_t)j) : 0u;
+  }
+  V *sv = reinterpret_cast<V *>(span);
+#pragma unroll
+  for (int k = 0; k < kVecs; ++k)
+    if (t + 256 * k < nvec) sv[t + 256 * k] = reg[k];
+  __syncthreads();
+  span_write_run(g, span, base, lim, (uint32_t)nk * (uint32_t)g.blk_words, values + p0 * g.blk_words);
 }
 
 template <int VB>
@@ -408,7 +460,7 @@ __global__ __launch_bounds__(256) void decompress_span_kernel(
   constexpr int kWords = kSpanBytes / 4 / 256;
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   uint32_t *span = lds, *base = lds + span_words, *lim = base + g.rb * g.nbc;
-  __shared__ int32_t rp[16];
+  __shared__ int32_t rp[kSpanRows + 2];
   const int t = threadIdx.x;
   const int64_t i0 = (int64_t)blockIdx.x * g.rb;
   const int nb = (int)((nbr - i0) < g.rb ? (nbr - i0) : g.rb);
@@ -480,14 +532,15 @@ bool span_geometry(int dtype, int64_t M, int64_t K, int64_t ld, int br, int bc, 
   if (M <= 0 || K <= 0 || ld != K) return false;
   const int64_t rowb = K * e, segb = (int64_t)bc * e;
   if (rowb % 4 != 0 || segb % 4 != 0) return false;
-  if (segb % 16 == 0 && rowb % 16 == 0) return false;      // 16-byte vectors fit the block rows: direct kernels
+  // blocks of 8 or more rows whose rows take 16-byte vectors are served by the direct kernels
+  if (segb % 16 == 0 && rowb % 16 == 0 && br >= 8) return false;
   if ((uintptr_t)p0 % 16 != 0 || (uintptr_t)p1 % 16 != 0) return false;
   const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
   // a block-row padded to whole blocks must fit the span (bounds the BSR run of a workgroup as well)
   const int64_t brow_bytes = (int64_t)br * nbc * segb;
   if (brow_bytes > kSpanBytes || nbc > kSpanList) return false;
   int64_t rb = kSpanBytes / brow_bytes;
-  if (rb > 8) rb = 8;
+  if (rb > kSpanRows) rb = kSpanRows;
   if (rb > kSpanList / nbc) rb = kSpanList / nbc;
   if (rb > nbr) rb = nbr;
   g->rb = (int)rb;
@@ -547,6 +600,37 @@ int launch_compress(const uint8_t *keep_mask, const void *X, int dtype, int64_t 
                     int br, int bc, int64_t n_keep, int32_t *row_ptr, int32_t *col_idx, void *values,
                     hipStream_t s) {
   const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
+  const int e = elem_bytes(dtype);
+  const uint8_t *x = static_cast<const uint8_t *>(X);
+  uint8_t *v = static_cast<uint8_t *>(values);
+  SpanGeom g;
+  if (nbr > 0 && nbc > 0 && (uintptr_t)values % 4 == 0 && span_geometry(dtype, M, K, ldx, br, bc, X, nullptr, &g)) {
+    const size_t span_words = span_lds_words(g);
+    const size_t lds = (span_words + 2 * (size_t)g.rb * g.nbc) * 4;
+    const int64_t wgs = ceil_div(nbr, g.rb);
+    const dim3 grid((unsigned)wgs);
+    // one launch if re-counting the mask prefix in every workgroup stays cheap (bytes out of L2)
+    const bool fused = wgs * (nbr * nbc / 2) <= (int64_t(64) << 20);
+    if (!fused) {
+      const int rc = launch_index_build(keep_mask, nbr, nbc, n_keep, row_ptr, col_idx, s);
+      if (rc != BSR_OK) return rc;
+      if (n_keep == 0) return BSR_OK;
+    }
+#define BSR_COMPRESS_SPAN(VB)                                                                              \
+  if (fused)                                                                                               \
+    hipLaunchKernelGGL((compress_span_kernel<VB>), grid, dim3(256), lds, s, keep_mask, x, M, nbr, n_keep,  \
+                       g, span_words, row_ptr, col_idx, reinterpret_cast<uint32_t *>(v));                  \
+  else                                                                                                     \
+    hipLaunchKernelGGL((pack_span_kernel<VB>), grid, dim3(256), lds, s, row_ptr, col_idx, x, M, nbr,       \
+                       n_keep, g, span_words, reinterpret_cast<uint32_t *>(v))
+    switch (g.vb) {
+      case 16: BSR_COMPRESS_SPAN(16); break;
+      case 8: BSR_COMPRESS_SPAN(8); break;
+      default: BSR_COMPRESS_SPAN(4); break;
+    }
+#undef BSR_COMPRESS_SPAN
+    return check_launch();
+  }
   // one fused launch when a block-row's columns fit its LDS list and re-reading the
   // mask prefix in every workgroup stays cheap (nbr * nblocks / 2 bytes out of L2)
   const bool fused = nbr > 0 && nbc > 0 && nbc <= kFusedCols && nbr <= 65535 &&
@@ -555,25 +639,6 @@ int launch_compress(const uint8_t *keep_mask, const void *X, int dtype, int64_t 
     int rc = launch_index_build(keep_mask, nbr, nbc, n_keep, row_ptr, col_idx, s);
     if (rc != BSR_OK) return rc;
     return launch_pack(X, dtype, M, K, ldx, br, bc, row_ptr, col_idx, n_keep, values, s);
-  }
-  const int e = elem_bytes(dtype);
-  const uint8_t *x = static_cast<const uint8_t *>(X);
-  uint8_t *v = static_cast<uint8_t *>(values);
-  SpanGeom g;
-  if ((uintptr_t)values % 4 == 0 && span_geometry(dtype, M, K, ldx, br, bc, X, nullptr, &g)) {
-    const size_t span_words = span_lds_words(g);
-    const size_t lds = (span_words + 2 * (size_t)g.rb * g.nbc) * 4;
-    const dim3 grid((unsigned)ceil_div(nbr, g.rb));
-#define BSR_COMPRESS_SPAN(VB)                                                                          \
-  hipLaunchKernelGGL((compress_span_kernel<VB>), grid, dim3(256), lds, s, keep_mask, x, M, nbr, n_keep, \
-                     g, span_words, row_ptr, col_idx, reinterpret_cast<uint32_t *>(v))
-    switch (g.vb) {
-      case 16: BSR_COMPRESS_SPAN(16); break;
-      case 8: BSR_COMPRESS_SPAN(8); break;
-      default: BSR_COMPRESS_SPAN(4); break;
-    }
-#undef BSR_COMPRESS_SPAN
-    return check_launch();
   }
   const int vb = pick_bytes(e, bc, K, ldx, X, values);
 #define BSR_COMPRESS(VB)                                                                            \

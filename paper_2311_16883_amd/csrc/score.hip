@@ -89,14 +89,15 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
   }
 }
 
-// Narrow blocks (rows shorter than a 16-byte vector, e.g. 14x14 patches) on
-// contiguous matrix rows: a workgroup reads the rows of g.rb block-rows as one
-// linear span into LDS, then a thread per (matrix row, block-column) adds that
-// row segment's squares left to right, and a thread per block adds the row sums
-// top to bottom.  LDS layout: span | row sums (binary64).
+// Narrow blocks (rows shorter than a 16-byte vector, e.g. 14x14 patches) and blocks
+// of few rows (1 x b row segments) on contiguous matrix rows: a workgroup reads the rows of g.rb block-rows as one
+// linear span into LDS, then a thread per (matrix row, block-column, piece of 32
+// elements) adds that piece's squares left to right, and a thread per block adds
+// the pieces row by row.  LDS layout: span | partial sums (binary64).
 template <typename T, typename V>
 __global__ __launch_bounds__(256) void score_span_kernel(const uint8_t *__restrict__ X, int64_t M, int64_t K,
                                                          int bc, int64_t nbr, SpanGeom g, size_t span_words,
+                                                         int pieces, uint32_t magic_pieces,
                                                          double *__restrict__ scores) {
   constexpr int kVecs = kSpanBytes / (int)sizeof(V) / 256;
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
@@ -119,23 +120,28 @@ __global__ __launch_bounds__(256) void score_span_kernel(const uint8_t *__restri
   __syncthreads();
   const T *sp = reinterpret_cast<const T *>(lds);
   const int kk = (int)K;
-  for (int pair = t; pair < rows * g.nbc; pair += 256) {
-    const uint32_t row = span_div((uint32_t)pair, (uint32_t)g.nbc, g.magic_nbc), j = (uint32_t)pair - row * g.nbc;
-    const int c0 = (int)j * bc, c1 = c0 + bc < kk ? c0 + bc : kk;
+  // a row segment is summed in pieces of 32 elements (`pieces` per segment)
+  for (int pc = t; pc < rows * g.nbc * pieces; pc += 256) {
+    const uint32_t pair = span_div((uint32_t)pc, (uint32_t)pieces, magic_pieces), sub = (uint32_t)pc - pair * pieces;
+    const uint32_t row = span_div(pair, (uint32_t)g.nbc, g.magic_nbc), j = pair - row * g.nbc;
+    const int c0 = (int)j * bc + (int)sub * 32;
+    int c1 = c0 + 32 < (int)(j + 1) * bc ? c0 + 32 : (int)(j + 1) * bc;
+    if (c1 > kk) c1 = kk;
     const T *p = sp + (int)row * kk;
     double acc = 0.0;
     for (int c = c0; c < c1; ++c) {
       const double x = (double)elem_to_float<T>(p[c]);
       acc = fma(x, x, acc);
     }
-    part[pair] = acc;
+    part[pc] = acc;
   }
   __syncthreads();
   for (int bj = t; bj < nb * g.nbc; bj += 256) {
     const uint32_t b = span_div((uint32_t)bj, (uint32_t)g.nbc, g.magic_nbc), j = (uint32_t)bj - b * g.nbc;
     const int r1 = rows - (int)b * g.br < g.br ? rows - (int)b * g.br : g.br;
     double sum = 0.0;
-    for (int r = 0; r < r1; ++r) sum += part[((int)b * g.br + r) * g.nbc + (int)j];
+    for (int r = 0; r < r1; ++r)
+      for (int u = 0; u < pieces; ++u) sum += part[(((int)b * g.br + r) * g.nbc + (int)j) * pieces + u];
     scores[(i0 + b) * g.nbc + j] = sum;
   }
 }
@@ -145,18 +151,20 @@ int run_score_span(const void *X, int64_t M, int64_t K, int bc, const SpanGeom &
                    hipStream_t s) {
   const int64_t nbr = ceil_div(M, g.br);
   const size_t span_words = align_up((size_t)g.rb * g.br * g.row_words, 4);
-  const size_t lds = span_words * 4 + (size_t)g.rb * g.br * g.nbc * sizeof(double);
+  const int pieces = (bc + 31) / 32;
+  const uint32_t magic_pieces = (uint32_t)(((uint64_t(1) << 32) + pieces - 1) / pieces);
+  const size_t lds = span_words * 4 + (size_t)g.rb * g.br * g.nbc * pieces * sizeof(double);
   const dim3 grid((unsigned)ceil_div(nbr, g.rb));
   const uint8_t *x = static_cast<const uint8_t *>(X);
   switch (g.vb) {
     case 16:
-      hipLaunchKernelGGL((score_span_kernel<T, uint4>), grid, dim3(256), lds, s, x, M, K, bc, nbr, g, span_words, scores);
+      hipLaunchKernelGGL((score_span_kernel<T, uint4>), grid, dim3(256), lds, s, x, M, K, bc, nbr, g, span_words, pieces, magic_pieces, scores);
       break;
     case 8:
-      hipLaunchKernelGGL((score_span_kernel<T, uint2>), grid, dim3(256), lds, s, x, M, K, bc, nbr, g, span_words, scores);
+      hipLaunchKernelGGL((score_span_kernel<T, uint2>), grid, dim3(256), lds, s, x, M, K, bc, nbr, g, span_words, pieces, magic_pieces, scores);
       break;
     default:
-      hipLaunchKernelGGL((score_span_kernel<T, uint32_t>), grid, dim3(256), lds, s, x, M, K, bc, nbr, g, span_words, scores);
+      hipLaunchKernelGGL((score_span_kernel<T, uint32_t>), grid, dim3(256), lds, s, x, M, K, bc, nbr, g, span_words, pieces, magic_pieces, scores);
       break;
   }
   return check_launch();
@@ -200,8 +208,9 @@ int launch_score(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, in
                  double *scores, hipStream_t s) {
   if (M == 0 || K == 0) return BSR_OK;
   SpanGeom g;
-  // row sums in LDS: at most 48 KB of binary64 beside the span
-  if (span_geometry(dtype, M, K, ldx, br, bc, X, nullptr, &g) && (int64_t)g.rb * br * g.nbc <= 6144)
+  // partial sums in LDS: at most 48 KB of binary64 beside the span
+  if (span_geometry(dtype, M, K, ldx, br, bc, X, nullptr, &g) &&
+      (int64_t)g.rb * br * g.nbc * ((bc + 31) / 32) <= 6144)
     return dtype == BSR_F32 ? run_score_span<float>(X, M, K, bc, g, scores, s)
                             : run_score_span<uint16_t>(X, M, K, bc, g, scores, s);
   if (dtype == BSR_F32) {

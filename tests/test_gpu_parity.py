@@ -99,6 +99,12 @@ FORWARD_CASES = [
     (333, 60, 3, 6, "bf16", 0.7),            # 8 block-rows per workgroup, the last workgroup has 7
     (64, 2046, 4, 6, "bf16", 0.5),           # 341 block-columns: one block-row fills the LDS span
     (1030, 130, 8, 8, "bf16", 0.35),         # 16-byte segments on rows that are not 16-byte aligned; ragged columns
+    # row segments (1 x b), the block shape Table II's overheads imply: many block-rows per workgroup
+    (3000, 384, 1, 32, "bf16", 0.5),
+    (2048, 384, 1, 384, "bf16", 0.5),        # b = K: whole rows pruned
+    (4096, 96, 1, 4, "bf16", 0.5),           # 32 block-rows per workgroup
+    (20000, 384, 1, 4, "bf16", 0.5),         # 1.9 M blocks: index build and LDS-staged pack as two launches
+    (5000, 200, 2, 50, "f32", 0.25),         # segments of several 32-element pieces, ragged last piece
 ]
 
 
