@@ -94,7 +94,7 @@ size_t bsr_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int br, int 
   if (check_shape(dtype, M, K, K, br, bc, &g) != BSR_OK) return 0;
   switch (op) {
     case BSR_OP_SCORE_SELECT: return score_select_ws(g.nblocks);
-    case BSR_OP_COMPRESS: return 0;
+    case BSR_OP_COMPRESS: return compress_ws_bytes(dtype, M, K, br, bc);
     case BSR_OP_DECOMPRESS: return 0;
     case BSR_OP_T_DENSE_MATMUL:
       if (N < 0) return 0;
@@ -171,12 +171,13 @@ int bsr_score_select_grouped(const void *X, int dtype, int64_t M, int64_t K, int
 int bsr_compress(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int br, int bc,
                  const uint8_t *keep_mask, int64_t n_keep, int32_t *row_ptr, int32_t *col_idx,
                  void *values, void *ws, size_t ws_bytes, void *stream) {
-  (void)ws;
-  (void)ws_bytes;
   Geometry g;
   int rc = check_shape(dtype, M, K, ldx, br, bc, &g);
   if (rc != BSR_OK) return rc;
   if (n_keep < 0 || n_keep > g.nblocks) return BSR_ERR_KEEP;
+  const size_t need = compress_ws_bytes(dtype, M, K, br, bc);
+  if (need > 0 && (ws == nullptr || ws_bytes < need)) return BSR_ERR_WORKSPACE;
+  if (need > 0 && misaligned(ws, 16)) return BSR_ERR_ALIGN;
   if (row_ptr == nullptr) return BSR_ERR_NULL;
   if (g.nblocks > 0 && (X == nullptr || keep_mask == nullptr)) return BSR_ERR_NULL;
   if (n_keep > 0 && (col_idx == nullptr || values == nullptr)) return BSR_ERR_NULL;
@@ -184,7 +185,7 @@ int bsr_compress(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, in
       misaligned(row_ptr, 4) || misaligned(col_idx, 4))
     return BSR_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  return launch_compress(keep_mask, X, dtype, M, K, ldx, br, bc, n_keep, row_ptr, col_idx, values, s);
+  return launch_compress(keep_mask, X, dtype, M, K, ldx, br, bc, n_keep, row_ptr, col_idx, values, ws, s);
 }
 
 int bsr_decompress(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int dtype,

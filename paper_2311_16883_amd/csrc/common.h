@@ -58,9 +58,10 @@ int launch_pack(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int
                 const int32_t *row_ptr, const int32_t *col_idx, int64_t n_keep, void *values,
                 hipStream_t s);
 // mask -> row_ptr, col_idx, values (one fused launch when the shape allows it)
+size_t compress_ws_bytes(int dtype, int64_t M, int64_t K, int br, int bc);
 int launch_compress(const uint8_t *keep_mask, const void *X, int dtype, int64_t M, int64_t K, int64_t ldx,
                     int br, int bc, int64_t n_keep, int32_t *row_ptr, int32_t *col_idx, void *values,
-                    hipStream_t s);
+                    void *ws, hipStream_t s);
 int launch_decompress(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int dtype,
                       int64_t M, int64_t K, int64_t ldx, int br, int bc, void *X_out, hipStream_t s);
 

@@ -339,11 +339,27 @@ __device__ __forceinline__ void span_write_run(const SpanGeom &g, const uint32_t
 
 inline size_t span_lds_words(const SpanGeom &g) { return align_up((size_t)g.rb * g.br * g.row_words, 4); }
 
+// Kept blocks of every workgroup's mask range (per_wg = rb * nbc <= kSpanList bytes): one wave per range.
+__global__ __launch_bounds__(256) void span_count_kernel(const uint8_t *__restrict__ mask, int64_t nblocks,
+                                                         int per_wg, int64_t wgs, uint32_t *__restrict__ wg_kept) {
+  const int lane = threadIdx.x & 63;
+  const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (w >= wgs) return;
+  const int64_t e0 = w * per_wg;
+  const int n = (int)((nblocks - e0) < per_wg ? (nblocks - e0) : per_wg);
+  uint32_t cnt = 0;
+#pragma unroll 4
+  for (int e = lane; e < n; e += 64) cnt += mask[e0 + e] != 0 ? 1u : 0u;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d, 64);
+  if (lane == 0) wg_kept[w] = cnt;
+}
+
 template <int VB>
 __global__ __launch_bounds__(256) void compress_span_kernel(
     const uint8_t *__restrict__ mask, const uint8_t *__restrict__ X, int64_t M, int64_t nbr, int64_t n_keep,
-    SpanGeom g, size_t span_words, int32_t *__restrict__ row_ptr, int32_t *__restrict__ col_idx,
-    uint32_t *__restrict__ values) {
+    SpanGeom g, size_t span_words, const uint32_t *__restrict__ wg_kept, int32_t *__restrict__ row_ptr,
+    int32_t *__restrict__ col_idx, uint32_t *__restrict__ values) {
   typedef typename BytesOf<VB>::type V;
   constexpr int kVecs = kSpanBytes / VB / 256;
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
@@ -364,7 +380,21 @@ __global__ __launch_bounds__(256) void compress_span_kernel(
     reg[k] = zero_bytes<VB>();
     if (t + 256 * k < nvec) reg[k] = src[t + 256 * k];
   }
-  const uint32_t prefix = count_kept_prefix(mask, i0 * g.nbc, wave_tot, &total);
+  // kept blocks in front of this workgroup: from the mask itself, or from the per-workgroup
+  // counts of span_count_kernel when the mask is too long to re-read in every workgroup
+  uint32_t prefix;
+  if (wg_kept == nullptr) {
+    prefix = count_kept_prefix(mask, i0 * g.nbc, wave_tot, &total);
+  } else {
+    uint32_t cnt = 0;
+    for (uint32_t w = t; w < blockIdx.x; w += 256) cnt += wg_kept[w];
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d, 64);
+    if (lane == 0) wave_tot[wave] = cnt;
+    __syncthreads();
+    prefix = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+    __syncthreads();
+  }
 
   // ---- kept blocks of these block-rows, in order ----
   const int nblk = nb * g.nbc;
@@ -400,54 +430,6 @@ __global__ __launch_bounds__(256) void compress_span_kernel(
   int64_t nk = kept;                                       // blocks that have a place in `values`
   if ((int64_t)prefix + nk > n_keep) nk = n_keep > (int64_t)prefix ? n_keep - prefix : 0;
   span_write_run(g, span, base, lim, (uint32_t)nk * (uint32_t)g.blk_words, values + (int64_t)prefix * g.blk_words);
-}
-
-// The same copy with the index arrays already built (shapes whose mask prefix is too
-// long to recount in every workgroup): the mirror image of decompress_span_kernel.
-template <int VB>
-__global__ __launch_bounds__(256) void pack_span_kernel(
-    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, const uint8_t *__restrict__ X,
-    int64_t M, int64_t nbr, int64_t n_keep, SpanGeom g, size_t span_words, uint32_t *__restrict__ values) {
-  typedef typename BytesOf<VB>::type V;
-  constexpr int kVecs = kSpanBytes / VB / 256;
-  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
-  uint32_t *span = lds, *base = lds + span_words, *lim = base + g.rb * g.nbc;
-  __shared__ int32_t rp[kSpanRows + 2];
-  const int t = threadIdx.x;
-  const int64_t i0 = (int64_t)blockIdx.x * g.rb;
-  const int nb = (int)((nbr - i0) < g.rb ? (nbr - i0) : g.rb);
-  const int64_t m0 = i0 * g.br;
-  const int rows = (int)((M - m0) < (int64_t)nb * g.br ? (M - m0) : (int64_t)nb * g.br);
-  const int nvec = rows * g.row_words * 4 / VB;
-  const V *src = reinterpret_cast<const V *>(X + m0 * g.row_words * 4);
-  V reg[kVecs];
-#pragma unroll
-  for (int k = 0; k < kVecs; ++k) {
-    reg[k] = zero_bytes<VB>();
-    if (t + 256 * k < nvec) reg[k] = src[t + 256 * k];
-  }
-  if (t <= nb) rp[t] = row_ptr[i0 + t];
-  __syncthreads();
-  const int64_t p0 = rp[0];
-  int64_t nk = (int64_t)rp[nb] - p0;
-  if (nk > (int64_t)nb * g.nbc) nk = (int64_t)nb * g.nbc;
-  if (p0 + nk > n_keep) nk = n_keep - p0;                  // blocks that have a place in `values`
-  if (nk < 0) nk = 0;
-  for (int q = t; q < (int)nk; q += 256) {
-    const int64_t p = p0 + q;
-    uint32_t b = 0;
-    while ((int)b + 1 < nb && p >= rp[b + 1]) ++b;
-    const int32_t j = col_idx[p];
-    const bool ok = j >= 0 && j < g.nbc;
-    base[q] = ok ? b * g.br * g.row_words + (uint32_t)j * g.seg_words : 0u;
-    lim[q] = ok ? span_lim(g, rows, b, (uint32_t)j) : 0u;
-  }
-  V *sv = reinterpret_cast<V *>(span);
-#pragma unroll
-  for (int k = 0; k < kVecs; ++k)
-    if (t + 256 * k < nvec) sv[t + 256 * k] = reg[k];
-  __syncthreads();
-  span_write_run(g, span, base, lim, (uint32_t)nk * (uint32_t)g.blk_words, values + p0 * g.blk_words);
 }
 
 template <int VB>
@@ -596,9 +578,18 @@ int launch_pack(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int
   return check_launch();
 }
 
+size_t compress_ws_bytes(int dtype, int64_t M, int64_t K, int br, int bc) {
+  SpanGeom g;
+  if (!span_geometry(dtype, M, K, K, br, bc, nullptr, nullptr, &g)) return 0;
+  const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
+  const int64_t wgs = ceil_div(nbr, g.rb);
+  if (wgs * (nbr * nbc / 2) <= (int64_t(64) << 20)) return 0;      // every workgroup re-counts the mask prefix
+  return align_up((size_t)wgs * sizeof(uint32_t), 256);
+}
+
 int launch_compress(const uint8_t *keep_mask, const void *X, int dtype, int64_t M, int64_t K, int64_t ldx,
                     int br, int bc, int64_t n_keep, int32_t *row_ptr, int32_t *col_idx, void *values,
-                    hipStream_t s) {
+                    void *ws, hipStream_t s) {
   const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
   const int e = elem_bytes(dtype);
   const uint8_t *x = static_cast<const uint8_t *>(X);
@@ -609,20 +600,19 @@ int launch_compress(const uint8_t *keep_mask, const void *X, int dtype, int64_t 
     const size_t lds = (span_words + 2 * (size_t)g.rb * g.nbc) * 4;
     const int64_t wgs = ceil_div(nbr, g.rb);
     const dim3 grid((unsigned)wgs);
-    // one launch if re-counting the mask prefix in every workgroup stays cheap (bytes out of L2)
-    const bool fused = wgs * (nbr * nbc / 2) <= (int64_t(64) << 20);
-    if (!fused) {
-      const int rc = launch_index_build(keep_mask, nbr, nbc, n_keep, row_ptr, col_idx, s);
+    // one launch if re-counting the mask prefix in every workgroup stays cheap (bytes out of
+    // L2); else a first launch counts every workgroup's kept blocks into the workspace
+    uint32_t *wg_kept = nullptr;
+    if (compress_ws_bytes(dtype, M, K, br, bc) != 0) {
+      wg_kept = static_cast<uint32_t *>(ws);
+      hipLaunchKernelGGL(span_count_kernel, dim3((unsigned)ceil_div(wgs, 4)), dim3(256), 0, s, keep_mask,
+                         nbr * nbc, g.rb * g.nbc, wgs, wg_kept);
+      const int rc = check_launch();
       if (rc != BSR_OK) return rc;
-      if (n_keep == 0) return BSR_OK;
     }
 #define BSR_COMPRESS_SPAN(VB)                                                                              \
-  if (fused)                                                                                               \
-    hipLaunchKernelGGL((compress_span_kernel<VB>), grid, dim3(256), lds, s, keep_mask, x, M, nbr, n_keep,  \
-                       g, span_words, row_ptr, col_idx, reinterpret_cast<uint32_t *>(v));                  \
-  else                                                                                                     \
-    hipLaunchKernelGGL((pack_span_kernel<VB>), grid, dim3(256), lds, s, row_ptr, col_idx, x, M, nbr,       \
-                       n_keep, g, span_words, reinterpret_cast<uint32_t *>(v))
+  hipLaunchKernelGGL((compress_span_kernel<VB>), grid, dim3(256), lds, s, keep_mask, x, M, nbr, n_keep, g, \
+                     span_words, wg_kept, row_ptr, col_idx, reinterpret_cast<uint32_t *>(v))
     switch (g.vb) {
       case 16: BSR_COMPRESS_SPAN(16); break;
       case 8: BSR_COMPRESS_SPAN(8); break;

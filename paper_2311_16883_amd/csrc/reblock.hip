@@ -26,11 +26,17 @@ namespace {
 constexpr int kRbEntries = 2048;          // entries listed in LDS per round
 constexpr int kRbTileBytes = 32768;       // LDS tile: 32 rows x chunk
 
-template <typename T>
+// WORDS: blocks of at most 32 rows whose rows are whole 32-bit words.  The stored blocks
+// of the tile's block-rows are one contiguous run of words in `values`; it is read
+// linearly, eight loads in flight per thread, and every word finds its place in the
+// tile from (entry, row, word) = decode(position).  Otherwise `group` lanes walk the
+// part of each block that lies inside the tile, element by element.
+template <typename T, bool WORDS>
 __global__ __launch_bounds__(256) void reblock_kernel(
     const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, const T *__restrict__ values,
-    int64_t K, int br, int bc, int64_t nbr, int64_t nbr2, int64_t nbc2, int kc, int group,
-    int32_t *__restrict__ rp2, int32_t *__restrict__ ci2, T *__restrict__ values2) {
+    int64_t K, int br, int bc, int64_t nbr, int64_t nbr2, int64_t nbc2, int kc, int group, int ebatch,
+    uint32_t magic_blk, uint32_t magic_seg, int32_t *__restrict__ rp2, int32_t *__restrict__ ci2,
+    T *__restrict__ values2) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   T *tile = reinterpret_cast<T *>(smem);                                        // [32][kc]
   int32_t *erow = reinterpret_cast<int32_t *>(smem + (size_t)32 * kc * sizeof(T));   // tile row of an entry's first row
@@ -51,8 +57,8 @@ __global__ __launch_bounds__(256) void reblock_kernel(
     for (int v = t; v < 32 * kc / kVec; v += 256) t4[v] = make_uint4(0, 0, 0, 0);
     __syncthreads();
     const int64_t P0 = rp[0], P1 = rp[ni];
-    for (int64_t pb = P0; pb < P1; pb += kRbEntries) {
-      const int nb = (int)((P1 - pb) < kRbEntries ? (P1 - pb) : kRbEntries);
+    for (int64_t pb = P0; pb < P1; pb += ebatch) {
+      const int nb = (int)((P1 - pb) < ebatch ? (P1 - pb) : ebatch);
       for (int q = t; q < nb; q += 256) {
         const int64_t p = pb + q;
         int lo = 0, hi = ni - 1;                                                // last source block-row with rp <= p
@@ -66,6 +72,34 @@ __global__ __launch_bounds__(256) void reblock_kernel(
         ecol[q] = (j < 0 || c0 >= kc || c0 + bc <= 0) ? INT_MIN : (int32_t)c0;
       }
       __syncthreads();
+      if (WORDS) {
+        constexpr int kPerWord = 4 / (int)sizeof(T);
+        const uint32_t seg_words = (uint32_t)bc / kPerWord, blk_words = (uint32_t)br * seg_words;
+        const int kcw = kc / kPerWord;
+        const uint32_t total = (uint32_t)nb * blk_words;                       // < 2^16 (ebatch)
+        const uint32_t *vw = reinterpret_cast<const uint32_t *>(values) + pb * blk_words;
+        uint32_t *tw = reinterpret_cast<uint32_t *>(tile);
+        for (uint32_t w0 = 0; w0 < total; w0 += 8 * 256) {
+          uint32_t reg[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            const uint32_t w = w0 + t + 256 * k;
+            reg[k] = w < total ? vw[w] : 0u;
+          }
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            const uint32_t w = w0 + t + 256 * k;
+            if (w < total) {
+              const uint32_t q = span_div(w, blk_words, magic_blk), rem = w - q * blk_words;
+              const uint32_t r = span_div(rem, seg_words, magic_seg), c = rem - r * seg_words;
+              const int32_t ec = ecol[q];
+              const int row = erow[q] + (int)r;
+              const int col = ec / kPerWord + (int)c;                           // ec is a multiple of the word size
+              if (ec != INT_MIN && row >= 0 && row < 32 && col >= 0 && col < kcw) tw[row * kcw + col] = reg[k];
+            }
+          }
+        }
+      } else
       // `group` lanes per entry: they walk the part of the block that lies inside the tile
       for (int q = grp; q < nb; q += ngrp) {
         const int32_t er = erow[q], ec = ecol[q];
@@ -158,14 +192,28 @@ int launch_dw_reblocked(int dtype, const int32_t *row_ptr, const int32_t *col_id
   const int64_t nbr = ceil_div(M, br);
   const dim3 grid((unsigned)ceil_div(k2, kc), (unsigned)(p.nbr2 < 65535 ? p.nbr2 : 65535));
   const size_t lds = (size_t)32 * kc * e + 2 * (size_t)kRbEntries * 4;
-  if (dtype == BSR_F32)
-    hipLaunchKernelGGL(reblock_kernel<float>, grid, dim3(256), lds, s, row_ptr, col_idx,
-                       static_cast<const float *>(values), K, br, bc, nbr, p.nbr2, p.nbc2, kc, group, rp2, ci2,
-                       reinterpret_cast<float *>(w + p.values_off));
-  else
-    hipLaunchKernelGGL(reblock_kernel<uint16_t>, grid, dim3(256), lds, s, row_ptr, col_idx,
-                       static_cast<const uint16_t *>(values), K, br, bc, nbr, p.nbr2, p.nbc2, kc, group, rp2, ci2,
-                       reinterpret_cast<uint16_t *>(w + p.values_off));
+  // word mode: rows of whole words, at most 32 rows, few column chunks (every chunk reads the whole run)
+  const int64_t blk_words = (int64_t)br * bc * e / 4;
+  const bool words = ((int64_t)bc * e) % 4 == 0 && br <= 32 && blk_words <= 4096 && grid.x <= 4 &&
+                     (uintptr_t)values % 4 == 0;
+  int ebatch = kRbEntries;
+  uint32_t magic_blk = 0, magic_seg = 0;
+  if (words) {
+    if (ebatch > 65536 / blk_words) ebatch = (int)(65536 / blk_words);
+    auto magic = [](uint32_t d) { return (uint32_t)(((uint64_t(1) << 32) + d - 1) / d); };
+    magic_blk = magic((uint32_t)blk_words);
+    magic_seg = magic((uint32_t)(bc * e / 4));
+  }
+#define BSR_REBLOCK(T, W)                                                                                   \
+  hipLaunchKernelGGL((reblock_kernel<T, W>), grid, dim3(256), lds, s, row_ptr, col_idx,                     \
+                     static_cast<const T *>(values), K, br, bc, nbr, p.nbr2, p.nbc2, kc, group, ebatch,     \
+                     magic_blk, magic_seg, rp2, ci2, reinterpret_cast<T *>(w + p.values_off))
+  if (dtype == BSR_F32) {
+    if (words) BSR_REBLOCK(float, true); else BSR_REBLOCK(float, false);
+  } else {
+    if (words) BSR_REBLOCK(uint16_t, true); else BSR_REBLOCK(uint16_t, false);
+  }
+#undef BSR_REBLOCK
   const int rc = check_launch();
   if (rc != BSR_OK) return rc;
   return launch_dw_mfma(dtype, rp2, ci2, w + p.values_off, M, K, 32, 32, dY, N, lddy, dW, lddw, accumulate,

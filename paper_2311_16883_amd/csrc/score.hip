@@ -146,10 +146,62 @@ __global__ __launch_bounds__(256) void score_span_kernel(const uint8_t *__restri
   }
 }
 
+// Few-row blocks whose row segments are whole 16-byte vectors (1 x b row segments):
+// the same span of g.rb block-rows, but every lane keeps its vectors in registers
+// and only their sums of squares go to LDS; a thread per block then adds the
+// vectors of its segments left to right, row by row.
+template <typename T>
+__global__ __launch_bounds__(256) void score_rows_kernel(const uint8_t *__restrict__ X, int64_t M, int bc,
+                                                         int64_t nbr, SpanGeom g, double *__restrict__ scores) {
+  constexpr int VE = 16 / (int)sizeof(T);
+  constexpr int kVecs = kSpanBytes / 16 / 256;
+  __shared__ double part[kSpanBytes / 16];
+  const int t = threadIdx.x;
+  const int64_t i0 = (int64_t)blockIdx.x * g.rb;
+  const int nb = (int)((nbr - i0) < g.rb ? (nbr - i0) : g.rb);
+  const int64_t m0 = i0 * g.br;
+  const int rows = (int)((M - m0) < (int64_t)nb * g.br ? (M - m0) : (int64_t)nb * g.br);
+  const int rv = g.row_words / 4;                        // vectors per matrix row
+  const int nvec = rows * rv;
+  const Vec<T, VE> *src = reinterpret_cast<const Vec<T, VE> *>(X + m0 * g.row_words * 4);
+  Vec<T, VE> reg[kVecs];
+#pragma unroll
+  for (int k = 0; k < kVecs; ++k)
+    if (t + 256 * k < nvec) reg[k] = src[t + 256 * k];
+#pragma unroll
+  for (int k = 0; k < kVecs; ++k) {
+    if (t + 256 * k < nvec) {
+      double acc = 0.0;
+#pragma unroll
+      for (int q = 0; q < VE; ++q) {
+        const double x = (double)elem_to_float<T>(reg[k].e[q]);
+        acc = fma(x, x, acc);
+      }
+      part[t + 256 * k] = acc;
+    }
+  }
+  __syncthreads();
+  const int vps = bc / VE;                               // vectors per row segment
+  for (int bj = t; bj < nb * g.nbc; bj += 256) {
+    const uint32_t b = span_div((uint32_t)bj, (uint32_t)g.nbc, g.magic_nbc), j = (uint32_t)bj - b * g.nbc;
+    const int r1 = rows - (int)b * g.br < g.br ? rows - (int)b * g.br : g.br;
+    const int u1 = rv - (int)j * vps < vps ? rv - (int)j * vps : vps;       // ragged last block-column
+    double sum = 0.0;
+    for (int r = 0; r < r1; ++r)
+      for (int u = 0; u < u1; ++u) sum += part[((int)b * g.br + r) * rv + (int)j * vps + u];
+    scores[(i0 + b) * g.nbc + j] = sum;
+  }
+}
+
 template <typename T>
 int run_score_span(const void *X, int64_t M, int64_t K, int bc, const SpanGeom &g, double *scores,
                    hipStream_t s) {
   const int64_t nbr = ceil_div(M, g.br);
+  if (g.vb == 16 && g.seg_words % 4 == 0) {
+    hipLaunchKernelGGL((score_rows_kernel<T>), dim3((unsigned)ceil_div(nbr, g.rb)), dim3(256), 0, s,
+                       static_cast<const uint8_t *>(X), M, bc, nbr, g, scores);
+    return check_launch();
+  }
   const size_t span_words = align_up((size_t)g.rb * g.br * g.row_words, 4);
   const int pieces = (bc + 31) / 32;
   const uint32_t magic_pieces = (uint32_t)(((uint64_t(1) << 32) + pieces - 1) / pieces);

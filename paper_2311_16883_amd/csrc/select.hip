@@ -504,8 +504,18 @@ __global__ __launch_bounds__(kGridThreads) void select_count_kernel(
 #pragma unroll
   for (int i = 0; i < kKeys; ++i)
     if (e0 + t + i * kGridThreads < e1) atomicAdd(&hist[bucket_of(score_key(raw[i]), lo, hi, shift)], 1u);
-  for (uint32_t e = e0 + t + kKeys * kGridThreads; e < e1; e += kGridThreads)
-    atomicAdd(&hist[bucket_of(score_key(scores[e]), lo, hi, shift)], 1u);
+  // longer slices (more than 256 K blocks): eight loads in flight per round
+  for (uint32_t eb = e0 + t + kKeys * kGridThreads; eb < e1; eb += 8 * kGridThreads) {
+    double more[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t e = eb + i * kGridThreads;
+      more[i] = scores[e < e1 ? e : e0];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (eb + i * kGridThreads < e1) atomicAdd(&hist[bucket_of(score_key(more[i]), lo, hi, shift)], 1u);
+  }
   __syncthreads();
   counts[blockIdx.x * kBuckets + t] = hist[t];
 }
@@ -575,7 +585,17 @@ __global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
     const uint32_t e = e0 + t + i * kGridThreads;
     if (e < e1) classify(e, score_key(raw[i]));
   }
-  for (uint32_t e = e0 + t + kKeys * kGridThreads; e < e1; e += kGridThreads) classify(e, score_key(scores[e]));
+  for (uint32_t eb = e0 + t + kKeys * kGridThreads; eb < e1; eb += 8 * kGridThreads) {
+    double more[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t e = eb + i * kGridThreads;
+      more[i] = scores[e < e1 ? e : e0];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (eb + i * kGridThreads < e1) classify(eb + i * kGridThreads, score_key(more[i]));
+  }
   __syncthreads();
   const uint32_t mine = wg_cand < (uint32_t)kCap ? wg_cand : (uint32_t)kCap;
   if (t == 0 && mine > 0) wg_base = atomicAdd(&ctrl->n_cand, mine);
