@@ -232,6 +232,36 @@ def main():
 
     grouped_ms = timed(lambda: [score_select_grouped(t) for t in tensors], args.phase_reps)
 
+    # ---- next row: 1 x b row segments (the block shape Table II's overheads imply) and b = K,
+    # at the fc1 shape, one tensor, every call of the path.  Not part of the timed step.
+    def row_segments(bc):
+        t = next(t for t in tensors if t["spec"].name.endswith("fc1"))
+        s = t["spec"]
+        nbr, nbc = s.M, -(-s.K // bc)
+        n_keep = B.bsr_keep_count(nbr * nbc, s.keep)
+        code = B.dtype_code(t["X"].dtype)
+        nbytes = max(B.bsr_workspace_bytes(op, s.M, s.K, s.N, 1, bc, code)
+                     for op in (B.BSR_OP_SCORE_SELECT, B.BSR_OP_COMPRESS, B.BSR_OP_T_DENSE_MATMUL))
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+        mask = torch.empty(nbr * nbc, dtype=torch.uint8, device=dev)
+        rp = torch.empty(nbr + 1, dtype=torch.int32, device=dev)
+        ci = torch.empty(n_keep, dtype=torch.int32, device=dev)
+        val = torch.empty((n_keep, 1, bc), dtype=t["X"].dtype, device=dev)
+        calls = {
+            "score_select": lambda: B.bsr_score_select(t["X"], 1, bc, s.keep, keep_mask=mask, ws=ws),
+            "compress": lambda: B.bsr_compress(t["X"], 1, bc, mask, n_keep, row_ptr=rp, col_idx=ci, values=val, ws=ws),
+            "decompress": lambda: B.bsr_decompress(rp, ci, val, s.M, s.K, 1, bc, out=t["Xhat"]),
+            "dw": lambda: B.bsr_t_dense_matmul(rp, ci, val, s.M, s.K, 1, bc, t["dY"], dW=t["dW"], ws=ws),
+        }
+        out = {}
+        for name, f in calls.items():
+            f()
+            out[name] = round(timed(f, max(args.phase_reps, 3)) * 1e3, 1)
+        return out
+
+    fc1_K = next(t["spec"].K for t in tensors if t["spec"].name.endswith("fc1"))
+    row_seg_us = {f"1x{bc}": row_segments(bc) for bc in (32, fc1_K)}
+
     # ---- the dominant kernel: one event pair around every dW launch ----
     def per_launch_ms(fn, group):
         pairs = []
@@ -311,7 +341,8 @@ def main():
                               "bytes_per_step": comp_alg_bytes},
         "next_rows": {"per_sample_score_select": {"ms_per_step": round(grouped_ms, 4),
                                                  "group_block_rows": {"xpatch": 14, "fc1": 49, "fc2": 49},
-                                                 "vs_whole_matrix_ms": round(phase_ms["score_select"], 4)}},
+                                                 "vs_whole_matrix_ms": round(phase_ms["score_select"], 4)},
+                      "row_segments_fc1_us_per_call": row_seg_us},
         "activation_memory": {"dense_MiB": round(dense_bytes / 2 ** 20, 2), "bsr_MiB": round(bsr_bytes / 2 ** 20, 2),
                               "saved_frac": round(1.0 - bsr_bytes / dense_bytes, 4)},
         "host_enqueue_ms": round(host_enqueue_ms, 3),

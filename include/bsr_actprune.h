@@ -154,6 +154,9 @@ int bsr_score_select_grouped(const void *X, int dtype, int64_t M, int64_t K,
  *                     row-major inside a block, +0.0 in edge padding.
  * If the mask holds a different number of ones than n_keep the result is
  * unspecified, but nothing is written outside the given buffers.
+ * Workspace: bsr_workspace_bytes(BSR_OP_COMPRESS, ...), which is zero for most
+ * shapes (then ws may be NULL); matrices of very many few-row blocks keep one
+ * counter per workgroup there.
  */
 int bsr_compress(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx,
                  int br, int bc, const uint8_t *keep_mask, int64_t n_keep,
@@ -180,6 +183,11 @@ int bsr_decompress(const int32_t *row_ptr, const int32_t *col_idx,
  * bfloat16).  This is X^T*dY; torch's nn.Linear.weight.grad is its transpose.
  * The contraction is split over block-rows; partial sums are reduced in a fixed
  * order, so results are reproducible run to run.
+ * Block shapes 32x32, 64x64, 16x16 and 14x14 are multiplied as stored (pruned
+ * blocks are skipped).  Any other shape -- 1 x b row segments, b = K, rectangular
+ * blocks -- is first re-tiled into 32x32 blocks inside the workspace (pruned
+ * positions become +0.0 and are multiplied like any other value); the workspace
+ * size reported for such a shape includes that copy (about M*K elements).
  */
 int bsr_t_dense_matmul(const int32_t *row_ptr, const int32_t *col_idx,
                        const void *values, int dtype, int64_t M, int64_t K,
