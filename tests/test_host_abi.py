@@ -78,6 +78,13 @@ def test_workspace_bytes_are_sane():
     assert B.bsr_workspace_bytes(B.BSR_OP_SCORE_SELECT, 25088, 384, 0, 32, 32, 9) == 0
     assert B.bsr_workspace_bytes(99, 25088, 384, 0, 32, 32, B.BSR_BF16) == 0
     assert B.bsr_workspace_bytes(B.BSR_OP_T_DENSE_MATMUL, 25088, 384, 1536, 32, 32, B.BSR_BF16) % 256 == 0
+    # mask -> BSR needs none at the benchmark's shapes, a counter per workgroup for millions of row segments
+    assert B.bsr_workspace_bytes(B.BSR_OP_COMPRESS, 25088, 384, 0, 32, 32, B.BSR_BF16) == 0
+    assert B.bsr_workspace_bytes(B.BSR_OP_COMPRESS, 49152, 196, 0, 14, 14, B.BSR_BF16) == 0
+    assert 0 < B.bsr_workspace_bytes(B.BSR_OP_COMPRESS, 25088, 384, 0, 1, 4, B.BSR_BF16) <= 4 * 25088 + 256
+    # block shapes that are re-tiled for the matrix cores: room for the 32x32 copy of the operand
+    tiled = B.bsr_workspace_bytes(B.BSR_OP_T_DENSE_MATMUL, 25088, 384, 1536, 1, 32, B.BSR_BF16)
+    assert tiled >= 25088 * 384 * 2 + 4 * 384 * 1536
 
 
 def test_invalid_arguments_are_rejected_on_the_host():
@@ -126,6 +133,11 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert cp(values=None) == B.BSR_ERR_NULL
     assert cp(values=odd) == B.BSR_ERR_ALIGN
     assert cp(col_idx=C.c_void_p(0x1002)) == B.BSR_ERR_ALIGN
+    # 2.4 M row segments: the call wants its workspace
+    assert lib.bsr_compress(fake, 1, 25088, 384, 384, 1, 4, fake, 100, fake, fake, fake, None, 0, None) \
+        == B.BSR_ERR_WORKSPACE
+    assert lib.bsr_compress(fake, 1, 25088, 384, 384, 1, 4, fake, 100, fake, fake, fake, fake, 64, None) \
+        == B.BSR_ERR_WORKSPACE
 
     assert lib.bsr_decompress(fake, fake, fake, 1, 64, 64, 64, 16, 16, None, None) == B.BSR_ERR_NULL
     assert lib.bsr_decompress(fake, fake, fake, 5, 64, 64, 64, 16, 16, fake, None) == B.BSR_ERR_DTYPE
