@@ -47,6 +47,9 @@ def parse():
                         "(same work; measured equal to eager enqueue: the step is GPU-bound)")
     p.add_argument("--streams", type=int, default=6,
                    help="HIP streams (default priority) the independent tensors of a step are spread over")
+    p.add_argument("--no-next-rows", action="store_true",
+                   help="skip the measurements outside the timed step (per-sample ranking, row segments), "
+                        "so that a profile of the run holds the step's kernels only")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run a plain 256 MiB device copy (known traffic) for scaling rocprofv3 byte counters")
     return p.parse_args()
@@ -230,7 +233,8 @@ def main():
         B.bsr_score_select_grouped(t["X"], s.br, s.bc, group_rows(s), s.keep, keep_mask=mask_g[:s.nblocks],
                                    ws=t["ws"])
 
-    grouped_ms = timed(lambda: [score_select_grouped(t) for t in tensors], args.phase_reps)
+    grouped_ms = None if args.no_next_rows else timed(lambda: [score_select_grouped(t) for t in tensors],
+                                                      args.phase_reps)
 
     # ---- next row: 1 x b row segments (the block shape Table II's overheads imply) and b = K,
     # at the fc1 shape, one tensor, every call of the path.  Not part of the timed step.
@@ -260,7 +264,7 @@ def main():
         return out
 
     fc1_K = next(t["spec"].K for t in tensors if t["spec"].name.endswith("fc1"))
-    row_seg_us = {f"1x{bc}": row_segments(bc) for bc in (32, fc1_K)}
+    row_seg_us = None if args.no_next_rows else {f"1x{bc}": row_segments(bc) for bc in (32, fc1_K)}
 
     # ---- the dominant kernel: one event pair around every dW launch ----
     def per_launch_ms(fn, group):
@@ -339,10 +343,11 @@ def main():
                               "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                               "frac": round(comp_alg_bytes / (comp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 5),
                               "bytes_per_step": comp_alg_bytes},
-        "next_rows": {"per_sample_score_select": {"ms_per_step": round(grouped_ms, 4),
-                                                 "group_block_rows": {"xpatch": 14, "fc1": 49, "fc2": 49},
-                                                 "vs_whole_matrix_ms": round(phase_ms["score_select"], 4)},
-                      "row_segments_fc1_us_per_call": row_seg_us},
+        "next_rows": None if args.no_next_rows else {
+            "per_sample_score_select": {"ms_per_step": round(grouped_ms, 4),
+                                        "group_block_rows": {"xpatch": 14, "fc1": 49, "fc2": 49},
+                                        "vs_whole_matrix_ms": round(phase_ms["score_select"], 4)},
+            "row_segments_fc1_us_per_call": row_seg_us},
         "activation_memory": {"dense_MiB": round(dense_bytes / 2 ** 20, 2), "bsr_MiB": round(bsr_bytes / 2 ** 20, 2),
                               "saved_frac": round(1.0 - bsr_bytes / dense_bytes, 4)},
         "host_enqueue_ms": round(host_enqueue_ms, 3),

@@ -9,6 +9,8 @@ would take minutes), plus two properties that hold at any size: rows of dW that
 belong to block-columns with no kept block are exactly zero, and the result is
 bitwise reproducible.
 """
+from dataclasses import replace
+
 import numpy as np
 import pytest
 import torch
@@ -44,6 +46,7 @@ def run_case(spec, seed, samples=192):
     row_ptr, col_idx, values = B.bsr_compress(Xd, spec.br, spec.bc, mask, n_keep)
     dW = B.bsr_t_dense_matmul(row_ptr, col_idx, values, spec.M, spec.K, spec.br, spec.bc, dYd)
     dW2 = B.bsr_t_dense_matmul(row_ptr, col_idx, values, spec.M, spec.K, spec.br, spec.bc, dYd)
+    Xhat = B.bsr_decompress(row_ptr, col_idx, values, spec.M, spec.K, spec.br, spec.bc)
     torch.cuda.synchronize()
 
     o_scores, o_mask, o_rp, o_ci, o_val = oracle.prune(X, spec.br, spec.bc, spec.keep)
@@ -61,6 +64,7 @@ def run_case(spec, seed, samples=192):
     g = dW.cpu().numpy()
     assert g.tobytes() == dW2.cpu().numpy().tobytes()                 # reproducible
     xhat = oracle.mask_dense(X, spec.br, spec.bc, o_mask)
+    assert to_host(Xhat).tobytes() == xhat.tobytes()                  # BSR -> dense is mask (.) X, bit for bit
     rng = np.random.default_rng(seed + 1000)
     ks, ns = rng.integers(0, spec.K, samples), rng.integers(0, spec.N, samples)
     ref = np.array([oracle.dw_entry(xhat, dY, int(k), int(n)) for k, n in zip(ks, ns)])
@@ -94,6 +98,14 @@ def test_s24_sweep_samples(name):
 @pytest.mark.parametrize("hot_first", [False, True])
 def test_b24_fc2_skewed_norms(hot_first):
     run_case(synth.b24_fc2(hot_first=hot_first)[0], 50 + int(hot_first), samples=128)
+
+
+@pytest.mark.parametrize("bc", [4, 32, 384])
+def test_s12_fc1_row_segments(bc):
+    """1 x b row segments (the block shape the overheads of Table II imply; b = 384 prunes whole
+    rows) at the benchmark's fc1 shape: 2.4 M, 301 k and 25 k blocks."""
+    fc1 = {s.name: s for s in synth.s12_layer(128)}["fc1"]
+    run_case(replace(fc1, name=f"fc1_1x{bc}", br=1, bc=bc), 70 + bc, samples=128)
 
 
 def test_s12_layer_per_sample_selection():
