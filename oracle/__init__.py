@@ -55,6 +55,8 @@ def _load():
         lib.oracle_select.argtypes = [vp, i64, i64, vp]
         lib.oracle_select_grouped.argtypes = [vp, i64, i64, i64, dbl, vp]
         lib.oracle_select_grouped.restype = i64
+        lib.oracle_affine_dscale.restype = None
+        lib.oracle_affine_dscale.argtypes = [vp, vp, i32, i64, i64, i64, i64, vp]
         lib.oracle_mask_dense.restype = None
         lib.oracle_mask_dense.argtypes = [vp, i32, i64, i64, i64, i32, i32, vp, vp, i64]
         lib.oracle_bsr_from_mask.restype = None
@@ -184,6 +186,18 @@ def dw(Xhat: np.ndarray, dY: np.ndarray) -> np.ndarray:
     N = dY.shape[1]
     out = np.empty((K, N), dtype=np.float64)
     _load().oracle_dw(_p(Xhat), _p(dY), _dtype_of(Xhat), M, K, K, N, N, _p(out))
+    return out
+
+
+def affine_dscale(Xhat: np.ndarray, dY: np.ndarray) -> np.ndarray:
+    """Scale gradient of the affine layer y = alpha * x + beta from the masked dense input:
+    dalpha [K] in float64, dalpha[k] = sum_m Xhat[m,k] * dY[m,k]  (dY has the shape of X)."""
+    Xhat, dY = _mat(Xhat), _mat(dY)
+    if Xhat.dtype != dY.dtype or Xhat.shape != dY.shape:
+        raise ValueError("Xhat and dY must share dtype and shape")
+    M, K = Xhat.shape
+    out = np.empty(K, dtype=np.float64)
+    _load().oracle_affine_dscale(_p(Xhat), _p(dY), _dtype_of(Xhat), M, K, K, K, _p(out))
     return out
 
 

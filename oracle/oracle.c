@@ -273,6 +273,22 @@ void oracle_dw(const void *Xhat, const void *dY, int dtype, int64_t M,
       dW[k * N + n] = oracle_dw_entry(Xhat, dY, dtype, M, ldx, lddy, k, n);
 }
 
+/* Sec. VI (outlook): the block-sparse version of ResMLP's affine scaling layer,
+ * y[m,k] = alpha[k] * x[m,k] + beta[k].  Of its backward pass only the scale
+ * gradient depends on the saved (pruned) input:
+ *   dalpha[k] = sum_m Xhat[m,k] * dY[m,k],
+ * accumulated in binary64 with m ascending (dbeta = sum_m dY[m,k] and
+ * dx = alpha * dy never see X). */
+void oracle_affine_dscale(const void *Xhat, const void *dY, int dtype, int64_t M,
+                          int64_t K, int64_t ldx, int64_t lddy, double *dalpha) {
+  for (int64_t k = 0; k < K; ++k) {
+    double acc = 0.0;
+    for (int64_t m = 0; m < M; ++m)
+      acc += load_elem(Xhat, dtype, m * ldx + k) * load_elem(dY, dtype, m * lddy + k);
+    dalpha[k] = acc;
+  }
+}
+
 /* Sec. II-A, Table II: bytes of one BSR-encoded matrix with 4-byte indices:
  * the kept blocks, one column index per kept block, nbr+1 row pointers. */
 int64_t oracle_bsr_bytes(int64_t n_keep, int64_t nbr, int br, int bc,

@@ -364,6 +364,60 @@ def _read_table(name):
     return rows
 
 
+# ----------------------------------------------------------------------------
+# scale gradient of the affine layer (Sec. VI, outlook: block-sparse affine scaling layer)
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_affine_dscale_is_the_derivative_of_the_layer(dtype):
+    """y = alpha * xhat + beta per channel, loss = sum(y * G): the derivative with respect to alpha[k],
+    taken numerically from the layer's forward pass, is what the oracle returns."""
+    M, K, br, bc = 45, 24, 8, 6
+    rng = np.random.default_rng(21)
+    X = rng.standard_normal((M, K), dtype=np.float32)
+    G = rng.standard_normal((M, K), dtype=np.float32)
+    if dtype == "bf16":
+        X, G = synth.f32_to_bf16_bits(X), synth.f32_to_bf16_bits(G)
+    nbr, nbc = oracle.grid(M, K, br, bc)
+    mask = (rng.random(nbr * nbc) < 0.5).astype(np.uint8)
+    Xhat = oracle.mask_dense(X, br, bc, mask)
+    got = oracle.affine_dscale(Xhat, G)
+    assert got.shape == (K,)
+    xh, g = synth.to_f64(Xhat), synth.to_f64(G)
+    alpha, beta = rng.standard_normal(K), rng.standard_normal(K)
+    loss = lambda a: float(np.sum((a[None, :] * xh + beta[None, :]) * g))
+    for k in (0, 5, K - 1):
+        e = np.zeros(K)
+        e[k] = 0.5
+        fd = loss(alpha + e) - loss(alpha - e)              # the loss is linear in alpha: exact up to rounding
+        assert abs(fd - got[k]) <= 1e-12 * np.sum(np.abs(xh[:, k] * g[:, k]))
+    # textbook routine: column-wise dot products of the masked matrix with G
+    want = np.einsum("mk,mk->k", synth.to_f64(X) * full_mask(mask, M, K, br, bc), g)
+    assert np.max(np.abs(got - want)) <= 1e-13 * np.max(np.abs(want))
+
+
+def test_affine_dscale_closed_forms_and_diagonal_of_dw():
+    M, K, br, bc = 40, 12, 4, 3
+    nbr, nbc = oracle.grid(M, K, br, bc)
+    X = np.ones((M, K), dtype=np.float32)
+    G = np.tile(np.arange(1, K + 1, dtype=np.float32), (M, 1))          # G[m,k] = k+1
+    mask = np.zeros((nbr, nbc), dtype=np.uint8)
+    mask[:, 0] = 1                   # block-column 0 kept everywhere
+    mask[:3, 2] = 1                  # block-column 2 kept in the first three block-rows
+    Xhat = oracle.mask_dense(X, br, bc, mask.reshape(-1))
+    got = oracle.affine_dscale(Xhat, G)
+    want = np.zeros(K)
+    want[0:3] = M * np.arange(1, 4)                 # all 40 rows
+    want[6:9] = 3 * br * np.arange(7, 10)           # 12 rows
+    assert np.array_equal(got, want)                # pruned block-columns give exactly zero
+    # with a square gradient the scale gradient is the diagonal of the weight gradient
+    rng = np.random.default_rng(22)
+    X = rng.standard_normal((M, K), dtype=np.float32)
+    G = rng.standard_normal((M, K), dtype=np.float32)
+    Xhat = oracle.mask_dense(X, br, bc, (rng.random(nbr * nbc) < 0.6).astype(np.uint8))
+    assert np.array_equal(oracle.affine_dscale(Xhat, G), np.diag(oracle.dw(Xhat, G)))
+
+
 def test_bsr_bytes_reproduce_table_2():
     """Table II: overhead of BSR over the ideal (1 - s), 384-wide binary32 rows.
 
