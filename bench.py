@@ -266,6 +266,27 @@ def main():
     fc1_K = next(t["spec"].K for t in tensors if t["spec"].name.endswith("fc1"))
     row_seg_us = None if args.no_next_rows else {f"1x{bc}": row_segments(bc) for bc in (32, fc1_K)}
 
+    # ---- next row: scale gradient of the block-sparse affine layer, from the fc1 input's BSR form and a
+    # gradient of the input's shape (the fc2 output gradient of the same layer is [25088 x 384]).
+    def affine_us():
+        t = next(t for t in tensors if t["spec"].name.endswith("fc1"))
+        g = next(u for u in tensors if u["spec"].name.endswith("fc2"))["dY"]
+        s = t["spec"]
+        assert tuple(g.shape) == (s.M, s.K)
+        code = B.dtype_code(g.dtype)
+        ws = torch.empty(max(B.bsr_workspace_bytes(B.BSR_OP_AFFINE_SCALE_GRAD, s.M, s.K, 0, s.br, s.bc, code), 256),
+                         dtype=torch.uint8, device=dev)
+        out = torch.empty(s.K, dtype=torch.float32, device=dev)
+        f = lambda: B.bsr_affine_scale_grad(t["row_ptr"], t["col_idx"], t["values"], s.M, s.K, s.br, s.bc, g,
+                                            dalpha=out, ws=ws)
+        f()
+        us = timed(f, max(args.phase_reps, 5)) * 1e3
+        n_keep = B.bsr_keep_count(s.nblocks, s.keep)
+        alg = 2 * n_keep * s.br * s.bc * g.element_size()       # kept values + the matching part of the gradient
+        return {"us_per_call": round(us, 1), "GBps": round(alg / (us * 1e-6) / 1e9, 1), "bytes": alg}
+
+    affine = None if args.no_next_rows else affine_us()
+
     # ---- the dominant kernel: one event pair around every dW launch ----
     def per_launch_ms(fn, group):
         pairs = []
@@ -347,7 +368,8 @@ def main():
             "per_sample_score_select": {"ms_per_step": round(grouped_ms, 4),
                                         "group_block_rows": {"xpatch": 14, "fc1": 49, "fc2": 49},
                                         "vs_whole_matrix_ms": round(phase_ms["score_select"], 4)},
-            "row_segments_fc1_us_per_call": row_seg_us},
+            "row_segments_fc1_us_per_call": row_seg_us,
+            "affine_scale_grad_fc1": affine},
         "activation_memory": {"dense_MiB": round(dense_bytes / 2 ** 20, 2), "bsr_MiB": round(bsr_bytes / 2 ** 20, 2),
                               "saved_frac": round(1.0 - bsr_bytes / dense_bytes, 4)},
         "host_enqueue_ms": round(host_enqueue_ms, 3),

@@ -58,7 +58,8 @@ enum {
   BSR_OP_SCORE_SELECT = 0,
   BSR_OP_COMPRESS = 1,
   BSR_OP_DECOMPRESS = 2,
-  BSR_OP_T_DENSE_MATMUL = 3
+  BSR_OP_T_DENSE_MATMUL = 3,
+  BSR_OP_AFFINE_SCALE_GRAD = 4
 };
 
 /* Host, pure.  Library version string. */
@@ -194,6 +195,25 @@ int bsr_t_dense_matmul(const int32_t *row_ptr, const int32_t *col_idx,
                        int br, int bc, const void *dY, int64_t N, int64_t lddy,
                        float *dW, int64_t lddw, int accumulate, void *ws,
                        size_t ws_bytes, void *stream);
+
+/*
+ * Sec. VI (outlook) names a block-sparse version of ResMLP's affine scaling
+ * layer, y[m,k] = alpha[k] * x[m,k] + beta[k].  Of its backward pass only the
+ * scale gradient needs the saved input; from the pruned input in BSR form:
+ *   dalpha[j*bc + c] (+)= sum over kept blocks (i,j), rows r of the block:
+ *                          values[block][r][c] * dY[i*br + r, j*bc + c].
+ * dY: [M x K] of the same dtype as values, leading dimension lddy (the layer's
+ * output gradient has the shape of its input).  dalpha: [K] binary32,
+ * overwritten when accumulate == 0, added to otherwise.  Products and sums in
+ * binary32, in a fixed order (reproducible run to run).  Pruned blocks are not
+ * read.  Workspace: bsr_workspace_bytes(BSR_OP_AFFINE_SCALE_GRAD, M, K, 0, ...).
+ * Errors as for bsr_t_dense_matmul.
+ */
+int bsr_affine_scale_grad(const int32_t *row_ptr, const int32_t *col_idx,
+                          const void *values, int dtype, int64_t M, int64_t K,
+                          int br, int bc, const void *dY, int64_t lddy,
+                          float *dalpha, int accumulate, void *ws,
+                          size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -17,6 +17,7 @@ import torch
 
 BSR_F32, BSR_BF16 = 0, 1
 BSR_OP_SCORE_SELECT, BSR_OP_COMPRESS, BSR_OP_DECOMPRESS, BSR_OP_T_DENSE_MATMUL = 0, 1, 2, 3
+BSR_OP_AFFINE_SCALE_GRAD = 4
 
 BSR_OK = 0
 BSR_ERR_NULL, BSR_ERR_SHAPE, BSR_ERR_DTYPE, BSR_ERR_KEEP = -1, -2, -3, -4
@@ -29,6 +30,7 @@ EXPORTS = (
     "bsr_version", "bsr_error_string", "bsr_last_hip_error", "bsr_keep_count",
     "bsr_storage_bytes", "bsr_workspace_bytes", "bsr_score_select", "bsr_compress",
     "bsr_decompress", "bsr_t_dense_matmul", "bsr_grouped_keep_count", "bsr_score_select_grouped",
+    "bsr_affine_scale_grad",
 )
 
 
@@ -78,6 +80,8 @@ def lib() -> C.CDLL:
     l.bsr_t_dense_matmul.restype = i32
     l.bsr_t_dense_matmul.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64, i32,
                                      vp, sz, vp]
+    l.bsr_affine_scale_grad.restype = i32
+    l.bsr_affine_scale_grad.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, vp, i64, vp, i32, vp, sz, vp]
     _lib = l
     return l
 
@@ -265,3 +269,26 @@ def bsr_t_dense_matmul(row_ptr: torch.Tensor, col_idx: torch.Tensor, values: tor
                                   _ptr(ws), ws.numel() if ws is not None else 0, _stream(stream))
     _check(rc, "bsr_t_dense_matmul")
     return dW
+
+
+def bsr_affine_scale_grad(row_ptr: torch.Tensor, col_idx: torch.Tensor, values: torch.Tensor, M: int,
+                          K: int, br: int, bc: int, dY: torch.Tensor, *,
+                          dalpha: Optional[torch.Tensor] = None, accumulate: bool = False,
+                          ws: Optional[torch.Tensor] = None, stream=None):
+    """-> dalpha [K] float32: scale gradient of the affine layer from its pruned input (dY is [M x K])."""
+    Md, Kd, lddy = _dense2d(dY, "dY")
+    if Md != M or Kd != K:
+        raise ValueError("dY must be [M x K]")
+    if dalpha is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing dalpha")
+        dalpha = torch.empty(K, dtype=torch.float32, device=dY.device)
+    code = dtype_code(dY.dtype)
+    if values.dtype != dY.dtype:
+        raise BsrError(BSR_ERR_DTYPE, "values and dY differ in dtype")
+    ws = _workspace(bsr_workspace_bytes(BSR_OP_AFFINE_SCALE_GRAD, M, K, 0, br, bc, code), dY.device, ws)
+    rc = lib().bsr_affine_scale_grad(_ptr(row_ptr), _ptr(col_idx), _ptr(values), code, M, K, br, bc,
+                                     _ptr(dY), lddy, _ptr(dalpha), 1 if accumulate else 0,
+                                     _ptr(ws), ws.numel() if ws is not None else 0, _stream(stream))
+    _check(rc, "bsr_affine_scale_grad")
+    return dalpha

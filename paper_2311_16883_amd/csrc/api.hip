@@ -109,6 +109,7 @@ size_t bsr_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int br, int 
         }
         return align_up(a, 256);
       }
+    case BSR_OP_AFFINE_SCALE_GRAD: return affine_ws_bytes(M, K, br, bc);
     default: return 0;
   }
 }
@@ -229,6 +230,26 @@ int bsr_t_dense_matmul(const int32_t *row_ptr, const int32_t *col_idx, const voi
                                accumulate, ws, ws_bytes, static_cast<hipStream_t>(stream));
   return launch_dw_generic(row_ptr, col_idx, values, dtype, M, K, br, bc, dY, N, lddy, dW, lddw,
                            accumulate, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int bsr_affine_scale_grad(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int dtype,
+                          int64_t M, int64_t K, int br, int bc, const void *dY, int64_t lddy, float *dalpha,
+                          int accumulate, void *ws, size_t ws_bytes, void *stream) {
+  Geometry g;
+  int rc = check_shape(dtype, M, K, K, br, bc, &g);
+  if (rc != BSR_OK) return rc;
+  if (lddy < K) return BSR_ERR_SHAPE;
+  if (K == 0) return BSR_OK;
+  if (dalpha == nullptr || row_ptr == nullptr) return BSR_ERR_NULL;
+  if (M > 0 && dY == nullptr) return BSR_ERR_NULL;
+  if (misaligned(values, elem_bytes(dtype)) || misaligned(dY, elem_bytes(dtype)) || misaligned(dalpha, 4) ||
+      misaligned(row_ptr, 4) || misaligned(col_idx, 4) || misaligned(ws, 16))
+    return BSR_ERR_ALIGN;
+  const size_t need = bsr_workspace_bytes(BSR_OP_AFFINE_SCALE_GRAD, M, K, 0, br, bc, dtype);
+  if (need > 0 && (ws == nullptr || ws_bytes < need)) return BSR_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (M == 0) return launch_splitk_reduce(nullptr, 0, 1, K, dalpha, K, accumulate, s);
+  return launch_affine_dscale(row_ptr, col_idx, values, dtype, M, K, br, bc, dY, lddy, dalpha, accumulate, ws, s);
 }
 
 }  // extern "C"

@@ -87,6 +87,12 @@ int launch_dw_reblocked(int dtype, const int32_t *row_ptr, const int32_t *col_id
                         int64_t K, int br, int bc, const void *dY, int64_t N, int64_t lddy, float *dW,
                         int64_t lddw, int accumulate, void *ws, size_t ws_bytes, hipStream_t s);
 
+// affine.hip: dalpha[k] = sum over kept blocks of values * dY at the same position.
+size_t affine_ws_bytes(int64_t M, int64_t K, int br, int bc);
+int launch_affine_dscale(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int dtype, int64_t M,
+                         int64_t K, int br, int bc, const void *dY, int64_t lddy, float *dalpha, int accumulate,
+                         void *ws, hipStream_t s);
+
 // dw_generic.hip: dW = (accumulate ? dW : 0) + sum_s partial[s], s ascending.
 int launch_splitk_reduce(const float *partial, int splits, int64_t K, int64_t N, float *dW,
                          int64_t lddw, int accumulate, hipStream_t s);

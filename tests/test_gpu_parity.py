@@ -343,3 +343,54 @@ def test_empty_inputs():
         dW = B.bsr_t_dense_matmul(rp, ci, val, M, K, 16, 16, dY)
         torch.cuda.synchronize()
         assert dW.shape == (K, 8) and not dW.cpu().numpy().any()
+
+
+# ----------------------------------------------------------------------------
+# scale gradient of the block-sparse affine layer
+# ----------------------------------------------------------------------------
+
+AFFINE_CASES = [
+    # M, K, br, bc, dtype, keep
+    (2048, 384, 32, 32, "bf16", 0.5),
+    (1000, 200, 32, 32, "f32", 0.25),        # ragged rows and columns
+    (777, 196, 14, 14, "bf16", 0.5),         # 4-byte vectors
+    (3000, 384, 1, 32, "bf16", 0.5),         # row segments
+    (300, 70, 7, 5, "f32", 0.9),             # scalar columns
+    (1024, 4096, 16, 16, "bf16", 0.3),       # several column chunks per row
+    (96, 8192, 8, 4096, "bf16", 0.5),        # a block row wider than one workgroup's columns
+    (40, 64, 64, 64, "f32", 1.0),            # one ragged block-row, everything kept
+]
+
+
+@pytest.mark.parametrize("M,K,br,bc,dtype,keep", AFFINE_CASES)
+def test_affine_scale_grad_parity(M, K, br, bc, dtype, keep):
+    print(f"[case] affine M={M} K={K} block={br}x{bc} {dtype} keep={keep}", flush=True)
+    X, dY = rand_pair(M, K, K, dtype, seed=M + K + 5)
+    o_scores, o_mask, o_rp, o_ci, o_val = oracle.prune(X, br, bc, keep)
+    ref = oracle.affine_dscale(oracle.mask_dense(X, br, bc, o_mask), dY)
+    dYd = to_dev(dY)
+    rp, ci = torch.from_numpy(o_rp).cuda(), torch.from_numpy(o_ci).cuda()
+    val = to_dev(o_val.reshape(-1, bc)).reshape(o_val.shape)
+    got = B.bsr_affine_scale_grad(rp, ci, val, M, K, br, bc, dYd)
+    again = B.bsr_affine_scale_grad(rp, ci, val, M, K, br, bc, dYd)
+    torch.cuda.synchronize()
+    g = got.cpu().numpy()
+    assert g.tobytes() == again.cpu().numpy().tobytes()                       # reproducible
+    # products are exact in binary32 for bfloat16; sums of at most M terms in binary32
+    xh, dy = synth.to_f64(oracle.mask_dense(X, br, bc, o_mask)), synth.to_f64(dY)
+    bound = 2.0 ** -23 * (np.log2(max(M, 2)) + 4) * np.sum(np.abs(xh * dy), axis=0)
+    assert np.all(np.abs(g - ref) <= bound + 1e-30), float(np.max(np.abs(g - ref) / (bound + 1e-30)))
+    # block-columns without a kept block give exactly zero
+    nbr, nbc = oracle.grid(M, K, br, bc)
+    dead = np.flatnonzero(o_mask.reshape(nbr, nbc).sum(axis=0) == 0)
+    for j in dead:
+        assert not g[j * bc:(j + 1) * bc].any()
+    # accumulate, and a strided dY view
+    base = torch.full((K,), 0.5, dtype=torch.float32, device="cuda")
+    B.bsr_affine_scale_grad(rp, ci, val, M, K, br, bc, dYd, dalpha=base, accumulate=True)
+    wide = torch.zeros((M, K + 16), dtype=dYd.dtype, device="cuda")
+    wide[:, 8:8 + K] = dYd
+    viewed = B.bsr_affine_scale_grad(rp, ci, val, M, K, br, bc, wide[:, 8:8 + K])
+    torch.cuda.synchronize()
+    assert np.all(np.abs(base.cpu().numpy() - 0.5 - ref) <= bound + 1e-6 * 0.5 + 1e-30)
+    assert np.all(np.abs(viewed.cpu().numpy() - ref) <= bound + 1e-30)

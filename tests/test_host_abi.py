@@ -23,7 +23,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     syms = declared_symbols()
-    assert set(syms) == set(B.EXPORTS) and len(syms) == 12
+    assert set(syms) == set(B.EXPORTS) and len(syms) == 13
     lib = B.lib()
     for s in syms:
         assert getattr(lib, s) is not None
@@ -155,6 +155,15 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert mm(dY=None) == B.BSR_ERR_NULL
     assert mm(dW=C.c_void_p(0x1002)) == B.BSR_ERR_ALIGN
     assert mm(N=0, lddy=0, lddw=0) == B.BSR_OK
+    af = lambda **k: lib.bsr_affine_scale_grad(
+        fake, fake, fake, k.get("dtype", 1), 64, 64, 16, 16, k.get("dY", fake), k.get("lddy", 64),
+        k.get("dalpha", fake), 0, k.get("ws", fake), k.get("ws_bytes", 1 << 20), None)
+    assert af(dtype=3) == B.BSR_ERR_DTYPE
+    assert af(lddy=63) == B.BSR_ERR_SHAPE
+    assert af(dalpha=None) == B.BSR_ERR_NULL
+    assert af(dY=None) == B.BSR_ERR_NULL
+    assert af(dalpha=C.c_void_p(0x1002)) == B.BSR_ERR_ALIGN
+    assert af(ws_bytes=16) == B.BSR_ERR_WORKSPACE
     assert B.lib().bsr_error_string(B.BSR_ERR_WORKSPACE) == b"BSR_ERR_WORKSPACE"
 
 
