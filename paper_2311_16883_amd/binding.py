@@ -177,7 +177,8 @@ def bsr_score_select(X: torch.Tensor, br: int, bc: int, keep: float, *,
     if keep_mask is None:
         keep_mask = torch.empty(nblocks, dtype=torch.uint8, device=X.device)
     code = dtype_code(X.dtype)
-    ws = _workspace(bsr_workspace_bytes(BSR_OP_SCORE_SELECT, M, K, 0, br, bc, code), X.device, ws)
+    if ws is None:
+        ws = _workspace(bsr_workspace_bytes(BSR_OP_SCORE_SELECT, M, K, 0, br, bc, code), X.device, None)
     rc = lib().bsr_score_select(_ptr(X), code, M, K, ldx, br, bc, float(keep), _ptr(scores),
                                 _ptr(keep_mask), _ptr(ws), ws.numel() if ws is not None else 0,
                                 _stream(stream))
@@ -204,7 +205,8 @@ def bsr_score_select_grouped(X: torch.Tensor, br: int, bc: int, group_rows: int,
     if keep_mask is None:
         keep_mask = torch.empty(nblocks, dtype=torch.uint8, device=X.device)
     code = dtype_code(X.dtype)
-    ws = _workspace(bsr_workspace_bytes(BSR_OP_SCORE_SELECT, M, K, 0, br, bc, code), X.device, ws)
+    if ws is None:
+        ws = _workspace(bsr_workspace_bytes(BSR_OP_SCORE_SELECT, M, K, 0, br, bc, code), X.device, None)
     rc = lib().bsr_score_select_grouped(_ptr(X), code, M, K, ldx, br, bc, int(group_rows), float(keep),
                                         _ptr(scores), _ptr(keep_mask), _ptr(ws),
                                         ws.numel() if ws is not None else 0, _stream(stream))
@@ -227,7 +229,8 @@ def bsr_compress(X: torch.Tensor, br: int, bc: int, keep_mask: torch.Tensor, n_k
     if values is None:
         values = torch.empty((max(n_keep, 0), br, bc), dtype=X.dtype, device=dev)
     code = dtype_code(X.dtype)
-    ws = _workspace(bsr_workspace_bytes(BSR_OP_COMPRESS, M, K, 0, br, bc, code), dev, ws)
+    if ws is None:
+        ws = _workspace(bsr_workspace_bytes(BSR_OP_COMPRESS, M, K, 0, br, bc, code), dev, None)
     rc = lib().bsr_compress(_ptr(X), code, M, K, ldx, br, bc, _ptr(keep_mask), int(n_keep),
                             _ptr(row_ptr), _ptr(col_idx), _ptr(values), _ptr(ws),
                             ws.numel() if ws is not None else 0, _stream(stream))
@@ -263,7 +266,8 @@ def bsr_t_dense_matmul(row_ptr: torch.Tensor, col_idx: torch.Tensor, values: tor
     code = dtype_code(dY.dtype)
     if values.dtype != dY.dtype:
         raise BsrError(BSR_ERR_DTYPE, "values and dY differ in dtype")
-    ws = _workspace(bsr_workspace_bytes(BSR_OP_T_DENSE_MATMUL, M, K, N, br, bc, code), dY.device, ws)
+    if ws is None:
+        ws = _workspace(bsr_workspace_bytes(BSR_OP_T_DENSE_MATMUL, M, K, N, br, bc, code), dY.device, None)
     rc = lib().bsr_t_dense_matmul(_ptr(row_ptr), _ptr(col_idx), _ptr(values), code, M, K, br, bc,
                                   _ptr(dY), N, lddy, _ptr(dW), lddw, 1 if accumulate else 0,
                                   _ptr(ws), ws.numel() if ws is not None else 0, _stream(stream))
@@ -286,7 +290,8 @@ def bsr_affine_scale_grad(row_ptr: torch.Tensor, col_idx: torch.Tensor, values: 
     code = dtype_code(dY.dtype)
     if values.dtype != dY.dtype:
         raise BsrError(BSR_ERR_DTYPE, "values and dY differ in dtype")
-    ws = _workspace(bsr_workspace_bytes(BSR_OP_AFFINE_SCALE_GRAD, M, K, 0, br, bc, code), dY.device, ws)
+    if ws is None:
+        ws = _workspace(bsr_workspace_bytes(BSR_OP_AFFINE_SCALE_GRAD, M, K, 0, br, bc, code), dY.device, None)
     rc = lib().bsr_affine_scale_grad(_ptr(row_ptr), _ptr(col_idx), _ptr(values), code, M, K, br, bc,
                                      _ptr(dY), lddy, _ptr(dalpha), 1 if accumulate else 0,
                                      _ptr(ws), ws.numel() if ws is not None else 0, _stream(stream))
