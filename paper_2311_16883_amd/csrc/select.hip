@@ -16,7 +16,7 @@
 // for any input and is the fallback of bracketed_select, which is much faster
 // when the caller can bracket the threshold's key (see there).
 //
-// Small inputs (<= 8192 blocks) and per-group selection: one workgroup per
+// Small inputs (<= 12288 blocks) and per-group selection: one workgroup per
 // ranking group, bracketed_select between the group's smallest and largest key.
 //
 // Large inputs: two grid-wide passes.
@@ -649,7 +649,7 @@ __global__ void fill_u8_kernel(uint8_t *p, int64_t n, uint8_t v) {
     p[i] = v;
 }
 
-constexpr int64_t kSmallLimit = 8192;      // one workgroup (8 keys per thread)
+constexpr int64_t kSmallLimit = 12288;     // one workgroup (up to 12 keys per thread)
 
 constexpr int kMaxGridWgs = 256;
 
@@ -687,8 +687,11 @@ int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t
     if (nblocks <= 1024)
       hipLaunchKernelGGL((select_groups_kernel<256, 4, 8>), dim3(1), dim3(256), 0, s, scores, (uint32_t)nblocks,
                          (uint32_t)n_keep, (uint32_t)nblocks, (uint32_t)n_keep, keep_mask);
-    else
+    else if (nblocks <= 8192)
       hipLaunchKernelGGL((select_groups_kernel<1024, 8, kDigitBits>), dim3(1), dim3(1024), 0, s, scores,
+                         (uint32_t)nblocks, (uint32_t)n_keep, (uint32_t)nblocks, (uint32_t)n_keep, keep_mask);
+    else
+      hipLaunchKernelGGL((select_groups_kernel<1024, 12, kDigitBits>), dim3(1), dim3(1024), 0, s, scores,
                          (uint32_t)nblocks, (uint32_t)n_keep, (uint32_t)nblocks, (uint32_t)n_keep, keep_mask);
     return check_launch();
   }
@@ -737,8 +740,12 @@ int launch_select_grouped(const double *scores, int64_t nbr, int64_t nbc, int64_
     hipLaunchKernelGGL((select_groups_kernel<256, 4, 8>), dim3((unsigned)groups), dim3(256), 0, s, scores,
                        (uint32_t)group_blocks, (uint32_t)n_keep_group, (uint32_t)last_blocks,
                        (uint32_t)n_keep_last, keep_mask);
-  else
+  else if (group_blocks <= 8192)
     hipLaunchKernelGGL((select_groups_kernel<1024, 8, kDigitBits>), dim3((unsigned)groups), dim3(1024), 0, s,
+                       scores, (uint32_t)group_blocks, (uint32_t)n_keep_group, (uint32_t)last_blocks,
+                       (uint32_t)n_keep_last, keep_mask);
+  else
+    hipLaunchKernelGGL((select_groups_kernel<1024, 12, kDigitBits>), dim3((unsigned)groups), dim3(1024), 0, s,
                        scores, (uint32_t)group_blocks, (uint32_t)n_keep_group, (uint32_t)last_blocks,
                        (uint32_t)n_keep_last, keep_mask);
   return check_launch();

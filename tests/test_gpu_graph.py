@@ -57,7 +57,7 @@ class Buffers:
 
 
 @pytest.mark.parametrize("spec", [
-    synth.TensorSpec("graph_32", 24576, 384, 512, 32, 32, "bf16", keep=0.5),    # 9216 blocks: grid-wide selection; split-K dW
+    synth.TensorSpec("graph_32", 36864, 384, 512, 32, 32, "bf16", keep=0.5),    # 13824 blocks: grid-wide selection; split-K dW
     synth.TensorSpec("graph_14", 2744, 196, 196, 14, 14, "bf16", keep=0.5),     # zero-filled LDS tiles
 ], ids=lambda s: s.name)
 def test_replays_match_eager(spec):

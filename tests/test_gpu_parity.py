@@ -184,9 +184,16 @@ def selection_stress(M, K, br, bc, keep, seed):
                                        (2048, 1536, 8, 8),       # 49152 blocks
                                        (2040, 2048, 8, 8)])      # 65280 blocks, ragged per-thread counts
 def test_grid_wide_selection_sizes(M, K, br, bc, keep):
-    """More than 8192 blocks: sampled bracket, bucket histogram, candidates selected by the last
+    """More than 12288 blocks: sampled bracket, bucket histogram, candidates selected by the last
     workgroup (linear 32-bit codes, lane-read ranking, general radix select when too many tie)."""
     selection_stress(M, K, br, bc, keep, seed=5)
+
+
+@pytest.mark.parametrize("keep", [0.5, 0.1, 0.9, 0.999])
+def test_single_workgroup_selection_twelve_keys_per_thread(keep):
+    """8193 ... 12288 blocks: one workgroup of 1024 threads with up to twelve keys per thread."""
+    selection_stress(5120, 512, 16, 16, keep, seed=8)           # 10240 blocks
+    selection_stress(3064, 512, 8, 16, keep, seed=9)            # 12256 blocks, ragged per-thread counts
 
 
 @pytest.mark.parametrize("keep", [0.5, 0.1, 0.9, 0.999])
@@ -203,7 +210,8 @@ def test_grid_wide_selection_large(keep):
     (6272, 384, 32, 32, 49, 0.5),        # groups of 8 samples (1568 rows = 49 block-rows, 588 blocks)
     (6272, 1536, 32, 32, 49, 0.25),      # 2352 blocks per group: the 1024-thread workgroups
     (1000, 200, 8, 8, 7, 0.3),           # ragged rows / columns, ragged last group
-    (8192, 512, 16, 16, 300, 0.5),       # 9600 blocks per group: grid-wide selection group after group
+    (8192, 512, 16, 16, 300, 0.5),       # 9600 blocks per group: twelve keys per thread
+    (8192, 512, 16, 16, 400, 0.5),       # 12800 blocks per group: grid-wide selection group after group
     (512, 128, 16, 16, 64, 0.6),         # one group: the ungrouped selection
 ])
 def test_grouped_selection_parity(M, K, br, bc, group_rows, keep):
