@@ -402,3 +402,39 @@ def test_affine_scale_grad_parity(M, K, br, bc, dtype, keep):
     torch.cuda.synchronize()
     assert np.all(np.abs(base.cpu().numpy() - 0.5 - ref) <= bound + 1e-6 * 0.5 + 1e-30)
     assert np.all(np.abs(viewed.cpu().numpy() - ref) <= bound + 1e-30)
+
+
+@pytest.mark.parametrize("M,K,br,bc,dtype", [(777, 196, 14, 14, "bf16"), (3000, 384, 1, 32, "bf16"),
+                                             (1500, 200, 1, 8, "f32"), (20000, 384, 1, 4, "bf16")])
+@pytest.mark.parametrize("keep", [0.0, 1.0])
+def test_degenerate_keeps_on_the_lds_staged_and_retiled_paths(M, K, br, bc, dtype, keep):
+    """Nothing kept / everything kept for the narrow and few-row block shapes: forward side, dW through the
+    re-tiled operand and the affine scale gradient."""
+    X, dY = rand_pair(M, K, 40, dtype, seed=M + bc)
+    (row_ptr, col_idx, values), o_mask = check_forward(X, br, bc, keep, "degenerate")
+    dYd = to_dev(dY)
+    dW = B.bsr_t_dense_matmul(row_ptr, col_idx, values, M, K, br, bc, dYd)
+    G = to_dev(rand_pair(M, K, K, dtype, seed=M + bc + 1)[1])
+    da = B.bsr_affine_scale_grad(row_ptr, col_idx, values, M, K, br, bc, G)
+    torch.cuda.synchronize()
+    if keep == 0.0:
+        assert not dW.cpu().numpy().any() and not da.cpu().numpy().any()
+    else:
+        dense = synth.to_f64(X).T @ synth.to_f64(dY)
+        assert dw_error(dW.cpu().numpy(), dense) <= DW_TOL[dtype]
+        ref = np.einsum("mk,mk->k", synth.to_f64(X), synth.to_f64(to_host(G)))
+        assert np.max(np.abs(da.cpu().numpy() - ref)) <= 1e-4 * np.max(np.abs(ref))
+
+
+def test_affine_scale_grad_empty_inputs():
+    rp = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ci = torch.zeros(0, dtype=torch.int32, device="cuda")
+    val = torch.zeros((0, 16, 16), dtype=torch.float32, device="cuda")
+    G = torch.ones((0, 64), dtype=torch.float32, device="cuda")
+    out = torch.full((64,), 3.0, dtype=torch.float32, device="cuda")
+    B.bsr_affine_scale_grad(rp, ci, val, 0, 64, 16, 16, G, dalpha=out, accumulate=True)      # no rows: unchanged
+    torch.cuda.synchronize()
+    assert np.all(out.cpu().numpy() == 3.0)
+    B.bsr_affine_scale_grad(rp, ci, val, 0, 64, 16, 16, G, dalpha=out)                       # no rows: zero
+    torch.cuda.synchronize()
+    assert not out.cpu().numpy().any()
