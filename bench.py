@@ -59,7 +59,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path is a single-GPU kernel pipeline "
-              "(sharding is described in DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "(rows shard over GPUs with no exchange but the usual gradient all-reduce); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
