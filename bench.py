@@ -47,6 +47,9 @@ def parse():
                         "(same work; measured equal to eager enqueue: the step is GPU-bound)")
     p.add_argument("--streams", type=int, default=6,
                    help="HIP streams (default priority) the independent tensors of a step are spread over")
+    p.add_argument("--select", choices=("batched", "single"), default="batched",
+                   help="batched: one bsr_score_select_batched call for all tensors of the step (a handful of "
+                        "launches); single: one bsr_score_select call per tensor on its stream")
     p.add_argument("--no-next-rows", action="store_true",
                    help="skip the measurements outside the timed step (per-sample ranking, row segments), "
                         "so that a profile of the run holds the step's kernels only")
@@ -130,6 +133,20 @@ def main():
                              dW=t["dW"], ws=t["ws"])
 
     phases = [("score_select", score_select), ("compress", compress), ("decompress", decompress), ("dw", dw)]
+    batched = args.select == "batched"
+    per_tensor = phases[1:] if batched else phases
+    if batched:
+        # scores and selection of all tensors of the step in one call: same masks, a handful of launches
+        sel = B.SelectBatch([t["X"] for t in tensors], [(t["spec"].br, t["spec"].bc) for t in tensors],
+                            [t["spec"].keep for t in tensors], keep_masks=[t["mask"] for t in tensors])
+        sel_ws = torch.empty(max(sel.ws_bytes, 256), dtype=torch.uint8, device=dev)
+
+    def score_select_all():
+        if batched:
+            B.bsr_score_select_batched(sel, ws=sel_ws)
+        else:
+            for t in tensors:
+                score_select(t)
 
     # The tensors of a step are independent: spread them over a few streams so that the
     # short dependent kernels of one tensor overlap with the others'.  Stream i waits for
@@ -150,9 +167,11 @@ def main():
 
     def step():
         main_stream = torch.cuda.current_stream()
+        if batched:
+            score_select_all()
         if not side:
             for t in tensors:
-                for _, f in phases:
+                for _, f in per_tensor:
                     f(t)
             return
         fork = torch.cuda.Event()
@@ -164,7 +183,7 @@ def main():
             for st, l in zip(side, per_stream):
                 if k < len(l):
                     with torch.cuda.stream(st):
-                        for _, f in phases:
+                        for _, f in per_tensor:
                             f(l[k])
         for st in side:
             done = torch.cuda.Event()
@@ -218,7 +237,10 @@ def main():
 
     phase_ms = {}
     for name, f in phases:
-        phase_ms[name] = timed(lambda: [f(t) for t in tensors], args.phase_reps)
+        if name == "score_select":
+            phase_ms[name] = timed(score_select_all, args.phase_reps)
+        else:
+            phase_ms[name] = timed(lambda: [f(t) for t in tensors], args.phase_reps)
 
     # ---- next row: the paper's local ranking (groups of block-rows select on their own) ----
     # One sample has 196 rows: 14 block-rows of 14 for the cross-patch input; 32 does not divide
@@ -348,6 +370,7 @@ def main():
                                "(xpatch 14x14, fc1 32x32, fc2 32x32), bf16, keep 0.5",
                    "tensors_per_step": len(tensors), "keep": keep, "streams": max(args.streams, 1),
                    "launch": "hip graph replay" if args.graph else "eager",
+                   "score_select": "one batched call per step" if batched else "one call per tensor",
                    "step": "score+select -> compress -> decompress -> dW for every tensor"},
         "phases": {
             "compress_GBps": round(comp_alg_bytes / (comp_ms * 1e-3) / 1e9, 2),

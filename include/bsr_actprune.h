@@ -197,6 +197,33 @@ int bsr_t_dense_matmul(const int32_t *row_ptr, const int32_t *col_idx,
                        size_t ws_bytes, void *stream);
 
 /*
+ * Several tensors per call (for instance the three pruned inputs of a residual
+ * block, or those of all blocks): exactly the masks (and scores) that
+ * bsr_score_select gives tensor by tensor, with a handful of kernel launches for
+ * the whole batch instead of two to three per tensor -- selection is bound by
+ * launch latency, not by work.  Every item is ranked on its own (Sec. IV: blocks
+ * are compared inside one activation only).  `items` is a host array that is
+ * read before the call returns; all tensors share `dtype`.  Workspace:
+ * bsr_score_select_batched_workspace_bytes(items, n, dtype) (0 for invalid items).
+ * Errors as for bsr_score_select, reported for the first offending item; nothing
+ * is launched if any item is invalid.
+ */
+typedef struct bsr_select_item {
+  const void *X;      /* device, [M x K], leading dimension ldx */
+  int64_t M, K, ldx;
+  int32_t br, bc;
+  double keep;
+  double *scores;     /* device, [nblocks], or NULL */
+  uint8_t *keep_mask; /* device, [nblocks] */
+} bsr_select_item;
+
+size_t bsr_score_select_batched_workspace_bytes(const bsr_select_item *items,
+                                                int n, int dtype);
+
+int bsr_score_select_batched(const bsr_select_item *items, int n, int dtype,
+                             void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Sec. VI (outlook) names a block-sparse version of ResMLP's affine scaling
  * layer, y[m,k] = alpha[k] * x[m,k] + beta[k].  Of its backward pass only the
  * scale gradient needs the saved input; from the pruned input in BSR form:

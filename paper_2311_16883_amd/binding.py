@@ -11,7 +11,7 @@ from __future__ import annotations
 
 import ctypes as C
 from pathlib import Path
-from typing import Optional, Tuple
+from typing import Sequence, Optional, Tuple
 
 import torch
 
@@ -30,7 +30,7 @@ EXPORTS = (
     "bsr_version", "bsr_error_string", "bsr_last_hip_error", "bsr_keep_count",
     "bsr_storage_bytes", "bsr_workspace_bytes", "bsr_score_select", "bsr_compress",
     "bsr_decompress", "bsr_t_dense_matmul", "bsr_grouped_keep_count", "bsr_score_select_grouped",
-    "bsr_affine_scale_grad",
+    "bsr_affine_scale_grad", "bsr_score_select_batched", "bsr_score_select_batched_workspace_bytes",
 )
 
 
@@ -80,6 +80,10 @@ def lib() -> C.CDLL:
     l.bsr_t_dense_matmul.restype = i32
     l.bsr_t_dense_matmul.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, vp, i64, i64, vp, i64, i32,
                                      vp, sz, vp]
+    l.bsr_score_select_batched_workspace_bytes.restype = sz
+    l.bsr_score_select_batched_workspace_bytes.argtypes = [vp, i32, i32]
+    l.bsr_score_select_batched.restype = i32
+    l.bsr_score_select_batched.argtypes = [vp, i32, i32, vp, sz, vp]
     l.bsr_affine_scale_grad.restype = i32
     l.bsr_affine_scale_grad.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, vp, i64, vp, i32, vp, sz, vp]
     _lib = l
@@ -297,3 +301,49 @@ def bsr_affine_scale_grad(row_ptr: torch.Tensor, col_idx: torch.Tensor, values: 
                                      _ptr(ws), ws.numel() if ws is not None else 0, _stream(stream))
     _check(rc, "bsr_affine_scale_grad")
     return dalpha
+
+
+class _SelectItem(C.Structure):
+    """Mirror of bsr_select_item."""
+    _fields_ = [("X", C.c_void_p), ("M", C.c_int64), ("K", C.c_int64), ("ldx", C.c_int64),
+                ("br", C.c_int32), ("bc", C.c_int32), ("keep", C.c_double),
+                ("scores", C.c_void_p), ("keep_mask", C.c_void_p)]
+
+
+class SelectBatch:
+    """The marshalled item array of one bsr_score_select_batched call; build it once for tensors
+    that stay where they are and pass it again every step.  Holds references to the tensors."""
+
+    def __init__(self, Xs: Sequence[torch.Tensor], blocks: Sequence[Tuple[int, int]], keeps: Sequence[float],
+                 keep_masks: Optional[Sequence[torch.Tensor]] = None,
+                 scores: Optional[Sequence[Optional[torch.Tensor]]] = None):
+        n = len(Xs)
+        if not (len(blocks) == len(keeps) == n) or n == 0:
+            raise ValueError("one block shape and one keep ratio per tensor")
+        self.dtype = dtype_code(Xs[0].dtype)
+        self.device = Xs[0].device
+        if keep_masks is None:
+            keep_masks = []
+            for X, (br, bc) in zip(Xs, blocks):
+                M, K, _ = _dense2d(X, "X")
+                keep_masks.append(torch.empty((-(-M // br)) * (-(-K // bc)), dtype=torch.uint8, device=X.device))
+        self.Xs, self.keep_masks, self.scores = list(Xs), list(keep_masks), list(scores) if scores else [None] * n
+        self.items = (_SelectItem * n)()
+        for i, (X, (br, bc), keep) in enumerate(zip(Xs, blocks, keeps)):
+            if dtype_code(X.dtype) != self.dtype:
+                raise BsrError(BSR_ERR_DTYPE, "all tensors of a batch share one dtype")
+            M, K, ldx = _dense2d(X, "X")
+            self.items[i] = _SelectItem(_ptr(X), M, K, ldx, br, bc, float(keep), _ptr(self.scores[i]),
+                                        _ptr(self.keep_masks[i]))
+        self.n = n
+        self.ws_bytes = int(lib().bsr_score_select_batched_workspace_bytes(self.items, n, self.dtype))
+
+
+def bsr_score_select_batched(batch: SelectBatch, *, ws: Optional[torch.Tensor] = None, stream=None):
+    """-> list of keep masks (uint8 [nblocks] each), the same as bsr_score_select tensor by tensor."""
+    if ws is None:
+        ws = _workspace(batch.ws_bytes, batch.device, None)
+    rc = lib().bsr_score_select_batched(batch.items, batch.n, batch.dtype, _ptr(ws),
+                                        ws.numel() if ws is not None else 0, _stream(stream))
+    _check(rc, "bsr_score_select_batched")
+    return batch.keep_masks

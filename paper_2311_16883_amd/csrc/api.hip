@@ -2,6 +2,7 @@
 // launches on the caller's stream.  See include/bsr_actprune.h for the contract
 // of every entry point.
 #include <cmath>
+#include <vector>
 
 #include "common.h"
 
@@ -250,6 +251,53 @@ int bsr_affine_scale_grad(const int32_t *row_ptr, const int32_t *col_idx, const 
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (M == 0) return launch_splitk_reduce(nullptr, 0, 1, K, dalpha, K, accumulate, s);
   return launch_affine_dscale(row_ptr, col_idx, values, dtype, M, K, br, bc, dY, lddy, dalpha, accumulate, ws, s);
+}
+
+size_t bsr_score_select_batched_workspace_bytes(const bsr_select_item *items, int n, int dtype) {
+  if (items == nullptr || n <= 0) return 0;
+  size_t total = 0;
+  for (int i = 0; i < n; ++i) {
+    Geometry g;
+    const bsr_select_item &it = items[i];
+    if (check_shape(dtype, it.M, it.K, it.ldx, it.br, it.bc, &g) != BSR_OK) return 0;
+    total += align_up(score_select_ws(g.nblocks), 256);
+  }
+  return total;
+}
+
+int bsr_score_select_batched(const bsr_select_item *items, int n, int dtype, void *ws, size_t ws_bytes,
+                             void *stream) {
+  if (n < 0) return BSR_ERR_SHAPE;
+  if (n == 0) return BSR_OK;
+  if (items == nullptr) return BSR_ERR_NULL;
+  std::vector<ScoreJob> score_jobs;
+  std::vector<SelectJob> select_jobs;
+  score_jobs.reserve(n);
+  select_jobs.reserve(n);
+  if (misaligned(ws, 16)) return BSR_ERR_ALIGN;
+  size_t off = 0;
+  for (int i = 0; i < n; ++i) {
+    const bsr_select_item &it = items[i];
+    Geometry g;
+    const int rc = check_shape(dtype, it.M, it.K, it.ldx, it.br, it.bc, &g);
+    if (rc != BSR_OK) return rc;
+    const int64_t n_keep = bsr_keep_count(g.nblocks, it.keep);
+    if (n_keep < 0) return BSR_ERR_KEEP;
+    if (g.nblocks == 0) continue;
+    if (it.X == nullptr || it.keep_mask == nullptr) return BSR_ERR_NULL;
+    if (misaligned(it.X, elem_bytes(dtype)) || misaligned(it.scores, 8)) return BSR_ERR_ALIGN;
+    const size_t need = align_up(score_select_ws(g.nblocks), 256);
+    if (ws == nullptr || off + need > ws_bytes) return BSR_ERR_WORKSPACE;
+    char *base = static_cast<char *>(ws) + off;
+    off += need;
+    double *sc = it.scores != nullptr ? it.scores : reinterpret_cast<double *>(base);
+    score_jobs.push_back(ScoreJob{it.X, it.M, it.K, it.ldx, it.br, it.bc, sc});
+    select_jobs.push_back(SelectJob{sc, g.nblocks, n_keep, it.keep_mask, base + scores_bytes(g.nblocks)});
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int rc = launch_score_batched(score_jobs.data(), (int)score_jobs.size(), dtype, s);
+  if (rc != BSR_OK) return rc;
+  return launch_select_batched(select_jobs.data(), (int)select_jobs.size(), s);
 }
 
 }  // extern "C"

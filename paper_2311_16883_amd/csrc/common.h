@@ -41,10 +41,28 @@ void set_hip_error(int e);
 int launch_score(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, int br, int bc,
                  double *scores, hipStream_t s);
 
+// several tensors scored with as few launches as their shapes allow
+struct ScoreJob {
+  const void *X;
+  int64_t M, K, ldx;
+  int br, bc;
+  double *scores;
+};
+int launch_score_batched(const ScoreJob *jobs, int n, int dtype, hipStream_t s);
+
 // select.hip: keep_mask = 1 for the n_keep best (score desc, index asc).
 size_t select_ws_bytes(int64_t nblocks);
 int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t *keep_mask, void *ws,
                   hipStream_t s);
+
+// several independent selections with as few launches as their sizes allow
+struct SelectJob {
+  const double *scores;
+  int64_t nblocks, n_keep;
+  uint8_t *mask;
+  void *ws;            // select_ws_bytes(nblocks) bytes of its own
+};
+int launch_select_batched(const SelectJob *jobs, int n, hipStream_t s);
 
 // per-group selection: groups of group_rows block-rows, n_keep_group kept per full group
 int launch_select_grouped(const double *scores, int64_t nbr, int64_t nbc, int64_t group_rows,

@@ -23,10 +23,12 @@ struct ScoreGeom {
   int nchunks;
 };
 
+// bx, by, gy: the workgroup's place in its tensor's (chunks x passes) grid.  Threads beyond
+// g.vct * g.gb * g.rb (a batched launch runs every tensor with 256) find no row group and idle.
 template <typename T, int V>
-__global__ __launch_bounds__(kScoreThreads) void score_kernel(
+__device__ __forceinline__ void score_body(
     const T *__restrict__ X, int64_t M, int64_t K, int64_t ldx, int br, int bc, int64_t nbr,
-    int64_t nbc, ScoreGeom g, double *__restrict__ scores) {
+    int64_t nbc, const ScoreGeom &g, double *__restrict__ scores, uint32_t bx, uint32_t by, uint32_t gy) {
   __shared__ double part[kScoreThreads];
   const int t = threadIdx.x;
   const int lane_col = t % g.vct;          // vector column inside the chunk
@@ -35,10 +37,10 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
   const int gr = grp % g.gb;               // row group inside the block-row
   const int jj = lane_col / g.vpbt;        // block-column inside the chunk
   const int vpb = bc / V;                  // vectors per block row
-  const int64_t j = (int64_t)blockIdx.x * g.jc + jj;
+  const int64_t j = (int64_t)bx * g.jc + jj;
   const int64_t col0 = j * bc;
 
-  for (int64_t pass = blockIdx.y; pass * g.rb < nbr; pass += gridDim.y) {
+  for (int64_t pass = by; pass * g.rb < nbr; pass += gy) {
     const int64_t i = pass * g.rb + ib;
     double acc = 0.0;
     if (ib < g.rb && i < nbr && j < nbc) {
@@ -77,7 +79,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
     // one lane per (block-row, block-column) of this pass adds the partials
     if (t < g.rb * g.jc) {
       const int oib = t / g.jc, ojj = t % g.jc;
-      const int64_t oi = pass * g.rb + oib, oj = (int64_t)blockIdx.x * g.jc + ojj;
+      const int64_t oi = pass * g.rb + oib, oj = (int64_t)bx * g.jc + ojj;
       if (oi < nbr && oj < nbc) {
         double s = 0.0;
         for (int a = 0; a < g.gb; ++a)
@@ -89,21 +91,53 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
   }
 }
 
+template <typename T, int V>
+__global__ __launch_bounds__(kScoreThreads) void score_kernel(
+    const T *__restrict__ X, int64_t M, int64_t K, int64_t ldx, int br, int bc, int64_t nbr,
+    int64_t nbc, ScoreGeom g, double *__restrict__ scores) {
+  score_body<T, V>(X, M, K, ldx, br, bc, nbr, nbc, g, scores, blockIdx.x, blockIdx.y, gridDim.y);
+}
+
+// Several tensors per launch: workgroup w belongs to the tensor whose range of
+// workgroups holds w; the tensors' parameters come with the kernel arguments.
+constexpr int kScoreBatchMax = 24;
+struct ScoreItem {
+  const void *X;
+  double *scores;
+  int64_t M, K, ldx, nbr, nbc;
+  int br, bc;
+  ScoreGeom g;
+  uint32_t wg_begin, gy;
+};
+struct ScoreBatch {
+  ScoreItem it[kScoreBatchMax];
+};
+
+template <typename T, int V>
+__global__ __launch_bounds__(kScoreThreads) void score_batched_kernel(ScoreBatch b, int n) {
+  int i = 0;
+  while (i + 1 < n && blockIdx.x >= b.it[i + 1].wg_begin) ++i;
+  const ScoreItem &it = b.it[i];
+  const uint32_t local = blockIdx.x - it.wg_begin;
+  score_body<T, V>(static_cast<const T *>(it.X), it.M, it.K, it.ldx, it.br, it.bc, it.nbr, it.nbc, it.g, it.scores,
+                   local % (uint32_t)it.g.nchunks, local / (uint32_t)it.g.nchunks, it.gy);
+}
+
 // Narrow blocks (rows shorter than a 16-byte vector, e.g. 14x14 patches) and blocks
 // of few rows (1 x b row segments) on contiguous matrix rows: a workgroup reads the rows of g.rb block-rows as one
 // linear span into LDS, then a thread per (matrix row, block-column, piece of 32
 // elements) adds that piece's squares left to right, and a thread per block adds
 // the pieces row by row.  LDS layout: span | partial sums (binary64).
 template <typename T, typename V>
-__global__ __launch_bounds__(256) void score_span_kernel(const uint8_t *__restrict__ X, int64_t M, int64_t K,
-                                                         int bc, int64_t nbr, SpanGeom g, size_t span_words,
-                                                         int pieces, uint32_t magic_pieces,
-                                                         double *__restrict__ scores) {
+__device__ __forceinline__ void score_span_body(const uint8_t *__restrict__ X, int64_t M, int64_t K, int bc,
+                                                int64_t nbr, const SpanGeom &g, size_t span_words, int pieces,
+                                                uint32_t magic_pieces, double *__restrict__ scores,
+                                                uint32_t wg) {
   constexpr int kVecs = kSpanBytes / (int)sizeof(V) / 256;
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   double *part = reinterpret_cast<double *>(lds + span_words);
   const int t = threadIdx.x;
-  const int64_t i0 = (int64_t)blockIdx.x * g.rb;
+  const int64_t i0 = (int64_t)wg * g.rb;
   const int nb = (int)((nbr - i0) < g.rb ? (nbr - i0) : g.rb);
   const int64_t m0 = i0 * g.br;
   const int rows = (int)((M - m0) < (int64_t)nb * g.br ? (M - m0) : (int64_t)nb * g.br);
@@ -144,6 +178,36 @@ __global__ __launch_bounds__(256) void score_span_kernel(const uint8_t *__restri
       for (int u = 0; u < pieces; ++u) sum += part[(((int)b * g.br + r) * g.nbc + (int)j) * pieces + u];
     scores[(i0 + b) * g.nbc + j] = sum;
   }
+}
+
+template <typename T, typename V>
+__global__ __launch_bounds__(256) void score_span_kernel(const uint8_t *__restrict__ X, int64_t M, int64_t K,
+                                                         int bc, int64_t nbr, SpanGeom g, size_t span_words,
+                                                         int pieces, uint32_t magic_pieces,
+                                                         double *__restrict__ scores) {
+  score_span_body<T, V>(X, M, K, bc, nbr, g, span_words, pieces, magic_pieces, scores, blockIdx.x);
+}
+
+struct SpanScoreItem {
+  const uint8_t *X;
+  double *scores;
+  int64_t M, K, nbr;
+  SpanGeom g;
+  uint32_t span_words, magic_pieces;
+  int bc, pieces;
+  uint32_t wg_begin;
+};
+struct SpanScoreBatch {
+  SpanScoreItem it[kScoreBatchMax];
+};
+
+template <typename T, typename V>
+__global__ __launch_bounds__(256) void score_span_batched_kernel(SpanScoreBatch b, int n) {
+  int i = 0;
+  while (i + 1 < n && blockIdx.x >= b.it[i + 1].wg_begin) ++i;
+  const SpanScoreItem &it = b.it[i];
+  score_span_body<T, V>(it.X, it.M, it.K, it.bc, it.nbr, it.g, it.span_words, it.pieces, it.magic_pieces, it.scores,
+                        blockIdx.x - it.wg_begin);
 }
 
 // Few-row blocks whose row segments are whole 16-byte vectors (1 x b row segments):
@@ -222,9 +286,8 @@ int run_score_span(const void *X, int64_t M, int64_t K, int bc, const SpanGeom &
   return check_launch();
 }
 
-template <typename T, int V>
-int run_score(const void *X, int64_t M, int64_t K, int64_t ldx, int br, int bc, double *scores,
-              hipStream_t s) {
+// Launch geometry of score_kernel for vectors of V elements; *gy = passes of the grid.
+ScoreGeom score_geometry(int V, int64_t M, int64_t K, int br, int bc, int64_t *gy_out) {
   const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
   ScoreGeom g;
   const int vpb = bc / V;
@@ -248,9 +311,62 @@ int run_score(const void *X, int64_t M, int64_t K, int64_t ldx, int br, int bc, 
   const int64_t cap = ceil_div(16384, g.nchunks);
   if (gy > cap) gy = cap;
   if (gy > 65535) gy = 65535;
+  *gy_out = gy;
+  return g;
+}
+
+template <typename T, int V>
+int run_score(const void *X, int64_t M, int64_t K, int64_t ldx, int br, int bc, double *scores,
+              hipStream_t s) {
+  const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
+  int64_t gy;
+  const ScoreGeom g = score_geometry(V, M, K, br, bc, &gy);
   dim3 grid((unsigned)g.nchunks, (unsigned)gy, 1);
   hipLaunchKernelGGL((score_kernel<T, V>), grid, dim3(g.vct * g.gb * g.rb), 0, s,
                      static_cast<const T *>(X), M, K, ldx, br, bc, nbr, nbc, g, scores);
+  return check_launch();
+}
+
+// Which kernel scores a tensor: 0 = score_kernel with vectors of `key` elements,
+// 1 = score_span_kernel with `key`-byte accesses, 2 = score_rows_kernel.
+int score_kind(int dtype, const void *X, int64_t M, int64_t K, int64_t ldx, int br, int bc, SpanGeom *g, int *key) {
+  if (span_geometry(dtype, M, K, ldx, br, bc, X, nullptr, g) &&
+      (int64_t)g->rb * br * g->nbc * ((bc + 31) / 32) <= 6144) {
+    *key = g->vb;
+    return (g->vb == 16 && g->seg_words % 4 == 0) ? 2 : 1;
+  }
+  *key = dtype == BSR_F32 ? pick_vector(4, 4, bc, K, ldx, X) : pick_vector(8, 2, bc, K, ldx, X);
+  return 0;
+}
+
+template <typename T>
+int launch_generic_batch(const ScoreBatch &b, int n, uint32_t wgs, int v, hipStream_t s) {
+  const dim3 grid(wgs), block(kScoreThreads);
+  if (sizeof(T) == 4) {
+    switch (v) {
+      case 4: hipLaunchKernelGGL((score_batched_kernel<float, 4>), grid, block, 0, s, b, n); break;
+      case 2: hipLaunchKernelGGL((score_batched_kernel<float, 2>), grid, block, 0, s, b, n); break;
+      default: hipLaunchKernelGGL((score_batched_kernel<float, 1>), grid, block, 0, s, b, n); break;
+    }
+  } else {
+    switch (v) {
+      case 8: hipLaunchKernelGGL((score_batched_kernel<uint16_t, 8>), grid, block, 0, s, b, n); break;
+      case 4: hipLaunchKernelGGL((score_batched_kernel<uint16_t, 4>), grid, block, 0, s, b, n); break;
+      case 2: hipLaunchKernelGGL((score_batched_kernel<uint16_t, 2>), grid, block, 0, s, b, n); break;
+      default: hipLaunchKernelGGL((score_batched_kernel<uint16_t, 1>), grid, block, 0, s, b, n); break;
+    }
+  }
+  return check_launch();
+}
+
+template <typename T>
+int launch_span_batch(const SpanScoreBatch &b, int n, uint32_t wgs, size_t lds, int vb, hipStream_t s) {
+  const dim3 grid(wgs), block(256);
+  switch (vb) {
+    case 16: hipLaunchKernelGGL((score_span_batched_kernel<T, uint4>), grid, block, lds, s, b, n); break;
+    case 8: hipLaunchKernelGGL((score_span_batched_kernel<T, uint2>), grid, block, lds, s, b, n); break;
+    default: hipLaunchKernelGGL((score_span_batched_kernel<T, uint32_t>), grid, block, lds, s, b, n); break;
+  }
   return check_launch();
 }
 
@@ -278,6 +394,85 @@ int launch_score(const void *X, int dtype, int64_t M, int64_t K, int64_t ldx, in
     case 2: return run_score<uint16_t, 2>(X, M, K, ldx, br, bc, scores, s);
     default: return run_score<uint16_t, 1>(X, M, K, ldx, br, bc, scores, s);
   }
+}
+
+int launch_score_batched(const ScoreJob *jobs, int n, int dtype, hipStream_t s) {
+  // tensors that take the same kernel instance share launches of up to kScoreBatchMax tensors
+  static const int kKeys[2][4] = {{8, 4, 2, 1}, {16, 8, 4, 0}};
+  for (int kind = 0; kind < 2; ++kind) {
+    for (int ki = 0; ki < 4; ++ki) {
+      const int want_key = kKeys[kind][ki];
+      if (want_key == 0) continue;
+      ScoreBatch gb;
+      SpanScoreBatch sb;
+      int m = 0;
+      uint32_t wgs = 0;
+      size_t lds = 0;
+      auto flush = [&]() -> int {
+        if (m == 0) return BSR_OK;
+        int rc;
+        if (kind == 0)
+          rc = dtype == BSR_F32 ? launch_generic_batch<float>(gb, m, wgs, want_key, s)
+                                : launch_generic_batch<uint16_t>(gb, m, wgs, want_key, s);
+        else
+          rc = dtype == BSR_F32 ? launch_span_batch<float>(sb, m, wgs, lds, want_key, s)
+                                : launch_span_batch<uint16_t>(sb, m, wgs, lds, want_key, s);
+        m = 0;
+        wgs = 0;
+        lds = 0;
+        return rc;
+      };
+      for (int i = 0; i < n; ++i) {
+        const ScoreJob &j = jobs[i];
+        if (j.M == 0 || j.K == 0) continue;
+        SpanGeom g;
+        int key;
+        const int k = score_kind(dtype, j.X, j.M, j.K, j.ldx, j.br, j.bc, &g, &key);
+        if (k == 2) {                                        // register-resident row segments: one by one
+          if (kind == 0 && ki == 0) {
+            const int rc = launch_score(j.X, dtype, j.M, j.K, j.ldx, j.br, j.bc, j.scores, s);
+            if (rc != BSR_OK) return rc;
+          }
+          continue;
+        }
+        if (k != kind || key != want_key) continue;
+        const int64_t nbr = ceil_div(j.M, j.br), nbc = ceil_div(j.K, j.bc);
+        if (kind == 0) {
+          ScoreItem &it = gb.it[m];
+          int64_t gy;
+          it.g = score_geometry(key, j.M, j.K, j.br, j.bc, &gy);
+          it.X = j.X;
+          it.scores = j.scores;
+          it.M = j.M; it.K = j.K; it.ldx = j.ldx; it.nbr = nbr; it.nbc = nbc;
+          it.br = j.br; it.bc = j.bc;
+          it.wg_begin = wgs;
+          it.gy = (uint32_t)gy;
+          wgs += (uint32_t)(it.g.nchunks * gy);
+        } else {
+          SpanScoreItem &it = sb.it[m];
+          it.g = g;
+          it.X = static_cast<const uint8_t *>(j.X);
+          it.scores = j.scores;
+          it.M = j.M; it.K = j.K; it.nbr = nbr;
+          it.bc = j.bc;
+          it.pieces = (j.bc + 31) / 32;
+          it.magic_pieces = (uint32_t)(((uint64_t(1) << 32) + it.pieces - 1) / it.pieces);
+          it.span_words = (uint32_t)align_up((size_t)g.rb * g.br * g.row_words, 4);
+          const size_t need = (size_t)it.span_words * 4 + (size_t)g.rb * g.br * g.nbc * it.pieces * sizeof(double);
+          if (need > lds) lds = need;
+          it.wg_begin = wgs;
+          wgs += (uint32_t)ceil_div(nbr, g.rb);
+        }
+        if (++m == kScoreBatchMax) {
+          const int rc = flush();
+          if (rc != BSR_OK) return rc;
+        }
+      }
+      const int rc = flush();
+      if (rc != BSR_OK) return rc;
+    }
+  }
+  return BSR_OK;
 }
 
 }  // namespace bsr

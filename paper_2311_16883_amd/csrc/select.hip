@@ -371,24 +371,19 @@ __device__ void bracketed_select(const Source &src, uint32_t n, uint32_t want_to
 // as the bracket of bracketed_select: codes linear in the key, a radix pass or
 // two, exact ranking of what shares the threshold's code.  The last group may be
 // shorter (last_blocks, keeping n_keep_last).
+// One workgroup selects the `want` best of the n scores at `scores` into gmask.
 template <int THREADS, int KPT, int DB>
-__global__ __launch_bounds__(THREADS) void select_groups_kernel(
-    const double *__restrict__ scores, uint32_t group_blocks, uint32_t n_keep_group, uint32_t last_blocks,
-    uint32_t n_keep_last, uint8_t *__restrict__ mask) {
+__device__ __forceinline__ void select_one_group(const double *__restrict__ scores, uint32_t n, uint32_t want,
+                                                 uint8_t *__restrict__ gmask) {
   __shared__ SelectShared sh;
   __shared__ BracketShared bs;
   __shared__ uint64_t wave_min[THREADS / 64], wave_max[THREADS / 64];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const bool last = blockIdx.x == gridDim.x - 1;
-  const uint32_t n = last ? last_blocks : group_blocks;
-  const uint32_t want = last ? n_keep_last : n_keep_group;
-  const size_t off = (size_t)blockIdx.x * group_blocks;
-  uint8_t *gmask = mask + off;
   if (want == 0 || want >= n) {
     for (uint32_t e = t; e < n; e += THREADS) gmask[e] = want > 0 ? 1 : 0;
     return;
   }
-  AllScores src{scores + off};
+  AllScores src{scores};
   uint64_t mn = ~0ull, mx = 0ull;
 #pragma unroll
   for (int i = 0; i < KPT; ++i) {
@@ -415,6 +410,16 @@ __global__ __launch_bounds__(THREADS) void select_groups_kernel(
   bracketed_select<THREADS, KPT, DB>(src, n, want, mn, mx, n, gmask, sh, bs);
 }
 
+template <int THREADS, int KPT, int DB>
+__global__ __launch_bounds__(THREADS) void select_groups_kernel(
+    const double *__restrict__ scores, uint32_t group_blocks, uint32_t n_keep_group, uint32_t last_blocks,
+    uint32_t n_keep_last, uint8_t *__restrict__ mask) {
+  const bool last = blockIdx.x == gridDim.x - 1;
+  const size_t off = (size_t)blockIdx.x * group_blocks;
+  select_one_group<THREADS, KPT, DB>(scores + off, last ? last_blocks : group_blocks,
+                                     last ? n_keep_last : n_keep_group, mask + off);
+}
+
 // Control block shared by the two grid-wide passes (lives in the workspace;
 // written by workgroup 0 of pass 1).
 struct SelectCtrl {
@@ -432,9 +437,9 @@ __device__ __forceinline__ uint32_t bucket_of(uint64_t key, uint64_t lo, uint64_
 // trips) or kSample = 256 (ranked through LDS; a tighter bracket for very large
 // inputs, where the threshold bucket must still fit the candidate ranking).
 template <int NS>
-__global__ __launch_bounds__(kGridThreads) void select_count_kernel(
+__device__ __forceinline__ void select_count_body(
     const double *__restrict__ scores, uint32_t nblocks, uint32_t n_keep, uint32_t per_wg,
-    uint32_t *__restrict__ counts, SelectCtrl *__restrict__ ctrl) {
+    uint32_t *__restrict__ counts, SelectCtrl *__restrict__ ctrl, uint32_t wg) {
   __shared__ uint32_t hist[kBuckets];
   __shared__ uint64_t sample[kSample];
   __shared__ uint64_t bracket[2];
@@ -442,7 +447,7 @@ __global__ __launch_bounds__(kGridThreads) void select_count_kernel(
   constexpr int kKeys = 4;                        // keys per thread held in registers (per_wg <= 1024)
 
   // this workgroup's slice (loads in flight while the sample is ranked)
-  const uint32_t e0 = blockIdx.x * per_wg;
+  const uint32_t e0 = wg * per_wg;
   const uint32_t e1 = (e0 + per_wg) < nblocks ? (e0 + per_wg) : nblocks;
   double raw[kKeys];
 #pragma unroll
@@ -494,7 +499,7 @@ __global__ __launch_bounds__(kGridThreads) void select_count_kernel(
   uint32_t shift = range == 0 ? 0u : (uint32_t)(64 - __clzll((long long)range));   // bit length of range
   shift = shift > 8 ? shift - 8 : 0u;
   if ((range >> shift) > (uint64_t)(kBuckets - 3)) ++shift;
-  if (blockIdx.x == 0 && t == 0) {
+  if (wg == 0 && t == 0) {
     ctrl->ticket = 0;
     ctrl->n_cand = 0;
     ctrl->shift = shift;
@@ -517,13 +522,26 @@ __global__ __launch_bounds__(kGridThreads) void select_count_kernel(
       if (eb + i * kGridThreads < e1) atomicAdd(&hist[bucket_of(score_key(more[i]), lo, hi, shift)], 1u);
   }
   __syncthreads();
-  counts[blockIdx.x * kBuckets + t] = hist[t];
+  counts[wg * kBuckets + t] = hist[t];
 }
 
-__global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
+template <int NS>
+__global__ __launch_bounds__(kGridThreads) void select_count_kernel(
+    const double *__restrict__ scores, uint32_t nblocks, uint32_t n_keep, uint32_t per_wg,
+    uint32_t *__restrict__ counts, SelectCtrl *__restrict__ ctrl) {
+  select_count_body<NS>(scores, nblocks, n_keep, per_wg, counts, ctrl, blockIdx.x);
+}
+
+// MODE 0: the whole pass in one kernel (the last workgroup to finish, found by an atomic
+// ticket, selects among the candidates).  MODE 1: classification only; MODE 2: only the
+// selection among the candidates, by one workgroup of a later launch -- for batches, where a
+// release fence per workgroup (an L2 write-back on this GPU) costs more than a launch.
+template <int MODE>
+__device__ __forceinline__ void select_classify_body(
     const double *__restrict__ scores, uint32_t nblocks, uint32_t n_keep, uint32_t per_wg,
     const uint32_t *__restrict__ counts, SelectCtrl *__restrict__ ctrl,
-    uint64_t *__restrict__ cand_key, uint32_t *__restrict__ cand_idx, uint8_t *__restrict__ mask) {
+    uint64_t *__restrict__ cand_key, uint32_t *__restrict__ cand_idx, uint8_t *__restrict__ mask,
+    uint32_t wg, uint32_t nwgs) {
   __shared__ SelectShared sh;
   __shared__ BracketShared bs;
   __shared__ uint32_t is_last, wg_cand, wg_base;
@@ -532,24 +550,26 @@ __global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
   const uint64_t lo = ctrl->lo, hi = ctrl->hi;
   constexpr int kKeys = 4;                        // keys per thread loaded up front (per_wg <= 1024 as a rule)
 
-  const uint32_t e0 = blockIdx.x * per_wg;
+  const uint32_t e0 = wg * per_wg;
   const uint32_t e1 = (e0 + per_wg) < nblocks ? (e0 + per_wg) : nblocks;
   double raw[kKeys];
+  if constexpr (MODE != 2) {
 #pragma unroll
-  for (int i = 0; i < kKeys; ++i) {
-    const uint32_t e = e0 + t + i * kGridThreads;
-    raw[i] = scores[e < e1 ? e : e0];
+    for (int i = 0; i < kKeys; ++i) {
+      const uint32_t e = e0 + t + i * kGridThreads;
+      raw[i] = scores[e < e1 ? e : e0];
+    }
   }
   if (t == 0) wg_cand = 0;
 
   // the bucket that holds the n_keep-th largest key (same answer in every workgroup):
   // thread t owns bucket kBuckets-1-t, the scan runs from the top
   uint32_t own = 0;
-  for (uint32_t w0 = 0; w0 < gridDim.x; w0 += 64) {       // 64 independent loads in flight per round
+  for (uint32_t w0 = 0; w0 < nwgs; w0 += 64) {       // 64 independent loads in flight per round
     uint32_t part[64];
 #pragma unroll
     for (uint32_t w = 0; w < 64; ++w)
-      part[w] = w0 + w < gridDim.x ? counts[(w0 + w) * kBuckets + (kBuckets - 1 - t)] : 0u;
+      part[w] = w0 + w < nwgs ? counts[(w0 + w) * kBuckets + (kBuckets - 1 - t)] : 0u;
 #pragma unroll
     for (uint32_t w = 0; w < 64; ++w) own += part[w];
   }
@@ -562,6 +582,7 @@ __global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
   const uint32_t bucket = sh.digit, above = sh.above;
   __syncthreads();
 
+  if constexpr (MODE != 2) {
   // other buckets: mask bytes; the threshold's bucket: this workgroup's candidates
   // go to LDS first, so the global list takes one atomic per workgroup
   auto classify = [&](uint32_t e, uint64_t key) {
@@ -604,12 +625,16 @@ __global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
     cand_key[wg_base + c] = sh.ckey[c];
     cand_idx[wg_base + c] = sh.cidx[c];
   }
-  __threadfence();
-  __syncthreads();
-  if (t == 0) is_last = (atomicAdd(&ctrl->ticket, 1u) == gridDim.x - 1) ? 1u : 0u;
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
+  }
+  if constexpr (MODE == 1) return;
+  if constexpr (MODE == 0) {
+    __threadfence();
+    __syncthreads();
+    if (t == 0) is_last = (atomicAdd(&ctrl->ticket, 1u) == nwgs - 1) ? 1u : 0u;
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+  }
 
   // last workgroup: the candidates all lie in the threshold bucket's key range,
   // which serves as the bracket of their exact selection
@@ -641,6 +666,59 @@ __global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
   } else {
     radix_select<kGridThreads>(src, n, n_keep - above, nblocks, mask, sh);
   }
+}
+
+__global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
+    const double *__restrict__ scores, uint32_t nblocks, uint32_t n_keep, uint32_t per_wg,
+    const uint32_t *__restrict__ counts, SelectCtrl *__restrict__ ctrl,
+    uint64_t *__restrict__ cand_key, uint32_t *__restrict__ cand_idx, uint8_t *__restrict__ mask) {
+  select_classify_body<0>(scores, nblocks, n_keep, per_wg, counts, ctrl, cand_key, cand_idx, mask, blockIdx.x,
+                          gridDim.x);
+}
+
+// ---- several independent selections per launch (one per tensor of a batch) ----
+// The kernels above with blockIdx.y (grid-wide passes) or blockIdx.x (one workgroup
+// per selection) naming the selection; its parameters come from the kernel
+// arguments.  Selection is bound by launch and fence latency, not by work, so a
+// batch costs about as much as one selection.
+constexpr int kBatchMax = 24;
+struct SelectItem {
+  const double *scores;
+  uint8_t *mask;
+  uint32_t nblocks, n_keep, per_wg, wgs;
+  uint32_t *counts;
+  SelectCtrl *ctrl;
+  uint64_t *cand_key;
+  uint32_t *cand_idx;
+};
+struct SelectBatch {
+  SelectItem it[kBatchMax];
+};
+
+template <int NS>
+__global__ __launch_bounds__(kGridThreads) void select_count_batched_kernel(SelectBatch b) {
+  const SelectItem &it = b.it[blockIdx.y];
+  if (blockIdx.x >= it.wgs) return;
+  select_count_body<NS>(it.scores, it.nblocks, it.n_keep, it.per_wg, it.counts, it.ctrl, blockIdx.x);
+}
+
+__global__ __launch_bounds__(kGridThreads) void select_classify_batched_kernel(SelectBatch b) {
+  const SelectItem &it = b.it[blockIdx.y];
+  if (blockIdx.x >= it.wgs) return;
+  select_classify_body<1>(it.scores, it.nblocks, it.n_keep, it.per_wg, it.counts, it.ctrl, it.cand_key,
+                          it.cand_idx, it.mask, blockIdx.x, it.wgs);
+}
+
+__global__ __launch_bounds__(kGridThreads) void select_finish_batched_kernel(SelectBatch b) {
+  const SelectItem &it = b.it[blockIdx.x];
+  select_classify_body<2>(it.scores, it.nblocks, it.n_keep, it.per_wg, it.counts, it.ctrl, it.cand_key,
+                          it.cand_idx, it.mask, 0u, it.wgs);
+}
+
+template <int THREADS, int KPT, int DB>
+__global__ __launch_bounds__(THREADS) void select_small_batched_kernel(SelectBatch b) {
+  const SelectItem &it = b.it[blockIdx.x];
+  select_one_group<THREADS, KPT, DB>(it.scores, it.nblocks, it.n_keep, it.mask);
 }
 
 __global__ void fill_u8_kernel(uint8_t *p, int64_t n, uint8_t v) {
@@ -749,6 +827,100 @@ int launch_select_grouped(const double *scores, int64_t nbr, int64_t nbc, int64_
                        scores, (uint32_t)group_blocks, (uint32_t)n_keep_group, (uint32_t)last_blocks,
                        (uint32_t)n_keep_last, keep_mask);
   return check_launch();
+}
+
+int launch_select_batched(const SelectJob *jobs, int n, hipStream_t s) {
+  // classes: 0 one workgroup <= 1024 blocks, 1 <= 8192, 2 <= 12288, 3 grid-wide with the
+  // 64-key sample, 4 grid-wide with the 256-key sample; everything else goes one by one
+  for (int cls = 0; cls < 5; ++cls) {
+    SelectBatch b;
+    int m = 0;
+    uint32_t max_wgs = 0;
+    auto flush = [&]() -> int {
+      if (m == 0) return BSR_OK;
+      switch (cls) {
+        case 0:
+          hipLaunchKernelGGL((select_small_batched_kernel<256, 4, 8>), dim3(m), dim3(256), 0, s, b);
+          break;
+        case 1:
+          hipLaunchKernelGGL((select_small_batched_kernel<1024, 8, kDigitBits>), dim3(m), dim3(1024), 0, s, b);
+          break;
+        case 2:
+          hipLaunchKernelGGL((select_small_batched_kernel<1024, 12, kDigitBits>), dim3(m), dim3(1024), 0, s, b);
+          break;
+        default:
+          if (cls == 3)
+            hipLaunchKernelGGL(select_count_batched_kernel<64>, dim3(max_wgs, m), dim3(kGridThreads), 0, s, b);
+          else
+            hipLaunchKernelGGL(select_count_batched_kernel<kSample>, dim3(max_wgs, m), dim3(kGridThreads), 0, s, b);
+          {
+            const int rc = check_launch();
+            if (rc != BSR_OK) return rc;
+          }
+          hipLaunchKernelGGL(select_classify_batched_kernel, dim3(max_wgs, m), dim3(kGridThreads), 0, s, b);
+          {
+            const int rc = check_launch();
+            if (rc != BSR_OK) return rc;
+          }
+          hipLaunchKernelGGL(select_finish_batched_kernel, dim3(m), dim3(kGridThreads), 0, s, b);
+          break;
+      }
+      m = 0;
+      max_wgs = 0;
+      return check_launch();
+    };
+    for (int i = 0; i < n; ++i) {
+      const SelectJob &j = jobs[i];
+      if (j.nblocks == 0) continue;
+      const bool degenerate = j.n_keep <= 0 || j.n_keep >= j.nblocks;
+      int c;
+      if (degenerate) c = -1;
+      else if (j.nblocks <= 1024) c = 0;
+      else if (j.nblocks <= 8192) c = 1;
+      else if (j.nblocks <= kSmallLimit) c = 2;
+      else if (j.nblocks <= 262144) c = 3;
+      else c = 4;
+      if (c == -1) {
+        if (cls == 0) {                                      // all kept / none kept: a fill, once
+          const int rc = launch_select(j.scores, j.nblocks, j.n_keep, j.mask, j.ws, s);
+          if (rc != BSR_OK) return rc;
+        }
+        continue;
+      }
+      if (c != cls) continue;
+      SelectItem &it = b.it[m];
+      it.scores = j.scores;
+      it.mask = j.mask;
+      it.nblocks = (uint32_t)j.nblocks;
+      it.n_keep = (uint32_t)j.n_keep;
+      it.per_wg = 0;
+      it.wgs = 1;
+      it.counts = nullptr;
+      it.ctrl = nullptr;
+      it.cand_key = nullptr;
+      it.cand_idx = nullptr;
+      if (cls >= 3) {
+        const SelectPlan p = select_plan(j.nblocks);
+        char *base = static_cast<char *>(j.ws);
+        it.counts = reinterpret_cast<uint32_t *>(base + p.counts_off);
+        it.ctrl = reinterpret_cast<SelectCtrl *>(base + p.ctrl_off);
+        it.cand_key = reinterpret_cast<uint64_t *>(base + p.key_off);
+        it.cand_idx = reinterpret_cast<uint32_t *>(base + p.idx_off);
+        int64_t wgs = ceil_div(j.nblocks, 1024);
+        if (wgs > kMaxGridWgs) wgs = kMaxGridWgs;
+        it.wgs = (uint32_t)wgs;
+        it.per_wg = (uint32_t)ceil_div(j.nblocks, wgs);
+        if (it.wgs > max_wgs) max_wgs = it.wgs;
+      }
+      if (++m == kBatchMax) {
+        const int rc = flush();
+        if (rc != BSR_OK) return rc;
+      }
+    }
+    const int rc = flush();
+    if (rc != BSR_OK) return rc;
+  }
+  return BSR_OK;
 }
 
 }  // namespace bsr

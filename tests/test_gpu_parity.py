@@ -438,3 +438,74 @@ def test_affine_scale_grad_empty_inputs():
     B.bsr_affine_scale_grad(rp, ci, val, 0, 64, 16, 16, G, dalpha=out)                       # no rows: zero
     torch.cuda.synchronize()
     assert not out.cpu().numpy().any()
+
+
+# ----------------------------------------------------------------------------
+# several tensors per call
+# ----------------------------------------------------------------------------
+
+BATCH_BF16 = [
+    # M, K, br, bc, keep
+    (2744, 196, 14, 14, 0.5),       # LDS-staged scoring, one workgroup selects (2744 blocks)
+    (6272, 384, 32, 32, 0.5),       # 2352 blocks
+    (25088, 384, 32, 32, 0.5),      # 9408 blocks: twelve keys per thread
+    (6272, 1536, 32, 32, 0.25),     # 9408 blocks again, another keep ratio
+    (8192, 1536, 32, 32, 0.5),      # 12288 blocks: the last single-workgroup size
+    (12544, 1536, 32, 32, 0.5),     # 18816 blocks: grid-wide passes
+    (4096, 1536, 8, 8, 0.9),        # 98304 blocks: grid-wide, long slices
+    (3000, 384, 1, 32, 0.5),        # row segments: scored one by one inside the call
+    (512, 128, 16, 16, 1.0),        # everything kept
+    (512, 128, 16, 16, 0.0),        # nothing kept
+    (640, 256, 16, 16, 0.3),        # 640 blocks: the 256-thread selection
+    (1030, 130, 8, 8, 0.35),        # ragged, LDS-staged with 8-byte accesses
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_batched_score_select_equals_single_calls(dtype):
+    cases = BATCH_BF16 if dtype == "bf16" else [c for c in BATCH_BF16 if c[0] * c[1] <= 4_000_000]
+    Xs_host = [rand_pair(M, K, 8, dtype, seed=100 + i)[0] for i, (M, K, br, bc, keep) in enumerate(cases)]
+    Xs = [to_dev(X) for X in Xs_host]
+    want_scores = [torch.empty(oracle.grid(M, K, br, bc)[0] * oracle.grid(M, K, br, bc)[1], dtype=torch.float64,
+                               device="cuda") if i % 2 == 0 else None
+                   for i, (M, K, br, bc, keep) in enumerate(cases)]
+    batch = B.SelectBatch(Xs, [(c[2], c[3]) for c in cases], [c[4] for c in cases], scores=want_scores)
+    masks = B.bsr_score_select_batched(batch)
+    torch.cuda.synchronize()
+    first = [m.cpu().numpy().copy() for m in masks]
+    for m in masks:
+        m.fill_(7)
+    masks = B.bsr_score_select_batched(batch)                       # again: the workspace carries nothing over
+    torch.cuda.synchronize()
+    for i, ((M, K, br, bc, keep), X, Xd) in enumerate(zip(cases, Xs_host, Xs)):
+        single, sc = B.bsr_score_select(Xd, br, bc, keep, want_scores=True)
+        torch.cuda.synchronize()
+        got = masks[i].cpu().numpy()
+        assert np.array_equal(got, single.cpu().numpy()), f"item {i} differs from the single call"
+        assert np.array_equal(got, first[i]), f"item {i} differs between two batched calls"
+        o_scores = oracle.block_scores(X, br, bc)
+        nbr, nbc = oracle.grid(M, K, br, bc)
+        o_mask = oracle.select(o_scores, oracle.keep_count(nbr * nbc, keep))
+        assert np.array_equal(got, o_mask), f"item {i} differs from the oracle"
+        if want_scores[i] is not None:
+            assert want_scores[i].cpu().numpy().tobytes() == sc.cpu().numpy().tobytes()
+
+
+def test_batched_score_select_more_items_than_one_launch_holds():
+    rng = np.random.default_rng(77)
+    shapes = [(256 + 32 * (i % 5), 128 + 64 * (i % 3), 16, 16, 0.1 + 0.025 * i) for i in range(30)]
+    shapes += [(12544, 1536, 32, 32, 0.5)] * 26                      # 26 grid-wide selections: two launches of each pass
+    Xs_host = [synth.f32_to_bf16_bits(rng.standard_normal((M, K), dtype=np.float32)) for M, K, *_ in shapes[:30]]
+    big = synth.f32_to_bf16_bits(rng.standard_normal((12544, 1536), dtype=np.float32))
+    Xs = [to_dev(X) for X in Xs_host] + [to_dev(np.roll(big, i, axis=0)) for i in range(26)]
+    batch = B.SelectBatch(Xs, [(s[2], s[3]) for s in shapes], [s[4] for s in shapes])
+    masks = B.bsr_score_select_batched(batch)
+    torch.cuda.synchronize()
+    for i, (M, K, br, bc, keep) in enumerate(shapes):
+        single = B.bsr_score_select(Xs[i], br, bc, keep)
+        torch.cuda.synchronize()
+        assert np.array_equal(masks[i].cpu().numpy(), single.cpu().numpy()), f"item {i}"
+    for i in (0, 7, 29):
+        M, K, br, bc, keep = shapes[i]
+        o_scores = oracle.block_scores(Xs_host[i], br, bc)
+        assert np.array_equal(masks[i].cpu().numpy(), oracle.select(o_scores, oracle.keep_count(o_scores.size, keep)))
