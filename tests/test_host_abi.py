@@ -164,6 +164,30 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert af(dY=None) == B.BSR_ERR_NULL
     assert af(dalpha=C.c_void_p(0x1002)) == B.BSR_ERR_ALIGN
     assert af(ws_bytes=16) == B.BSR_ERR_WORKSPACE
+    # several tensors per call: the first offending item decides, nothing is launched
+    def items(**k):
+        arr = (B._SelectItem * 2)()
+        arr[0] = B._SelectItem(0x1000, 64, 64, 64, 16, 16, 0.5, None, 0x1000)
+        arr[1] = B._SelectItem(k.get("X", 0x1000), k.get("M", 128), 64, k.get("ldx", 64), k.get("br", 16), 16,
+                               k.get("keep", 0.25), None, k.get("mask", 0x1000))
+        return arr
+    bt = lambda arr, n=2, dtype=1, ws=fake, ws_bytes=1 << 20: lib.bsr_score_select_batched(arr, n, dtype, ws,
+                                                                                          ws_bytes, None)
+    assert bt(items(), n=-1) == B.BSR_ERR_SHAPE
+    assert bt(None) == B.BSR_ERR_NULL
+    assert bt(items(), n=0) == B.BSR_OK
+    assert bt(items(), dtype=4) == B.BSR_ERR_DTYPE
+    assert bt(items(br=0)) == B.BSR_ERR_SHAPE
+    assert bt(items(ldx=32)) == B.BSR_ERR_SHAPE
+    assert bt(items(keep=2.0)) == B.BSR_ERR_KEEP
+    assert bt(items(X=None)) == B.BSR_ERR_NULL
+    assert bt(items(mask=None)) == B.BSR_ERR_NULL
+    assert bt(items(), ws=None) == B.BSR_ERR_WORKSPACE
+    need = lib.bsr_score_select_batched_workspace_bytes(items(), 2, 1)
+    assert need == sum(-(-B.bsr_workspace_bytes(B.BSR_OP_SCORE_SELECT, M, 64, 0, 16, 16, 1) // 256) * 256
+                       for M in (64, 128))
+    assert bt(items(), ws_bytes=need - 1) == B.BSR_ERR_WORKSPACE
+    assert lib.bsr_score_select_batched_workspace_bytes(items(br=0), 2, 1) == 0
     assert B.lib().bsr_error_string(B.BSR_ERR_WORKSPACE) == b"BSR_ERR_WORKSPACE"
 
 
