@@ -83,3 +83,33 @@ def test_replays_match_eager(spec):
             assert w.tobytes() == g.tobytes(), f"replay {rep} differs from the eager result"
         for w, g in zip(other_want, other_got):
             assert w.tobytes() == g.tobytes(), f"eager work after replay {rep} differs"
+
+
+def test_batched_score_select_replays_match_eager():
+    """The several-tensors-per-call entry point under capture: its item array is read on the host
+    while the call is recorded, the launches replay with the same arguments."""
+    specs = [synth.TensorSpec("g_fc", 36864, 384, 64, 32, 32, "bf16", keep=0.5),       # grid-wide selection
+             synth.TensorSpec("g_small", 6272, 384, 64, 32, 32, "bf16", keep=0.25),    # one workgroup
+             synth.TensorSpec("g_patch", 2744, 196, 64, 14, 14, "bf16", keep=0.5)]     # LDS-staged scoring
+    Xs = [to_dev(synth.make_pair(sp, 21 + i)[0]) for i, sp in enumerate(specs)]
+    batch = B.SelectBatch(Xs, [(sp.br, sp.bc) for sp in specs], [sp.keep for sp in specs])
+    ws = torch.empty(batch.ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    B.bsr_score_select_batched(batch, ws=ws)
+    torch.cuda.synchronize()
+    want = [m.cpu().numpy().copy() for m in batch.keep_masks]
+    for sp, X, w in zip(specs, Xs, want):
+        single = B.bsr_score_select(X, sp.br, sp.bc, sp.keep)
+        torch.cuda.synchronize()
+        assert np.array_equal(single.cpu().numpy(), w)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.bsr_score_select_batched(batch, ws=ws)
+    for rep in range(3):
+        for m in batch.keep_masks:
+            m.fill_(9)
+        ws.fill_(0x5A)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for m, w in zip(batch.keep_masks, want):
+            assert np.array_equal(m.cpu().numpy(), w), f"replay {rep}"
