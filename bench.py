@@ -42,9 +42,10 @@ def parse():
     p.add_argument("--batch", type=int, default=128)
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--phase-reps", type=int, default=5)
-    p.add_argument("--graph", action="store_true",
-                   help="capture the step once into a HIP graph and replay it in the timed region "
-                        "(same work; measured equal to eager enqueue: the step is GPU-bound)")
+    p.add_argument("--launch", choices=("graph", "eager"), default="graph",
+                   help="graph: capture the step once into a HIP graph and replay it in the timed region (same "
+                        "kernels, same work, no host time per launch); eager: enqueue every step from the host")
+    p.add_argument("--graph", action="store_true", help="same as --launch graph")
     p.add_argument("--streams", type=int, default=6,
                    help="HIP streams (default priority) the independent tensors of a step are spread over")
     p.add_argument("--select", choices=("batched", "single"), default="batched",
@@ -198,10 +199,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # About 250 kernel launches behind 144 calls through ctypes per step: the host needs about
-    # 2 ms to enqueue them, less than the GPU needs to run them, so the step is GPU-bound.
-    # --graph replays a captured HIP graph of the step instead (the library only launches
-    # kernels on the stream it is given, so every call is capturable); same work, same time.
+    # About 190 kernel launches behind 109 calls through ctypes per step: the host needs about
+    # 1.9 ms to enqueue them, the GPU about 2.2 ms to run them, so an eagerly issued step is
+    # close to host-bound (2.26 ms).  By default the step is therefore captured once into a HIP
+    # graph and replayed (the library only launches kernels on the stream it is given, so every
+    # call is capturable); if the capture fails the steps are issued eagerly.
     step()                                       # eager once: library loaded, workspaces touched
     torch.cuda.synchronize()
     h0 = time.perf_counter()
@@ -209,11 +211,17 @@ def main():
     host_enqueue_ms = (time.perf_counter() - h0) * 1e3     # host side of one eager step (enqueue only)
     torch.cuda.synchronize()
     run_step = step
-    if args.graph:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        run_step = graph.replay
+    launch = "graph" if args.graph else args.launch
+    if launch == "graph":
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            run_step = graph.replay
+        except Exception as e:                                   # noqa: BLE001 - any capture failure
+            print(f"bench.py: graph capture failed ({e}); issuing the steps eagerly", file=sys.stderr)
+            torch.cuda.synchronize()
+            launch = "eager (graph capture failed)"
     for _ in range(args.warmup):
         run_step()
     torch.cuda.synchronize()
@@ -369,7 +377,7 @@ def main():
         "config": {"workload": f"ResMLP-S12 full activation set, batch {args.batch}, {args.layers} layers x "
                                "(xpatch 14x14, fc1 32x32, fc2 32x32), bf16, keep 0.5",
                    "tensors_per_step": len(tensors), "keep": keep, "streams": max(args.streams, 1),
-                   "launch": "hip graph replay" if args.graph else "eager",
+                   "launch": "hip graph replay" if launch == "graph" else launch,
                    "score_select": "one batched call per step" if batched else "one call per tensor",
                    "step": "score+select -> compress -> decompress -> dW for every tensor"},
         "phases": {
