@@ -19,7 +19,7 @@
  *     32-bit (Table II prices one index like one value); nblocks < 2^31.
  *   - Every pointer named below is a DEVICE pointer unless it says "host".  All
  *     buffers, the workspace included, are owned by the caller; the library
- *     never allocates, frees or synchronises.  Work is enqueued on `stream`
+ *     never allocates or frees device memory and never synchronises.  Work is enqueued on `stream`
  *     (a hipStream_t passed as void*; NULL = the default stream) and the call
  *     returns at once.  Buffers must stay alive until that work has finished.
  *   - Pointers must be aligned to their element type; wider alignment (16 B,
