@@ -366,6 +366,11 @@ def main():
             traffic = None
 
     achieved_tflops = flops_per_launch / (dw_launch_ms * 1e-3) / 1e12
+    # the same launches against the memory side: kept values + dY read once, dW written once
+    dw_alg_bytes = sum(t["n_keep"] * t["spec"].br * t["spec"].bc * t["X"].element_size()
+                       + t["spec"].M * t["spec"].N * t["dY"].element_size() + 4 * t["spec"].K * t["spec"].N
+                       for t in tensors) / len(tensors)
+    dw_alg_GBps = dw_alg_bytes / (dw_launch_ms * 1e-3) / 1e9
     result = {
         "metric": "compress GB/s + block-sparse dW TFLOP/s (nonzero blocks) at ResMLP-S12, 50% keep",
         "value": round(total_flops / (ms_per_step * 1e-3) / 1e12, 4),
@@ -390,7 +395,9 @@ def main():
         "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved_tflops / MFMA_BF16_PEAK_TFLOPS, 5),
                      "traffic": traffic, "kernel": "bsr_t_dense_matmul (dW)",
-                     "flops_per_launch": flops_per_launch, "ms_per_launch": round(dw_launch_ms, 5)},
+                     "flops_per_launch": flops_per_launch, "ms_per_launch": round(dw_launch_ms, 5),
+                     "hbm_side": {"algorithmic_bytes_per_launch": round(dw_alg_bytes), "achieved_GBps": round(dw_alg_GBps, 1),
+                                  "peak_GBps": HBM_PEAK_GBPS, "frac": round(dw_alg_GBps / HBM_PEAK_GBPS, 5)}},
         "roofline_compress": {"bound": "hbm", "achieved": round(comp_alg_bytes / (comp_ms * 1e-3) / 1e9, 2),
                               "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                               "frac": round(comp_alg_bytes / (comp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 5),
