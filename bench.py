@@ -46,11 +46,14 @@ def parse():
                    help="graph: capture the step once into a HIP graph and replay it in the timed region (same "
                         "kernels, same work, no host time per launch); eager: enqueue every step from the host")
     p.add_argument("--graph", action="store_true", help="same as --launch graph")
-    p.add_argument("--streams", type=int, default=6,
+    p.add_argument("--streams", type=int, default=4,
                    help="HIP streams (default priority) the independent tensors of a step are spread over")
     p.add_argument("--select", choices=("batched", "single"), default="batched",
                    help="batched: one bsr_score_select_batched call for all tensors of the step (a handful of "
                         "launches); single: one bsr_score_select call per tensor on its stream")
+    p.add_argument("--dw", choices=("batched", "single"), default="batched",
+                   help="batched: one bsr_t_dense_matmul_batched call for all tensors of the step after their BSR "
+                        "forms exist; single: one bsr_t_dense_matmul call per tensor on its stream")
     p.add_argument("--no-next-rows", action="store_true",
                    help="skip the measurements outside the timed step (per-sample ranking, row segments), "
                         "so that a profile of the run holds the step's kernels only")
@@ -135,7 +138,21 @@ def main():
 
     phases = [("score_select", score_select), ("compress", compress), ("decompress", decompress), ("dw", dw)]
     batched = args.select == "batched"
-    per_tensor = phases[1:] if batched else phases
+    dw_batched = args.dw == "batched"
+    per_tensor = [p for p in phases if not (batched and p[0] == "score_select") and not (dw_batched and p[0] == "dw")]
+    if dw_batched:
+        # every weight gradient of the step in one call, once all BSR forms exist: same results, the kernels of
+        # one block shape share launches
+        mm = B.MatmulBatch([(t["row_ptr"], t["col_idx"], t["values"], t["spec"].M, t["spec"].K, t["spec"].br,
+                             t["spec"].bc, t["dY"], t["dW"]) for t in tensors])
+        mm_ws = torch.empty(max(mm.ws_bytes, 256), dtype=torch.uint8, device=dev)
+
+    def dw_all():
+        if dw_batched:
+            B.bsr_t_dense_matmul_batched(mm, ws=mm_ws)
+        else:
+            for t in tensors:
+                dw(t)
     if batched:
         # scores and selection of all tensors of the step in one call: same masks, a handful of launches
         sel = B.SelectBatch([t["X"] for t in tensors], [(t["spec"].br, t["spec"].bc) for t in tensors],
@@ -174,6 +191,8 @@ def main():
             for t in tensors:
                 for _, f in per_tensor:
                     f(t)
+            if dw_batched:
+                dw_all()
             return
         fork = torch.cuda.Event()
         fork.record(main_stream)
@@ -190,6 +209,8 @@ def main():
             done = torch.cuda.Event()
             done.record(st)
             main_stream.wait_event(done)
+        if dw_batched:
+            dw_all()
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -247,6 +268,8 @@ def main():
     for name, f in phases:
         if name == "score_select":
             phase_ms[name] = timed(score_select_all, args.phase_reps)
+        elif name == "dw":
+            phase_ms[name] = timed(dw_all, args.phase_reps)
         else:
             phase_ms[name] = timed(lambda: [f(t) for t in tensors], args.phase_reps)
 
@@ -338,7 +361,8 @@ def main():
         s = t["spec"]
         return s.M * s.K * s.elem_bytes
 
-    dw_launch_ms = per_launch_ms(dw, tensors)
+    # (with the batched call the 36 products share a few launches: their mean is the call's time / 36)
+    dw_launch_ms = phase_ms["dw"] / len(tensors) if dw_batched else per_launch_ms(dw, tensors)
     total_flops = sum(flops(t) for t in tensors)
     flops_per_launch = total_flops / len(tensors)
     by_kind = {}
@@ -384,6 +408,7 @@ def main():
                    "tensors_per_step": len(tensors), "keep": keep, "streams": max(args.streams, 1),
                    "launch": "hip graph replay" if launch == "graph" else launch,
                    "score_select": "one batched call per step" if batched else "one call per tensor",
+                   "dw": "one batched call per step" if dw_batched else "one call per tensor",
                    "step": "score+select -> compress -> decompress -> dW for every tensor"},
         "phases": {
             "compress_GBps": round(comp_alg_bytes / (comp_ms * 1e-3) / 1e9, 2),

@@ -224,6 +224,36 @@ int bsr_score_select_batched(const bsr_select_item *items, int n, int dtype,
                              void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Several weight gradients per call (for instance those of all linear layers whose
+ * pruned inputs are at hand): every item is exactly one bsr_t_dense_matmul, bit
+ * for bit, but items of the same block shape share kernel launches, so that the
+ * table build and the write-out of one product overlap the main loop of another.
+ * `items` is a host array, read before the call returns; all items share `dtype`;
+ * outputs of different items must not overlap.  Workspace:
+ * bsr_t_dense_matmul_batched_workspace_bytes(items, n, dtype) (0 for invalid
+ * items).  Errors as for bsr_t_dense_matmul, for the first offending item; nothing
+ * is launched if any item is invalid.
+ */
+typedef struct bsr_matmul_item {
+  const int32_t *row_ptr;  /* device */
+  const int32_t *col_idx;  /* device */
+  const void *values;      /* device */
+  int64_t M, K;
+  int32_t br, bc;
+  const void *dY;          /* device, [M x N], leading dimension lddy */
+  int64_t N, lddy;
+  float *dW;               /* device, [K x N], leading dimension lddw */
+  int64_t lddw;
+  int32_t accumulate;
+} bsr_matmul_item;
+
+size_t bsr_t_dense_matmul_batched_workspace_bytes(const bsr_matmul_item *items,
+                                                  int n, int dtype);
+
+int bsr_t_dense_matmul_batched(const bsr_matmul_item *items, int n, int dtype,
+                               void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Sec. VI (outlook) names a block-sparse version of ResMLP's affine scaling
  * layer, y[m,k] = alpha[k] * x[m,k] + beta[k].  Of its backward pass only the
  * scale gradient needs the saved input; from the pruned input in BSR form:

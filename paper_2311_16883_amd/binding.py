@@ -31,6 +31,7 @@ EXPORTS = (
     "bsr_storage_bytes", "bsr_workspace_bytes", "bsr_score_select", "bsr_compress",
     "bsr_decompress", "bsr_t_dense_matmul", "bsr_grouped_keep_count", "bsr_score_select_grouped",
     "bsr_affine_scale_grad", "bsr_score_select_batched", "bsr_score_select_batched_workspace_bytes",
+    "bsr_t_dense_matmul_batched", "bsr_t_dense_matmul_batched_workspace_bytes",
 )
 
 
@@ -84,6 +85,10 @@ def lib() -> C.CDLL:
     l.bsr_score_select_batched_workspace_bytes.argtypes = [vp, i32, i32]
     l.bsr_score_select_batched.restype = i32
     l.bsr_score_select_batched.argtypes = [vp, i32, i32, vp, sz, vp]
+    l.bsr_t_dense_matmul_batched_workspace_bytes.restype = sz
+    l.bsr_t_dense_matmul_batched_workspace_bytes.argtypes = [vp, i32, i32]
+    l.bsr_t_dense_matmul_batched.restype = i32
+    l.bsr_t_dense_matmul_batched.argtypes = [vp, i32, i32, vp, sz, vp]
     l.bsr_affine_scale_grad.restype = i32
     l.bsr_affine_scale_grad.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, vp, i64, vp, i32, vp, sz, vp]
     _lib = l
@@ -347,3 +352,52 @@ def bsr_score_select_batched(batch: SelectBatch, *, ws: Optional[torch.Tensor] =
                                         ws.numel() if ws is not None else 0, _stream(stream))
     _check(rc, "bsr_score_select_batched")
     return batch.keep_masks
+
+
+class _MatmulItem(C.Structure):
+    """Mirror of bsr_matmul_item."""
+    _fields_ = [("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("values", C.c_void_p),
+                ("M", C.c_int64), ("K", C.c_int64), ("br", C.c_int32), ("bc", C.c_int32),
+                ("dY", C.c_void_p), ("N", C.c_int64), ("lddy", C.c_int64),
+                ("dW", C.c_void_p), ("lddw", C.c_int64), ("accumulate", C.c_int32)]
+
+
+class MatmulBatch:
+    """The marshalled item array of one bsr_t_dense_matmul_batched call (see SelectBatch).  Every entry of
+    `problems` is (row_ptr, col_idx, values, M, K, br, bc, dY) or that plus a dW tensor to write into."""
+
+    def __init__(self, problems: Sequence[tuple], accumulate: bool = False):
+        n = len(problems)
+        if n == 0:
+            raise ValueError("empty batch")
+        self.dtype = dtype_code(problems[0][7].dtype)
+        self.device = problems[0][7].device
+        self.items = (_MatmulItem * n)()
+        self.keep, self.dWs = [], []
+        for i, pr in enumerate(problems):
+            row_ptr, col_idx, values, M, K, br, bc, dY = pr[:8]
+            Md, N, lddy = _dense2d(dY, "dY")
+            if Md != M or dtype_code(dY.dtype) != self.dtype or values.dtype != dY.dtype:
+                raise ValueError("dY must have M rows and the batch one dtype")
+            dW = pr[8] if len(pr) > 8 and pr[8] is not None else None
+            if dW is None:
+                if accumulate:
+                    raise ValueError("accumulate needs existing dW tensors")
+                dW = torch.empty((K, N), dtype=torch.float32, device=dY.device)
+            _, _, lddw = _dense2d(dW, "dW")
+            self.items[i] = _MatmulItem(_ptr(row_ptr), _ptr(col_idx), _ptr(values), M, K, br, bc, _ptr(dY), N, lddy,
+                                        _ptr(dW), lddw, 1 if accumulate else 0)
+            self.keep.append(pr)
+            self.dWs.append(dW)
+        self.n = n
+        self.ws_bytes = int(lib().bsr_t_dense_matmul_batched_workspace_bytes(self.items, n, self.dtype))
+
+
+def bsr_t_dense_matmul_batched(batch: MatmulBatch, *, ws: Optional[torch.Tensor] = None, stream=None):
+    """-> list of dW tensors, each what bsr_t_dense_matmul gives for its item."""
+    if ws is None:
+        ws = _workspace(batch.ws_bytes, batch.device, None)
+    rc = lib().bsr_t_dense_matmul_batched(batch.items, batch.n, batch.dtype, _ptr(ws),
+                                          ws.numel() if ws is not None else 0, _stream(stream))
+    _check(rc, "bsr_t_dense_matmul_batched")
+    return batch.dWs

@@ -300,4 +300,55 @@ int bsr_score_select_batched(const bsr_select_item *items, int n, int dtype, voi
   return launch_select_batched(select_jobs.data(), (int)select_jobs.size(), s);
 }
 
+size_t bsr_t_dense_matmul_batched_workspace_bytes(const bsr_matmul_item *items, int n, int dtype) {
+  if (items == nullptr || n <= 0) return 0;
+  size_t total = 0;
+  for (int i = 0; i < n; ++i) {
+    const bsr_matmul_item &it = items[i];
+    Geometry g;
+    if (check_shape(dtype, it.M, it.K, it.K, it.br, it.bc, &g) != BSR_OK || it.N < 0) return 0;
+    total += align_up(bsr_workspace_bytes(BSR_OP_T_DENSE_MATMUL, it.M, it.K, it.N, it.br, it.bc, dtype), 256);
+  }
+  return total;
+}
+
+int bsr_t_dense_matmul_batched(const bsr_matmul_item *items, int n, int dtype, void *ws, size_t ws_bytes,
+                               void *stream) {
+  if (n < 0) return BSR_ERR_SHAPE;
+  if (n == 0) return BSR_OK;
+  if (items == nullptr) return BSR_ERR_NULL;
+  if (misaligned(ws, 16)) return BSR_ERR_ALIGN;
+  std::vector<DwJob> batch, single;
+  batch.reserve(n);
+  size_t off = 0;
+  for (int i = 0; i < n; ++i) {
+    const bsr_matmul_item &it = items[i];
+    Geometry g;
+    const int rc = check_shape(dtype, it.M, it.K, it.K, it.br, it.bc, &g);
+    if (rc != BSR_OK) return rc;
+    if (it.N < 0 || it.lddy < it.N || it.lddw < it.N || it.N > (int64_t(1) << 40)) return BSR_ERR_SHAPE;
+    if (it.K == 0 || it.N == 0) continue;
+    if (it.dW == nullptr || it.row_ptr == nullptr) return BSR_ERR_NULL;
+    if (it.M > 0 && it.dY == nullptr) return BSR_ERR_NULL;
+    if (misaligned(it.values, elem_bytes(dtype)) || misaligned(it.dY, elem_bytes(dtype)) || misaligned(it.dW, 4) ||
+        misaligned(it.row_ptr, 4) || misaligned(it.col_idx, 4))
+      return BSR_ERR_ALIGN;
+    const size_t need = align_up(bsr_workspace_bytes(BSR_OP_T_DENSE_MATMUL, it.M, it.K, it.N, it.br, it.bc, dtype), 256);
+    if (need > 0 && (ws == nullptr || off + need > ws_bytes)) return BSR_ERR_WORKSPACE;
+    const DwJob job{it.row_ptr, it.col_idx, it.values, it.M, it.K, it.br, it.bc, it.dY, it.N, it.lddy, it.dW,
+                    it.lddw, it.accumulate, need > 0 ? static_cast<char *>(ws) + off : nullptr, need};
+    off += need;
+    if (dw_mfma_supported(dtype, it.br, it.bc, it.values, it.M, it.K, it.N, it.lddy)) batch.push_back(job);
+    else single.push_back(job);
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int rc = launch_dw_mfma_batched(dtype, batch.data(), (int)batch.size(), s);
+  for (size_t i = 0; rc == BSR_OK && i < single.size(); ++i) {
+    const DwJob &j = single[i];
+    rc = bsr_t_dense_matmul(j.row_ptr, j.col_idx, j.values, dtype, j.M, j.K, j.br, j.bc, j.dY, j.N, j.lddy, j.dW,
+                            j.lddw, j.accumulate, j.ws, j.ws_bytes, stream);
+  }
+  return rc;
+}
+
 }  // extern "C"

@@ -140,6 +140,33 @@ struct SpanGeom {
 bool span_geometry(int dtype, int64_t M, int64_t K, int64_t ld, int br, int bc, const void *p0,
                    const void *p1, SpanGeom *g);
 
+// Several reductions / several dW products per launch.
+constexpr int kReduceBatchMax = 16;
+struct ReduceJob {
+  const float *partial;
+  float *dW;
+  int64_t K, N, lddw;
+  int splits, accumulate;
+};
+int launch_splitk_reduce_batched(const ReduceJob *jobs, int n, hipStream_t s);
+
+struct DwJob {
+  const int32_t *row_ptr, *col_idx;
+  const void *values;
+  int64_t M, K;
+  int br, bc;
+  const void *dY;
+  int64_t N, lddy;
+  float *dW;
+  int64_t lddw;
+  int accumulate;
+  void *ws;
+  size_t ws_bytes;
+};
+// dw_mfma.hip: the jobs (all of block shapes and sizes dw_mfma_supported accepts, none with
+// K == 0 or N == 0) with as few launches as their kernel instances allow.
+int launch_dw_mfma_batched(int dtype, const DwJob *jobs, int n, hipStream_t s);
+
 // ---- device helpers ----
 
 // w / d for w * d < 2^32, with magic = ceil(2^32 / d) (d == 1 has no 32-bit magic)

@@ -142,6 +142,44 @@ __global__ __launch_bounds__(256) void splitk_reduce4_kernel(const float4 *__res
   }
 }
 
+// The same sums for several tensors in one launch (item = tensor, found from the prefix of
+// workgroup counts); per element the order of the additions is that of the kernels above.
+struct ReduceBatch {
+  ReduceJob it[kReduceBatchMax];
+  uint32_t wg_begin[kReduceBatchMax + 1];
+};
+
+__global__ __launch_bounds__(256) void splitk_reduce_batched_kernel(ReduceBatch b, int n) {
+  int i = 0;
+  while (i + 1 < n && blockIdx.x >= b.wg_begin[i + 1]) ++i;
+  const ReduceJob &it = b.it[i];
+  const int64_t wg = blockIdx.x - b.wg_begin[i], wgs = b.wg_begin[i + 1] - b.wg_begin[i];
+  const bool vec = it.N % 4 == 0 && it.lddw % 4 == 0 && (uintptr_t)it.dW % 16 == 0 && (uintptr_t)it.partial % 16 == 0;
+  if (vec) {
+    const int64_t N4 = it.N / 4, total4 = it.K * N4;
+    const float4 *partial = reinterpret_cast<const float4 *>(it.partial);
+    for (int64_t e = wg * 256 + threadIdx.x; e < total4; e += wgs * 256) {
+      const int64_t k = e / N4, n4 = e % N4;
+      float4 *dst = reinterpret_cast<float4 *>(it.dW + k * it.lddw) + n4;
+      float4 s = it.accumulate ? *dst : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+      for (int sp = 0; sp < it.splits; ++sp) {
+        const float4 v = partial[(int64_t)sp * total4 + e];
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+      }
+      *dst = s;
+    }
+  } else {
+    const int64_t total = it.K * it.N;
+    for (int64_t e = wg * 256 + threadIdx.x; e < total; e += wgs * 256) {
+      const int64_t k = e / it.N, c = e % it.N;
+      float s = it.accumulate ? it.dW[k * it.lddw + c] : 0.f;
+      for (int sp = 0; sp < it.splits; ++sp) s += it.partial[(int64_t)sp * total + e];
+      it.dW[k * it.lddw + c] = s;
+    }
+  }
+}
+
 int generic_splits(int64_t M, int64_t K, int64_t N, int br) {
   const int64_t nbr = ceil_div(M, br);
   const int64_t tiles = ceil_div(K, TK) * ceil_div(N, TN);
@@ -170,6 +208,25 @@ int launch_splitk_reduce(const float *partial, int splits, int64_t K, int64_t N,
   hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)(blocks < 8192 ? blocks : 8192)), dim3(256),
                      0, s, partial, splits, K, N, dW, lddw, accumulate);
   return check_launch();
+}
+
+int launch_splitk_reduce_batched(const ReduceJob *jobs, int n, hipStream_t s) {
+  for (int i0 = 0; i0 < n; i0 += kReduceBatchMax) {
+    const int m = n - i0 < kReduceBatchMax ? n - i0 : kReduceBatchMax;
+    ReduceBatch b;
+    uint32_t wgs = 0;
+    for (int i = 0; i < m; ++i) {
+      b.it[i] = jobs[i0 + i];
+      b.wg_begin[i] = wgs;
+      const int64_t blocks = ceil_div(ceil_div(jobs[i0 + i].K * jobs[i0 + i].N, 4), 256);
+      wgs += (uint32_t)(blocks < 1 ? 1 : (blocks < 2048 ? blocks : 2048));
+    }
+    b.wg_begin[m] = wgs;
+    hipLaunchKernelGGL(splitk_reduce_batched_kernel, dim3(wgs), dim3(256), 0, s, b, m);
+    const int rc = check_launch();
+    if (rc != BSR_OK) return rc;
+  }
+  return BSR_OK;
 }
 
 size_t dw_generic_ws_bytes(int64_t M, int64_t K, int64_t N, int br, int bc) {

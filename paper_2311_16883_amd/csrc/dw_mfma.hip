@@ -134,13 +134,29 @@ struct Geo {
 // WN = multiplier waves along N (2: 64 x 64 per wave, 4: 64 x 32 per wave); the
 // workgroup has 2 x WN multiplier waves and as many loader waves.
 // T = uint16_t (bfloat16 bits) or float.
+// What one tensor's launch needs (kernel arguments; an array of these for a batch).
+struct DwParams {
+  const int32_t *row_ptr, *col_idx;
+  const void *values, *dY;
+  float *out;
+  int64_t M, K, N, lddy, ldo, split_stride, nbr, nbc, stages_per_split;
+  int accumulate, tiles_k, tiles_n, splits;
+  uint32_t values_bytes;
+  uint32_t wg_begin;       // first workgroup of this tensor in a batched launch (a multiple of 8)
+};
+
+// wg = number of the workgroup among those of this tensor.
 template <typename T, int BR, int BC, int MS, int VB, int D, int WN>
-__global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(
-    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-    const T *__restrict__ values, const T *__restrict__ dY, float *__restrict__ out,
-    int64_t M, int64_t K, int64_t N, int64_t lddy, int64_t ldo, int64_t split_stride, int64_t nbr,
-    int64_t nbc, int64_t stages_per_split, int accumulate, int tiles_k, int tiles_n, int splits,
-    int xcd_map, uint32_t values_bytes) {
+__device__ __forceinline__ void dw_mfma_body(const DwParams &prm, const uint32_t wg, const int xcd_map) {
+  const int32_t *__restrict__ row_ptr = prm.row_ptr;
+  const int32_t *__restrict__ col_idx = prm.col_idx;
+  const T *__restrict__ values = static_cast<const T *>(prm.values);
+  const T *__restrict__ dY = static_cast<const T *>(prm.dY);
+  float *__restrict__ out = prm.out;
+  const int64_t M = prm.M, K = prm.K, N = prm.N, lddy = prm.lddy, ldo = prm.ldo, split_stride = prm.split_stride;
+  const int64_t nbr = prm.nbr, nbc = prm.nbc, stages_per_split = prm.stages_per_split;
+  const int accumulate = prm.accumulate, tiles_k = prm.tiles_k, tiles_n = prm.tiles_n, splits = prm.splits;
+  const uint32_t values_bytes = prm.values_bytes;
   constexpr int E = (int)sizeof(T);
   typedef Geo<E, BR, BC, MS, VB, WN> G;
   constexpr int kRole = G::THREADS;              // threads per role
@@ -160,10 +176,10 @@ __global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(
   int item;
   if (xcd_map) {
     const int per_xcd = (items + 7) / 8;
-    item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= per_xcd) return;
+    item = (wg & 7) * per_xcd + (wg >> 3);
+    if ((int)(wg >> 3) >= per_xcd) return;
   } else {
-    item = blockIdx.x;
+    item = wg;
   }
   if (item >= items) return;
   const int split = item / tiles, tile = item % tiles;
@@ -545,6 +561,27 @@ __global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(
   else write_tile(std::false_type{});
 }
 
+template <typename T, int BR, int BC, int MS, int VB, int D, int WN>
+__global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(DwParams prm, int xcd_map) {
+  dw_mfma_body<T, BR, BC, MS, VB, D, WN>(prm, blockIdx.x, xcd_map);
+}
+
+// Several tensors per launch: tensor i owns the workgroups [wg_begin_i, wg_begin_{i+1}); its
+// own 8-way dealing of work items to XCDs is kept because every wg_begin is a multiple of 8.
+// With many more workgroups than compute units the table build and the write-out of one
+// workgroup overlap the main loop of its neighbour on the same compute unit.
+constexpr int kDwBatchMax = 16;
+struct DwBatch {
+  DwParams it[kDwBatchMax];
+};
+
+template <typename T, int BR, int BC, int MS, int VB, int D, int WN>
+__global__ __launch_bounds__(256 * WN) void dw_mfma_batched_kernel(DwBatch b, int n) {
+  int i = 0;
+  while (i + 1 < n && blockIdx.x >= b.it[i + 1].wg_begin) ++i;
+  dw_mfma_body<T, BR, BC, MS, VB, D, WN>(b.it[i], blockIdx.x - b.it[i].wg_begin, 1);
+}
+
 struct Plan {
   int splits;
   int64_t stages_per_split;
@@ -588,34 +625,52 @@ Plan make_plan(int64_t M, int64_t K, int64_t N) {
   return p;
 }
 
+// elements per dY vector: 16 bytes at most
+template <int E>
+int dy_vector(const void *dY, int64_t N, int64_t lddy) {
+  int vb = 16 / E;
+  while (vb > 1 && (N % vb != 0 || lddy % vb != 0 || (uintptr_t)dY % (E * vb) != 0)) vb >>= 1;
+  return vb;
+}
+
+// Kernel parameters of one product; *wgs = workgroups of its launch, *splits as planned.
+template <int E, int BR, int BC, int MS>
+int fill_params(const DwJob &j, DwParams *prm, uint32_t *wgs) {
+  const Plan p = make_plan<E, BR, MS>(j.M, j.K, j.N);
+  const size_t need = p.splits > 1 ? (size_t)p.splits * j.K * j.N * sizeof(float) : 0;
+  if (need > 0 && (j.ws == nullptr || j.ws_bytes < need)) return BSR_ERR_WORKSPACE;
+  const int64_t nbr = ceil_div(j.M, BR), nbc = ceil_div(j.K, BC);
+  prm->row_ptr = j.row_ptr; prm->col_idx = j.col_idx; prm->values = j.values; prm->dY = j.dY;
+  prm->out = p.splits > 1 ? static_cast<float *>(j.ws) : j.dW;
+  prm->M = j.M; prm->K = j.K; prm->N = j.N; prm->lddy = j.lddy;
+  prm->ldo = p.splits > 1 ? j.N : j.lddw;
+  prm->split_stride = p.splits > 1 ? j.K * j.N : 0;
+  prm->nbr = nbr; prm->nbc = nbc; prm->stages_per_split = p.stages_per_split;
+  prm->accumulate = p.splits > 1 ? 0 : j.accumulate;
+  prm->tiles_k = (int)ceil_div(j.K, 128); prm->tiles_n = (int)ceil_div(j.N, 128); prm->splits = p.splits;
+  // 32-bit buffer offsets: both operands must stay below 4 GiB (checked by dw_mfma_supported)
+  prm->values_bytes = (uint32_t)(nbr * nbc * BR * BC * E);
+  prm->wg_begin = 0;
+  const int64_t n_items = (int64_t)p.splits * prm->tiles_k * prm->tiles_n;
+  *wgs = (uint32_t)(8 * ceil_div(n_items, 8));        // XCD-aware work item order: whole groups of 8
+  return BSR_OK;
+}
+
 template <typename T, int BR, int BC, int MS, int D, int WN>
 int run(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int64_t M, int64_t K,
         const void *dY, int64_t N, int64_t lddy, float *dW, int64_t lddw, int accumulate, void *ws,
         size_t ws_bytes, hipStream_t s) {
   constexpr int E = (int)sizeof(T);
-  const Plan p = make_plan<E, BR, MS>(M, K, N);
-  const size_t need = p.splits > 1 ? (size_t)p.splits * K * N * sizeof(float) : 0;
-  if (need > 0 && (ws == nullptr || ws_bytes < need)) return BSR_ERR_WORKSPACE;
-  const int64_t nbr = ceil_div(M, BR), nbc = ceil_div(K, BC);
-  float *out = p.splits > 1 ? static_cast<float *>(ws) : dW;
-  const int64_t ldo = p.splits > 1 ? N : lddw;
-  const int64_t stride = p.splits > 1 ? K * N : 0;
-  const int acc_direct = p.splits > 1 ? 0 : accumulate;
-  const int tiles_k = (int)ceil_div(K, 128), tiles_n = (int)ceil_div(N, 128);
+  const DwJob job{row_ptr, col_idx, values, M, K, BR, BC, dY, N, lddy, dW, lddw, accumulate, ws, ws_bytes};
+  DwParams prm;
+  uint32_t wgs;
+  int rc = fill_params<E, BR, BC, MS>(job, &prm, &wgs);
+  if (rc != BSR_OK) return rc;
+  const dim3 grid(wgs);
   const int xcd_map = 1;      // XCD-aware work item order (0 = plain order, kept for measurements)
-  const int64_t n_items = (int64_t)p.splits * tiles_k * tiles_n;
-  dim3 grid((unsigned)(xcd_map ? 8 * ceil_div(n_items, 8) : n_items));
-  const T *v = static_cast<const T *>(values);
-  const T *y = static_cast<const T *>(dY);
-  // 32-bit buffer offsets: both operands must stay below 4 GiB (checked by dw_mfma_supported)
-  const uint32_t values_bytes = (uint32_t)(nbr * nbc * BR * BC * E);
-  int vb = 16 / E;                                  // elements per dY vector: 16 bytes at most
-  while (vb > 1 && (N % vb != 0 || lddy % vb != 0 || (uintptr_t)dY % (E * vb) != 0)) vb >>= 1;
+  int vb = dy_vector<E>(dY, N, lddy);
 #define BSR_DW_LAUNCH(VB)                                                                         \
-  hipLaunchKernelGGL((dw_mfma_kernel<T, BR, BC, MS, VB, D, WN>), grid, dim3(256 * WN), 0, s,       \
-                     row_ptr, col_idx, v, y, out, M, K, N, lddy, ldo, stride, nbr, nbc,            \
-                     p.stages_per_split, acc_direct, tiles_k, tiles_n, p.splits, xcd_map,           \
-                     values_bytes)
+  hipLaunchKernelGGL((dw_mfma_kernel<T, BR, BC, MS, VB, D, WN>), grid, dim3(256 * WN), 0, s, prm, xcd_map)
   if constexpr (E == 2) {
     if (vb == 8) { BSR_DW_LAUNCH(8); vb = 0; }
   }
@@ -624,9 +679,53 @@ int run(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int6
   else if (vb == 2) BSR_DW_LAUNCH(2);
   else BSR_DW_LAUNCH(1);
 #undef BSR_DW_LAUNCH
-  int rc = check_launch();
-  if (rc != BSR_OK || p.splits == 1) return rc;
-  return launch_splitk_reduce(out, p.splits, K, N, dW, lddw, accumulate, s);
+  rc = check_launch();
+  if (rc != BSR_OK || prm.splits == 1) return rc;
+  return launch_splitk_reduce(prm.out, prm.splits, K, N, dW, lddw, accumulate, s);
+}
+
+// The jobs of one kernel instance (block shape and dY vector width `want_vb`), kDwBatchMax per launch.
+template <typename T, int BR, int BC, int MS, int D, int WN>
+int run_batched(const DwJob *jobs, int n, int want_vb, hipStream_t s) {
+  constexpr int E = (int)sizeof(T);
+  DwBatch b;
+  ReduceJob red[kDwBatchMax];
+  int m = 0, nred = 0;
+  uint32_t total = 0;
+  auto flush = [&]() -> int {
+    if (m == 0) return BSR_OK;
+    const dim3 grid(total), block(256 * WN);
+    switch (want_vb) {
+      case 8:
+        if constexpr (E == 2) hipLaunchKernelGGL((dw_mfma_batched_kernel<T, BR, BC, MS, 8, D, WN>), grid, block, 0, s, b, m);
+        break;
+      case 4: hipLaunchKernelGGL((dw_mfma_batched_kernel<T, BR, BC, MS, 4, D, WN>), grid, block, 0, s, b, m); break;
+      case 2: hipLaunchKernelGGL((dw_mfma_batched_kernel<T, BR, BC, MS, 2, D, WN>), grid, block, 0, s, b, m); break;
+      default: hipLaunchKernelGGL((dw_mfma_batched_kernel<T, BR, BC, MS, 1, D, WN>), grid, block, 0, s, b, m); break;
+    }
+    int rc = check_launch();
+    if (rc == BSR_OK && nred > 0) rc = launch_splitk_reduce_batched(red, nred, s);
+    m = 0;
+    nred = 0;
+    total = 0;
+    return rc;
+  };
+  for (int i = 0; i < n; ++i) {
+    const DwJob &j = jobs[i];
+    if (j.br != BR || j.bc != BC || dy_vector<E>(j.dY, j.N, j.lddy) != want_vb) continue;
+    uint32_t wgs;
+    int rc = fill_params<E, BR, BC, MS>(j, &b.it[m], &wgs);
+    if (rc != BSR_OK) return rc;
+    b.it[m].wg_begin = total;
+    total += wgs;
+    if (b.it[m].splits > 1)
+      red[nred++] = ReduceJob{b.it[m].out, j.dW, j.K, j.N, j.lddw, b.it[m].splits, j.accumulate};
+    if (++m == kDwBatchMax) {
+      rc = flush();
+      if (rc != BSR_OK) return rc;
+    }
+  }
+  return flush();
 }
 
 template <int E, int BR, int MS>
@@ -683,6 +782,27 @@ int launch_dw_mfma(int dtype, const int32_t *row_ptr, const int32_t *col_idx, co
   if (br == 14 && bc == 14) return run<uint16_t, 14, 14, 32, 2, 4>(BSR_ARGS);
 #undef BSR_ARGS
   return BSR_ERR_SHAPE;
+}
+
+int launch_dw_mfma_batched(int dtype, const DwJob *jobs, int n, hipStream_t s) {
+  static const int kVbs[4] = {8, 4, 2, 1};
+  for (int vi = 0; vi < 4; ++vi) {
+    const int vb = kVbs[vi];
+    int rc;
+    if (dtype == BSR_F32) {
+      if (vb == 8) continue;
+      if ((rc = run_batched<float, 32, 32, 64, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
+      if ((rc = run_batched<float, 64, 64, 64, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
+      if ((rc = run_batched<float, 16, 16, 32, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
+      if ((rc = run_batched<float, 14, 14, 32, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
+    } else {
+      if ((rc = run_batched<uint16_t, 32, 32, 64, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
+      if ((rc = run_batched<uint16_t, 64, 64, 64, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
+      if ((rc = run_batched<uint16_t, 16, 16, 32, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
+      if ((rc = run_batched<uint16_t, 14, 14, 32, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
+    }
+  }
+  return BSR_OK;
 }
 
 }  // namespace bsr

@@ -509,3 +509,63 @@ def test_batched_score_select_more_items_than_one_launch_holds():
         M, K, br, bc, keep = shapes[i]
         o_scores = oracle.block_scores(Xs_host[i], br, bc)
         assert np.array_equal(masks[i].cpu().numpy(), oracle.select(o_scores, oracle.keep_count(o_scores.size, keep)))
+
+
+DW_BATCH = [
+    # M, K, N, br, bc, keep
+    (2048, 384, 1536, 32, 32, 0.5),
+    (2048, 1536, 384, 32, 32, 0.5),
+    (4100, 384, 260, 32, 32, 0.25),       # several splits, ragged rows, N not a multiple of 8
+    (777, 196, 196, 14, 14, 0.5),
+    (1024, 256, 64, 64, 64, 0.75),
+    (640, 384, 100, 16, 16, 0.1),
+    (2000, 384, 200, 1, 32, 0.5),         # re-tiled inside the call, on its own
+    (300, 70, 33, 7, 5, 0.6),             # small: the general kernel, on its own
+    (512, 128, 96, 32, 32, 0.0),          # nothing kept
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_batched_dw_equals_single_calls(dtype):
+    problems, refs, singles = [], [], []
+    for i, (M, K, N, br, bc, keep) in enumerate(DW_BATCH):
+        X, dY = rand_pair(M, K, N, dtype, seed=300 + i)
+        o_scores, o_mask, o_rp, o_ci, o_val = oracle.prune(X, br, bc, keep)
+        rp, ci = torch.from_numpy(o_rp).cuda(), torch.from_numpy(o_ci).cuda()
+        val = to_dev(o_val.reshape(-1, bc)).reshape(o_val.shape)
+        dYd = to_dev(dY)
+        problems.append((rp, ci, val, M, K, br, bc, dYd))
+        singles.append(B.bsr_t_dense_matmul(rp, ci, val, M, K, br, bc, dYd))
+        refs.append(oracle.dw(oracle.mask_dense(X, br, bc, o_mask), dY) if M * K * N <= 2.5e8 else None)
+    batch = B.MatmulBatch(problems)
+    outs = B.bsr_t_dense_matmul_batched(batch)
+    torch.cuda.synchronize()
+    for i, (got, single, ref) in enumerate(zip(outs, singles, refs)):
+        assert got.cpu().numpy().tobytes() == single.cpu().numpy().tobytes(), f"item {i} differs from the single call"
+        if ref is not None:
+            assert dw_error(got.cpu().numpy(), ref) <= DW_TOL[dtype], f"item {i}"
+    # accumulate on top of existing gradients, twice the same batch
+    acc = [(p + (torch.full_like(o, 0.5),)) for p, o in zip(problems, outs)]
+    batch2 = B.MatmulBatch(acc, accumulate=True)
+    outs2 = B.bsr_t_dense_matmul_batched(batch2)
+    torch.cuda.synchronize()
+    for i, (a, o) in enumerate(zip(outs2, outs)):
+        want = o.cpu().numpy().astype(np.float64) + 0.5
+        assert np.max(np.abs(a.cpu().numpy() - want)) <= 1e-6 * max(1.0, float(np.max(np.abs(want)))), f"item {i}"
+
+
+def test_batched_dw_more_items_than_one_launch_holds():
+    rng = np.random.default_rng(5)
+    M, K, N = 1568, 384, 192
+    X = synth.f32_to_bf16_bits(rng.standard_normal((M, K), dtype=np.float32))
+    o_scores, o_mask, o_rp, o_ci, o_val = oracle.prune(X, 32, 32, 0.5)
+    rp, ci = torch.from_numpy(o_rp).cuda(), torch.from_numpy(o_ci).cuda()
+    val = to_dev(o_val.reshape(-1, 32)).reshape(o_val.shape)
+    dYs = [to_dev(synth.f32_to_bf16_bits(rng.standard_normal((M, N), dtype=np.float32))) for _ in range(37)]
+    batch = B.MatmulBatch([(rp, ci, val, M, K, 32, 32, dY) for dY in dYs])
+    outs = B.bsr_t_dense_matmul_batched(batch)
+    torch.cuda.synchronize()
+    for i, dY in enumerate(dYs):
+        single = B.bsr_t_dense_matmul(rp, ci, val, M, K, 32, 32, dY)
+        torch.cuda.synchronize()
+        assert outs[i].cpu().numpy().tobytes() == single.cpu().numpy().tobytes(), f"item {i}"
