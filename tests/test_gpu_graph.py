@@ -113,3 +113,37 @@ def test_batched_score_select_replays_match_eager():
         torch.cuda.synchronize()
         for m, w in zip(batch.keep_masks, want):
             assert np.array_equal(m.cpu().numpy(), w), f"replay {rep}"
+
+
+def test_batched_dw_replays_match_eager():
+    specs = [synth.TensorSpec("g_fc1", 6272, 384, 1536, 32, 32, "bf16", keep=0.5),
+             synth.TensorSpec("g_fc2", 6272, 1536, 384, 32, 32, "bf16", keep=0.5),
+             synth.TensorSpec("g_patch", 5488, 196, 196, 14, 14, "bf16", keep=0.5)]
+    problems = []
+    for i, sp in enumerate(specs):
+        X, dY = synth.make_pair(sp, 31 + i)
+        Xd = to_dev(X)
+        mask = B.bsr_score_select(Xd, sp.br, sp.bc, sp.keep)
+        rp, ci, val = B.bsr_compress(Xd, sp.br, sp.bc, mask, B.bsr_keep_count(sp.nblocks, sp.keep))
+        problems.append((rp, ci, val, sp.M, sp.K, sp.br, sp.bc, to_dev(dY)))
+    batch = B.MatmulBatch(problems)
+    ws = torch.empty(batch.ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    B.bsr_t_dense_matmul_batched(batch, ws=ws)
+    torch.cuda.synchronize()
+    want = [o.cpu().numpy().copy() for o in batch.dWs]
+    for pr, w in zip(problems, want):
+        single = B.bsr_t_dense_matmul(*pr)
+        torch.cuda.synchronize()
+        assert single.cpu().numpy().tobytes() == w.tobytes()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.bsr_t_dense_matmul_batched(batch, ws=ws)
+    for rep in range(3):
+        for o in batch.dWs:
+            o.fill_(float("nan"))
+        ws.fill_(0x5A)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, w in zip(batch.dWs, want):
+            assert o.cpu().numpy().tobytes() == w.tobytes(), f"replay {rep}"

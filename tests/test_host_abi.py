@@ -188,6 +188,30 @@ def test_invalid_arguments_are_rejected_on_the_host():
                        for M in (64, 128))
     assert bt(items(), ws_bytes=need - 1) == B.BSR_ERR_WORKSPACE
     assert lib.bsr_score_select_batched_workspace_bytes(items(br=0), 2, 1) == 0
+    def mm_items(**k):
+        arr = (B._MatmulItem * 2)()
+        arr[0] = B._MatmulItem(0x1000, 0x1000, 0x1000, 64, 64, 16, 16, 0x1000, 32, 32, 0x1000, 32, 0)
+        arr[1] = B._MatmulItem(0x1000, 0x1000, 0x1000, k.get("M", 128), 64, k.get("br", 32), 32, k.get("dY", 0x1000),
+                               k.get("N", 48), k.get("lddy", 48), k.get("dW", 0x1000), k.get("lddw", 48), 0)
+        return arr
+    bm = lambda arr, n=2, dtype=1, ws=fake, ws_bytes=1 << 24: lib.bsr_t_dense_matmul_batched(arr, n, dtype, ws,
+                                                                                            ws_bytes, None)
+    assert bm(mm_items(), n=-2) == B.BSR_ERR_SHAPE
+    assert bm(None) == B.BSR_ERR_NULL
+    assert bm(mm_items(), n=0) == B.BSR_OK
+    assert bm(mm_items(), dtype=9) == B.BSR_ERR_DTYPE
+    assert bm(mm_items(br=0)) == B.BSR_ERR_SHAPE
+    assert bm(mm_items(lddy=40)) == B.BSR_ERR_SHAPE
+    assert bm(mm_items(lddw=8)) == B.BSR_ERR_SHAPE
+    assert bm(mm_items(dW=None)) == B.BSR_ERR_NULL
+    assert bm(mm_items(dY=None)) == B.BSR_ERR_NULL
+    assert bm(mm_items(dW=0x1002)) == B.BSR_ERR_ALIGN
+    big = mm_items(M=25088, N=1536, lddy=1536, lddw=1536)           # a product that is split: needs its workspace
+    need = lib.bsr_t_dense_matmul_batched_workspace_bytes(big, 2, 1)
+    assert need >= 4 * 64 * 1536
+    assert bm(big, ws=None) == B.BSR_ERR_WORKSPACE
+    assert bm(big, ws_bytes=need - 1) == B.BSR_ERR_WORKSPACE
+    assert lib.bsr_t_dense_matmul_batched_workspace_bytes(mm_items(br=0), 2, 1) == 0
     assert B.lib().bsr_error_string(B.BSR_ERR_WORKSPACE) == b"BSR_ERR_WORKSPACE"
 
 
