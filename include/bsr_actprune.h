@@ -225,9 +225,13 @@ int bsr_score_select_batched(const bsr_select_item *items, int n, int dtype,
 
 /*
  * Several weight gradients per call (for instance those of all linear layers whose
- * pruned inputs are at hand): every item is exactly one bsr_t_dense_matmul, bit
- * for bit, but items of the same block shape share kernel launches, so that the
- * table build and the write-out of one product overlap the main loop of another.
+ * pruned inputs are at hand): every item is one bsr_t_dense_matmul, but items of
+ * the same block shape share kernel launches, so that the table build and the
+ * write-out of one product overlap the main loop of another, and a product that
+ * shares its launch splits its contraction into fewer parts (the other products
+ * keep the GPU busy).  The sums are therefore added in another order than in the
+ * single call: equal to rounding (same error bound), reproducible run to run, and
+ * identical to the single call for a batch of one.
  * `items` is a host array, read before the call returns; all items share `dtype`;
  * outputs of different items must not overlap.  Workspace:
  * bsr_t_dense_matmul_batched_workspace_bytes(items, n, dtype) (0 for invalid

@@ -633,10 +633,33 @@ int dy_vector(const void *dY, int64_t N, int64_t lddy) {
   return vb;
 }
 
+// The plan of a product that shares its launch with `companions` - 1 others.  A product on
+// its own needs enough splits to occupy every compute unit; in a batch the other products
+// do that, so it takes as few splits as the table of a split allows (fewer partial tiles to
+// write and to add up, fewer table builds), but enough that the whole launch still has
+// about four workgroups per compute unit.  Never more splits than on its own: the
+// workspace is sized for that.
+template <int E, int BR, int MS>
+Plan make_plan_batched(int64_t M, int64_t K, int64_t N, int companions) {
+  const Plan alone = make_plan<E, BR, MS>(M, K, N);
+  if (companions <= 1 || alone.splits <= 1) return alone;
+  constexpr int R = MS / BR;
+  const int64_t stages = ceil_div(ceil_div(M, BR), R);
+  const int64_t tiles = ceil_div(K, 128) * ceil_div(N, 128);
+  int64_t s = ceil_div(1024, (int64_t)companions * tiles);
+  const int64_t s_min = ceil_div(stages * R, (int64_t)kMaxRowsPerSplit);
+  if (s < s_min) s = s_min;
+  if (s >= alone.splits) return alone;
+  Plan p;
+  p.stages_per_split = ceil_div(stages, s);
+  p.splits = (int)ceil_div(stages, p.stages_per_split);
+  return p;
+}
+
 // Kernel parameters of one product; *wgs = workgroups of its launch, *splits as planned.
 template <int E, int BR, int BC, int MS>
-int fill_params(const DwJob &j, DwParams *prm, uint32_t *wgs) {
-  const Plan p = make_plan<E, BR, MS>(j.M, j.K, j.N);
+int fill_params(const DwJob &j, DwParams *prm, uint32_t *wgs, int companions = 1) {
+  const Plan p = make_plan_batched<E, BR, MS>(j.M, j.K, j.N, companions);
   const size_t need = p.splits > 1 ? (size_t)p.splits * j.K * j.N * sizeof(float) : 0;
   if (need > 0 && (j.ws == nullptr || j.ws_bytes < need)) return BSR_ERR_WORKSPACE;
   const int64_t nbr = ceil_div(j.M, BR), nbc = ceil_div(j.K, BC);
@@ -710,11 +733,18 @@ int run_batched(const DwJob *jobs, int n, int want_vb, hipStream_t s) {
     total = 0;
     return rc;
   };
+  int mine = 0;                                              // products of this kernel instance
+  for (int i = 0; i < n; ++i)
+    if (jobs[i].br == BR && jobs[i].bc == BC && dy_vector<E>(jobs[i].dY, jobs[i].N, jobs[i].lddy) == want_vb) ++mine;
+  int left = mine;
   for (int i = 0; i < n; ++i) {
     const DwJob &j = jobs[i];
     if (j.br != BR || j.bc != BC || dy_vector<E>(j.dY, j.N, j.lddy) != want_vb) continue;
     uint32_t wgs;
-    int rc = fill_params<E, BR, BC, MS>(j, &b.it[m], &wgs);
+    // products that share this launch: the rest of the list, up to the launch's capacity
+    const int companions = m + (left < kDwBatchMax - m ? left : kDwBatchMax - m);
+    --left;
+    int rc = fill_params<E, BR, BC, MS>(j, &b.it[m], &wgs, companions);
     if (rc != BSR_OK) return rc;
     b.it[m].wg_begin = total;
     total += wgs;

@@ -129,3 +129,35 @@ def test_s12_layer_per_sample_selection():
         # every full group keeps the same number of blocks (equal nnz per sample)
         per_group = o_mask[: (spec.nbr // g) * g * spec.nbc].reshape(-1, g * spec.nbc).sum(axis=1)
         assert len(set(per_group.tolist())) == 1
+
+
+@pytest.mark.parametrize("kind", ["fc1", "fc2", "xpatch"])
+def test_s12_batched_dw_of_a_whole_step_shape(kind):
+    """Twelve weight gradients of one shape in one bsr_t_dense_matmul_batched call, as in the benchmark step
+    (they then use fewer splits of the contraction than a single call): sampled entries against the oracle,
+    dead block-columns exactly zero, reproducible."""
+    spec = {s.name: s for s in synth.s12_layer(128)}[kind]
+    X, _ = synth.make_pair(spec, 80)
+    o_scores, o_mask, o_rp, o_ci, o_val = oracle.prune(X, spec.br, spec.bc, spec.keep)
+    rp, ci = torch.from_numpy(o_rp).cuda(), torch.from_numpy(o_ci).cuda()
+    val = to_dev(o_val.reshape(-1, spec.bc)).reshape(o_val.shape)
+    dYs_host = [synth.make_pair(spec, 81 + i)[1] for i in range(12)]
+    dYs = [to_dev(d) for d in dYs_host]
+    batch = B.MatmulBatch([(rp, ci, val, spec.M, spec.K, spec.br, spec.bc, d) for d in dYs])
+    outs = B.bsr_t_dense_matmul_batched(batch)
+    torch.cuda.synchronize()
+    first = [o.cpu().numpy().copy() for o in outs]
+    B.bsr_t_dense_matmul_batched(batch)
+    torch.cuda.synchronize()
+    xhat = oracle.mask_dense(X, spec.br, spec.bc, o_mask)
+    rng = np.random.default_rng(82)
+    dead = np.flatnonzero(o_mask.reshape(spec.nbr, spec.nbc).sum(axis=0) == 0)
+    for i in range(12):
+        g = first[i]
+        assert outs[i].cpu().numpy().tobytes() == g.tobytes()
+        ks, ns = rng.integers(0, spec.K, 24), rng.integers(0, spec.N, 24)
+        ref = np.array([oracle.dw_entry(xhat, dYs_host[i], int(k), int(n)) for k, n in zip(ks, ns)])
+        err = float(np.max(np.abs(g[ks, ns].astype(np.float64) - ref))) / float(np.max(np.abs(g)))
+        assert err <= DW_TOL[spec.dtype], (i, err)
+        for j in dead:
+            assert not g[j * spec.bc:(j + 1) * spec.bc].any()

@@ -565,7 +565,17 @@ def test_batched_dw_more_items_than_one_launch_holds():
     batch = B.MatmulBatch([(rp, ci, val, M, K, 32, 32, dY) for dY in dYs])
     outs = B.bsr_t_dense_matmul_batched(batch)
     torch.cuda.synchronize()
+    first = [o.cpu().numpy().copy() for o in outs]
+    B.bsr_t_dense_matmul_batched(batch)
+    torch.cuda.synchronize()
+    xhat = synth.to_f64(oracle.mask_dense(X, 32, 32, o_mask))
     for i, dY in enumerate(dYs):
+        # products that share a launch split their contraction less often than a product on its own:
+        # same sums in another order, so equal to rounding, and the same from run to run
         single = B.bsr_t_dense_matmul(rp, ci, val, M, K, 32, 32, dY)
         torch.cuda.synchronize()
-        assert outs[i].cpu().numpy().tobytes() == single.cpu().numpy().tobytes(), f"item {i}"
+        assert outs[i].cpu().numpy().tobytes() == first[i].tobytes(), f"item {i} not reproducible"
+        assert dw_error(first[i], single.cpu().numpy().astype(np.float64)) <= 2e-6, f"item {i}"
+        if i % 9 == 0:
+            ref = xhat.T @ synth.to_f64(to_host(dY))
+            assert dw_error(first[i], ref) <= DW_TOL_DERIVED, f"item {i}"
