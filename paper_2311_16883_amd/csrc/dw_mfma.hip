@@ -183,7 +183,12 @@ __device__ __forceinline__ void dw_mfma_body(const DwParams &prm, const uint32_t
   }
   if (item >= items) return;
   const int split = item / tiles, tile = item % tiles;
-  const int tile_x = tile % tiles_k, tile_y = tile / tiles_k;
+  // Tiles are numbered fastest along the dimension with fewer tiles: when a split's tiles are
+  // shared out to two XCDs (fewer splits than XCDs), each of them then needs all of the smaller
+  // operand but only its part of the larger one.
+  const bool n_fastest = tiles_n < tiles_k;
+  const int tile_x = n_fastest ? tile / tiles_n : tile % tiles_k;
+  const int tile_y = n_fastest ? tile % tiles_n : tile / tiles_k;
 
   // LDS: two stage buffers (A tile then B tile each) that also stage the column
   // indices of the split before the main loop, a 1 KB dump slot (16 bytes per
