@@ -831,10 +831,10 @@ int launch_dw_mfma_batched(int dtype, const DwJob *jobs, int n, hipStream_t s) {
       if ((rc = run_batched<float, 16, 16, 32, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
       if ((rc = run_batched<float, 14, 14, 32, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
     } else {
-      if ((rc = run_batched<uint16_t, 32, 32, 64, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
-      if ((rc = run_batched<uint16_t, 64, 64, 64, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
-      if ((rc = run_batched<uint16_t, 16, 16, 32, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
-      if ((rc = run_batched<uint16_t, 14, 14, 32, 2, 4>(jobs, n, vb, s)) != BSR_OK) return rc;
+      if ((rc = run_batched<uint16_t, 32, 32, 64, 2, 2>(jobs, n, vb, s)) != BSR_OK) return rc;
+      if ((rc = run_batched<uint16_t, 64, 64, 64, 2, 2>(jobs, n, vb, s)) != BSR_OK) return rc;
+      if ((rc = run_batched<uint16_t, 16, 16, 32, 2, 2>(jobs, n, vb, s)) != BSR_OK) return rc;
+      if ((rc = run_batched<uint16_t, 14, 14, 32, 2, 2>(jobs, n, vb, s)) != BSR_OK) return rc;
     }
   }
   return BSR_OK;
