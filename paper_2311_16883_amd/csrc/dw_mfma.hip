@@ -642,7 +642,7 @@ int dy_vector(const void *dY, int64_t N, int64_t lddy) {
 // its own needs enough splits to occupy every compute unit; in a batch the other products
 // do that, so it takes as few splits as the table of a split allows (fewer partial tiles to
 // write and to add up, fewer table builds), but enough that the whole launch still has
-// about four workgroups per compute unit.  Never more splits than on its own: the
+// about two workgroups per compute unit.  Never more splits than on its own: the
 // workspace is sized for that.
 template <int E, int BR, int MS>
 Plan make_plan_batched(int64_t M, int64_t K, int64_t N, int companions) {
@@ -651,7 +651,7 @@ Plan make_plan_batched(int64_t M, int64_t K, int64_t N, int companions) {
   constexpr int R = MS / BR;
   const int64_t stages = ceil_div(ceil_div(M, BR), R);
   const int64_t tiles = ceil_div(K, 128) * ceil_div(N, 128);
-  int64_t s = ceil_div(1024, (int64_t)companions * tiles);
+  int64_t s = ceil_div(512, (int64_t)companions * tiles);
   const int64_t s_min = ceil_div(stages * R, (int64_t)kMaxRowsPerSplit);
   if (s < s_min) s = s_min;
   if (s >= alone.splits) return alone;
