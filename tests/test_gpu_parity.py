@@ -541,9 +541,15 @@ def test_batched_dw_equals_single_calls(dtype):
     outs = B.bsr_t_dense_matmul_batched(batch)
     torch.cuda.synchronize()
     for i, (got, single, ref) in enumerate(zip(outs, singles, refs)):
-        assert got.cpu().numpy().tobytes() == single.cpu().numpy().tobytes(), f"item {i} differs from the single call"
+        # products that share a launch may split their contraction less often than on their own: equal to rounding
+        assert dw_error(got.cpu().numpy(), single.cpu().numpy().astype(np.float64)) <= 2e-6, f"item {i}"
         if ref is not None:
             assert dw_error(got.cpu().numpy(), ref) <= DW_TOL[dtype], f"item {i}"
+    # a batch of one is the single call, bit for bit
+    for i in (0, 3, 6, 7):
+        alone = B.bsr_t_dense_matmul_batched(B.MatmulBatch([problems[i]]))
+        torch.cuda.synchronize()
+        assert alone[0].cpu().numpy().tobytes() == singles[i].cpu().numpy().tobytes(), f"item {i} alone"
     # accumulate on top of existing gradients, twice the same batch
     acc = [(p + (torch.full_like(o, 0.5),)) for p, o in zip(problems, outs)]
     batch2 = B.MatmulBatch(acc, accumulate=True)
