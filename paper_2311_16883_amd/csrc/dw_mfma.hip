@@ -142,7 +142,7 @@ struct DwParams {
   int64_t M, K, N, lddy, ldo, split_stride, nbr, nbc, stages_per_split;
   int accumulate, tiles_k, tiles_n, splits;
   uint32_t values_bytes;
-  uint32_t wg_begin;       // first workgroup of this tensor in a batched launch (a multiple of 8)
+  uint32_t wg_begin;       // first work item of this tensor in a batched launch's list
 };
 
 // wg = number of the workgroup among those of this tensor.
@@ -571,20 +571,30 @@ __global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(DwParams prm, int xcd
   dw_mfma_body<T, BR, BC, MS, VB, D, WN>(prm, blockIdx.x, xcd_map);
 }
 
-// Several tensors per launch: tensor i owns the workgroups [wg_begin_i, wg_begin_{i+1}); its
-// own 8-way dealing of work items to XCDs is kept because every wg_begin is a multiple of 8.
+// Several tensors per launch.  The work items (split, tile) of all products form one list,
+// product after product (wg_begin = a product's first item), and XCD x (workgroup id % 8)
+// takes the contiguous part [xcd_begin[x], xcd_begin[x + 1]) of it, cut by the host so that
+// every XCD gets about the same number of stages.  An XCD then works on whole splits, one
+// after the other, and fetches the operands of a split into its L2 once; dealing every
+// product to all eight XCDs separately puts the halves of a split on two XCDs when a
+// product has fewer splits than there are XCDs (a fifth more L2 fetches at the ResMLP-S12
+// shapes, at the same run time).
 // With many more workgroups than compute units the table build and the write-out of one
 // workgroup overlap the main loop of its neighbour on the same compute unit.
 constexpr int kDwBatchMax = 16;
 struct DwBatch {
   DwParams it[kDwBatchMax];
+  uint32_t xcd_begin[9];
 };
 
 template <typename T, int BR, int BC, int MS, int VB, int D, int WN>
 __global__ __launch_bounds__(256 * WN) void dw_mfma_batched_kernel(DwBatch b, int n) {
+  const uint32_t x = blockIdx.x & 7u, slot = blockIdx.x >> 3;
+  if (slot >= b.xcd_begin[x + 1] - b.xcd_begin[x]) return;
+  const uint32_t g = b.xcd_begin[x] + slot;
   int i = 0;
-  while (i + 1 < n && blockIdx.x >= b.it[i + 1].wg_begin) ++i;
-  dw_mfma_body<T, BR, BC, MS, VB, D, WN>(b.it[i], blockIdx.x - b.it[i].wg_begin, 1);
+  while (i + 1 < n && g >= b.it[i + 1].wg_begin) ++i;
+  dw_mfma_body<T, BR, BC, MS, VB, D, WN>(b.it[i], g - b.it[i].wg_begin, 0);
 }
 
 struct Plan {
@@ -722,7 +732,31 @@ int run_batched(const DwJob *jobs, int n, int want_vb, hipStream_t s) {
   uint32_t total = 0;
   auto flush = [&]() -> int {
     if (m == 0) return BSR_OK;
-    const dim3 grid(total), block(256 * WN);
+    // cut the item list into eight parts of about equal cost: an item costs its stages plus
+    // a fixed part (table build, write-out) of about sixteen stages
+    int64_t cost[kDwBatchMax], all = 0;
+    for (int i = 0; i < m; ++i) {
+      cost[i] = b.it[i].stages_per_split + 16;
+      all += cost[i] * (int64_t)b.it[i].splits * b.it[i].tiles_k * b.it[i].tiles_n;
+    }
+    int x = 1;
+    int64_t cum = 0;
+    b.xcd_begin[0] = 0;
+    for (int i = 0; i < m; ++i) {
+      const int64_t items = (int64_t)b.it[i].splits * b.it[i].tiles_k * b.it[i].tiles_n;
+      while (x < 8 && x * all <= 8 * (cum + items * cost[i])) {
+        int64_t k = ceil_div(x * all - 8 * cum, 8 * cost[i]);     // items of product i before the cut
+        if (k < 0) k = 0;
+        if (k > items) k = items;
+        b.xcd_begin[x++] = b.it[i].wg_begin + (uint32_t)k;
+      }
+      cum += items * cost[i];
+    }
+    while (x <= 8) b.xcd_begin[x++] = total;
+    uint32_t longest = 0;
+    for (int q = 0; q < 8; ++q)
+      if (b.xcd_begin[q + 1] - b.xcd_begin[q] > longest) longest = b.xcd_begin[q + 1] - b.xcd_begin[q];
+    const dim3 grid(8 * longest), block(256 * WN);
     switch (want_vb) {
       case 8:
         if constexpr (E == 2) hipLaunchKernelGGL((dw_mfma_batched_kernel<T, BR, BC, MS, 8, D, WN>), grid, block, 0, s, b, m);
@@ -751,8 +785,9 @@ int run_batched(const DwJob *jobs, int n, int want_vb, hipStream_t s) {
     --left;
     int rc = fill_params<E, BR, BC, MS>(j, &b.it[m], &wgs, companions);
     if (rc != BSR_OK) return rc;
-    b.it[m].wg_begin = total;
-    total += wgs;
+    b.it[m].wg_begin = total;                                // first item of this product in the launch's list
+    total += (uint32_t)(b.it[m].splits * b.it[m].tiles_k * b.it[m].tiles_n);
+    (void)wgs;
     if (b.it[m].splits > 1)
       red[nred++] = ReduceJob{b.it[m].out, j.dW, j.K, j.N, j.lddw, b.it[m].splits, j.accumulate};
     if (++m == kDwBatchMax) {
