@@ -6,8 +6,14 @@ BSR -> dense, dW) and prints a Markdown table: microseconds per call (HIP events
 call, minimum of five), the dW rate on kept blocks and the forward rate
 ``(1 + 2 keep) |X| / (score + select + mask -> BSR)``.  Single calls with nothing else on the
 GPU: launch latency is part of every figure.  Inputs are the seeded synthetic tensors.
+
+By default a call is repeated on the same buffers, so operands of up to a few hundred MB may
+still sit in the memory-side cache from the previous repetition ("warm").  ``--cold`` rewrites
+a 1 GiB scratch buffer before every timed call, which leaves nothing of the operands in any cache.
 """
 from __future__ import annotations
+
+import sys
 
 import numpy as np
 import torch
@@ -20,11 +26,19 @@ def _event():
     return torch.cuda.Event(enable_timing=True)
 
 
-def _time_us(f, reps: int = 5) -> float:
+_scratch = None
+
+
+def _time_us(f, reps: int = 5, cold: bool = False) -> float:
+    global _scratch
+    if cold and _scratch is None:
+        _scratch = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     f()
     torch.cuda.synchronize()
     best = float("inf")
-    for _ in range(reps):
+    for rep in range(reps):
+        if cold:
+            _scratch.fill_(rep)
         a, b = _event(), _event()
         a.record()
         f()
@@ -45,11 +59,14 @@ def specs():
     picked = ["s24_fc1_b16_k50", "s24_fc2_b16_k50", "s24_fc1_b32_k50", "s24_fc2_b32_k50", "s24_fc1_b64_k50",
               "s24_fc2_b64_k10", "s24_fc2_b64_k50", "s24_fc2_b64_k90"]
     return (list(synth.tiny()) + list(synth.s12_fc1_f32()) + list(synth.s12_layer(128)) +
-            [sweep[n] for n in picked] + list(synth.b24_fc2()))
+            [sweep[n] for n in picked] + list(synth.b24_fc2()) + list(synth.b24_fc2(hot_first=True)))
 
 
 def main() -> None:
     assert torch.cuda.is_available(), "needs a GPU"
+    cold = "--cold" in sys.argv[1:]
+    print("# cold: a 1 GiB buffer is rewritten before every timed call" if cold
+          else "# warm: repeated calls on the same buffers")
     print("| workload | X, dY, block, keep | score+select | mask->BSR | BSR->dense | dW | dW TFLOP/s (kept) "
           "| forward GB/s |")
     print("|---|---|---|---|---|---|---|---|")
@@ -67,14 +84,16 @@ def main() -> None:
         val = torch.empty((n_keep, sp.br, sp.bc), dtype=Xd.dtype, device="cuda")
         Xh = torch.empty_like(Xd)
         dW = torch.empty((sp.K, sp.N), dtype=torch.float32, device="cuda")
-        t1 = _time_us(lambda: B.bsr_score_select(Xd, sp.br, sp.bc, sp.keep, keep_mask=mask, ws=ws))
+        t1 = _time_us(lambda: B.bsr_score_select(Xd, sp.br, sp.bc, sp.keep, keep_mask=mask, ws=ws), cold=cold)
         t2 = _time_us(lambda: B.bsr_compress(Xd, sp.br, sp.bc, mask, n_keep, row_ptr=rp, col_idx=ci, values=val,
-                                             ws=ws))
-        t3 = _time_us(lambda: B.bsr_decompress(rp, ci, val, sp.M, sp.K, sp.br, sp.bc, out=Xh))
-        t4 = _time_us(lambda: B.bsr_t_dense_matmul(rp, ci, val, sp.M, sp.K, sp.br, sp.bc, dYd, dW=dW, ws=ws))
+                                             ws=ws), cold=cold)
+        t3 = _time_us(lambda: B.bsr_decompress(rp, ci, val, sp.M, sp.K, sp.br, sp.bc, out=Xh), cold=cold)
+        t4 = _time_us(lambda: B.bsr_t_dense_matmul(rp, ci, val, sp.M, sp.K, sp.br, sp.bc, dYd, dW=dW, ws=ws),
+                      cold=cold)
         flops = 2.0 * n_keep * sp.br * sp.bc * sp.N
         fwd_bytes = (1 + 2 * sp.keep) * sp.M * sp.K * Xd.element_size()
-        print(f"| {sp.name} | [{sp.M}x{sp.K}], [{sp.M}x{sp.N}], {sp.br}x{sp.bc} {sp.dtype}, {sp.keep} | {t1:.1f} | "
+        name = sp.name + ("_first_columns_hot" if sp.hot_first else "")
+        print(f"| {name} | [{sp.M}x{sp.K}], [{sp.M}x{sp.N}], {sp.br}x{sp.bc} {sp.dtype}, {sp.keep} | {t1:.1f} | "
               f"{t2:.1f} | {t3:.1f} | {t4:.1f} | {flops / t4 / 1e6:.1f} | {fwd_bytes / (t1 + t2) / 1e3:.0f} |",
               flush=True)
         del Xd, dYd, val, Xh, dW, ws
