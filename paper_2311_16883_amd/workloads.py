@@ -3,8 +3,8 @@
 ``python -m paper_2311_16883_amd.workloads`` runs, for one tensor of each family, the
 calls of the path one after the other on the current stream (score + select, mask -> BSR,
 BSR -> dense, dW) and prints a Markdown table: microseconds per call (HIP events around the
-call, minimum of five), the dW rate on kept blocks and the forward rate
-``(1 + 2 keep) |X| / (score + select + mask -> BSR)``.  Single calls with nothing else on the
+call, minimum / median of 50 after 10 warm-up calls), the dW rate on kept blocks and the forward
+rate ``(1 + 2 keep) |X| / (score + select + mask -> BSR)``, both from the minima.  Single calls with nothing else on the
 GPU: launch latency is part of every figure.  Inputs are the seeded synthetic tensors.
 
 By default a call is repeated on the same buffers, so operands of up to a few hundred MB may
@@ -29,13 +29,15 @@ def _event():
 _scratch = None
 
 
-def _time_us(f, reps: int = 5, cold: bool = False) -> float:
+def _time_us(f, reps: int = 50, warmup: int = 10, cold: bool = False):
+    """(minimum, median) over `reps` timed calls after `warmup` untimed ones, in microseconds."""
     global _scratch
     if cold and _scratch is None:
         _scratch = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
-    f()
+    for _ in range(warmup):
+        f()
     torch.cuda.synchronize()
-    best = float("inf")
+    ts = []
     for rep in range(reps):
         if cold:
             _scratch.fill_(rep)
@@ -44,8 +46,8 @@ def _time_us(f, reps: int = 5, cold: bool = False) -> float:
         f()
         b.record()
         torch.cuda.synchronize()
-        best = min(best, a.elapsed_time(b) * 1e3)
-    return best
+        ts.append(a.elapsed_time(b) * 1e3)
+    return min(ts), float(np.median(ts))
 
 
 def _to_dev(a: np.ndarray) -> torch.Tensor:
@@ -93,9 +95,9 @@ def main() -> None:
         flops = 2.0 * n_keep * sp.br * sp.bc * sp.N
         fwd_bytes = (1 + 2 * sp.keep) * sp.M * sp.K * Xd.element_size()
         name = sp.name + ("_first_columns_hot" if sp.hot_first else "")
-        print(f"| {name} | [{sp.M}x{sp.K}], [{sp.M}x{sp.N}], {sp.br}x{sp.bc} {sp.dtype}, {sp.keep} | {t1:.1f} | "
-              f"{t2:.1f} | {t3:.1f} | {t4:.1f} | {flops / t4 / 1e6:.1f} | {fwd_bytes / (t1 + t2) / 1e3:.0f} |",
-              flush=True)
+        cells = " | ".join(f"{t[0]:.1f} / {t[1]:.1f}" for t in (t1, t2, t3, t4))
+        print(f"| {name} | [{sp.M}x{sp.K}], [{sp.M}x{sp.N}], {sp.br}x{sp.bc} {sp.dtype}, {sp.keep} | {cells} | "
+              f"{flops / t4[0] / 1e6:.1f} | {fwd_bytes / (t1[0] + t2[0]) / 1e3:.0f} |", flush=True)
         del Xd, dYd, val, Xh, dW, ws
 
 
