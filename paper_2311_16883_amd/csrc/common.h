@@ -141,7 +141,7 @@ bool span_geometry(int dtype, int64_t M, int64_t K, int64_t ld, int br, int bc, 
                    const void *p1, SpanGeom *g);
 
 // Several reductions / several dW products per launch.
-constexpr int kReduceBatchMax = 16;
+constexpr int kReduceBatchMax = 24;
 struct ReduceJob {
   const float *partial;
   float *dW;

@@ -581,7 +581,7 @@ __global__ __launch_bounds__(256 * WN) void dw_mfma_kernel(DwParams prm, int xcd
 // shapes, at the same run time).
 // With many more workgroups than compute units the table build and the write-out of one
 // workgroup overlap the main loop of its neighbour on the same compute unit.
-constexpr int kDwBatchMax = 16;
+constexpr int kDwBatchMax = 24;
 struct DwBatch {
   DwParams it[kDwBatchMax];
   uint32_t xcd_begin[9];
