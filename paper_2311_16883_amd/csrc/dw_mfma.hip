@@ -650,24 +650,37 @@ int dy_vector(const void *dY, int64_t N, int64_t lddy) {
 
 // The plan of a product that shares its launch with `companions` - 1 others.  A product on
 // its own needs enough splits to occupy every compute unit; in a batch the other products
-// do that, so it takes as few splits as the table of a split allows (fewer partial tiles to
-// write and to add up, fewer table builds), but enough that the whole launch still has
-// about two workgroups per compute unit.  Never more splits than on its own: the
-// workspace is sized for that.
+// do that, so fewer splits will do (fewer partial tiles to write and to add up, fewer table
+// builds).  The launch runs its work items about two per compute unit at a time, so its
+// duration is roughly (rounds of 512 items) x (stages of an item + a fixed part); the number
+// of splits is the one that makes this smallest, the partial tiles counted at what their
+// traffic costs, as if the companions were products of the same shape.  Never more splits
+// than on its own: the workspace is sized for that.
 template <int E, int BR, int MS>
 Plan make_plan_batched(int64_t M, int64_t K, int64_t N, int companions) {
   const Plan alone = make_plan<E, BR, MS>(M, K, N);
   if (companions <= 1 || alone.splits <= 1) return alone;
   constexpr int R = MS / BR;
+  constexpr int64_t kSlots = 512, kFixed = 16;                 // fixed part of an item, in stages
+  constexpr double kBytesPerStage = 4.6e6;                     // HBM bytes moved in the time of one stage
   const int64_t stages = ceil_div(ceil_div(M, BR), R);
   const int64_t tiles = ceil_div(K, 128) * ceil_div(N, 128);
-  int64_t s = ceil_div(512, (int64_t)companions * tiles);
   const int64_t s_min = ceil_div(stages * R, (int64_t)kMaxRowsPerSplit);
-  if (s < s_min) s = s_min;
-  if (s >= alone.splits) return alone;
-  Plan p;
-  p.stages_per_split = ceil_div(stages, s);
-  p.splits = (int)ceil_div(stages, p.stages_per_split);
+  if (s_min >= alone.splits) return alone;
+  const double split_cost = (double)companions * (double)K * (double)N * 8.0 / kBytesPerStage;
+  double best = 0;
+  Plan p = alone;
+  for (int64_t s = s_min; s <= alone.splits; ++s) {
+    const int64_t sps = ceil_div(stages, s);
+    const int64_t s_eff = ceil_div(stages, sps);
+    const int64_t rounds = ceil_div((int64_t)companions * tiles * s_eff, kSlots);
+    const double cost = (double)(rounds * (sps + kFixed)) + (double)s_eff * split_cost;
+    if (s == s_min || cost < best) {
+      best = cost;
+      p.splits = (int)s_eff;
+      p.stages_per_split = sps;
+    }
+  }
   return p;
 }
 
