@@ -45,7 +45,7 @@ typedef __attribute__((ext_vector_type(8))) short v8s;
 typedef __attribute__((ext_vector_type(8))) __bf16 v8bf;
 typedef __attribute__((ext_vector_type(16))) float v16f;
 
-constexpr int kMaxRowsPerSplit = 256;   // block-rows of one split: its block table must fit in LDS
+constexpr int kMaxRowsPerSplit = 512;   // block-rows of one split: its block table must fit in LDS
 
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose
 // index is a compile-time constant in every trip, whatever its length (register
@@ -662,7 +662,7 @@ Plan make_plan_batched(int64_t M, int64_t K, int64_t N, int companions) {
   if (companions <= 1 || alone.splits <= 1) return alone;
   constexpr int R = MS / BR;
   constexpr int64_t kSlots = 512, kFixed = 16;                 // fixed part of an item, in stages
-  constexpr double kBytesPerStage = 4.6e6;                     // HBM bytes moved in the time of one stage
+  constexpr double kBytesPerStage = 2.0e6;                     // partial-tile bytes that cost the time of one stage (measured)
   const int64_t stages = ceil_div(ceil_div(M, BR), R);
   const int64_t tiles = ceil_div(K, 128) * ceil_div(N, 128);
   const int64_t s_min = ceil_div(stages * R, (int64_t)kMaxRowsPerSplit);
