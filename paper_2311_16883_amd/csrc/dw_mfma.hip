@@ -622,7 +622,10 @@ Plan make_plan(int64_t M, int64_t K, int64_t N) {
   // (binary32 stages are bound by the matrix core: 16 times the passes per multiply-add)
   const double us_stage = (E == 4 ? 1.3 : 0.42) * MS / 64.0, us_round = 8.0;
   const double us_split = 2.0 * (double)K * (double)N * 4.0 / 3.0e6;
-  const int64_t s_min = ceil_div(stages * R, (int64_t)kMaxRowsPerSplit);
+  // (at least one split per 256 block-rows, although the table would hold 512: for 16-row blocks at
+  // 50176 rows 14 splits of 112 stages take 106 us where 7 of 224 take 156 us, which this model of
+  // rounds of 256 workgroups does not see -- two workgroups fit a compute unit)
+  const int64_t s_min = ceil_div(stages * R, (int64_t)256);
   int64_t s_max = stages < 64 ? stages : 64;
   if (s_max < s_min) s_max = s_min;
   double best = 0;
