@@ -602,16 +602,17 @@ struct Plan {
   int64_t stages_per_split;
 };
 
-// Number of splits of the contraction.  One workgroup (loader and multiplier
-// waves) runs per compute unit, so the tiles x splits work items are processed in
-// rounds of 256; a round costs its stages plus a fixed part (table build, partial
-// tile write-out), and every split adds one pass over the K x N partial tiles
-// (written once, read once by the reduction).  The constants are measured orders
-// of magnitude on MI355X, in microseconds; only the choice of s depends on them.
+// Number of splits of the contraction.  The tiles x splits work items are processed in rounds
+// of one workgroup per compute unit (binary32: 128 KB of LDS each) or two (2-byte elements); a
+// round costs its stages plus a fixed part (table build, partial tile write-out), and every
+// split adds one pass over the K x N partial tiles (written once, read once by the
+// reduction).  The constants are measured orders of magnitude on MI355X, in microseconds
+// (a stage of a workgroup that shares its compute unit takes 0.7 us); only the choice of s
+// depends on them.
 template <int E, int BR, int MS>
 Plan make_plan(int64_t M, int64_t K, int64_t N) {
   constexpr int R = MS / BR;
-  constexpr int kSlots = 256;
+  constexpr int kSlots = E == 2 ? 512 : 256;
   const int64_t nbr = ceil_div(M, BR);
   const int64_t stages = ceil_div(nbr, R);
   const int64_t tiles = ceil_div(K, 128) * ceil_div(N, 128);
@@ -620,11 +621,10 @@ Plan make_plan(int64_t M, int64_t K, int64_t N) {
   p.stages_per_split = stages > 0 ? stages : 1;
   if (stages <= 0 || tiles <= 0) return p;
   // (binary32 stages are bound by the matrix core: 16 times the passes per multiply-add)
-  const double us_stage = (E == 4 ? 1.3 : 0.42) * MS / 64.0, us_round = 8.0;
+  const double us_stage = (E == 4 ? 1.3 : 0.70) * MS / 64.0, us_round = 8.0;
   const double us_split = 2.0 * (double)K * (double)N * 4.0 / 3.0e6;
   // (at least one split per 256 block-rows, although the table would hold 512: for 16-row blocks at
-  // 50176 rows 14 splits of 112 stages take 106 us where 7 of 224 take 156 us, which this model of
-  // rounds of 256 workgroups does not see -- two workgroups fit a compute unit)
+  // 50176 rows 14 splits of 112 stages take 106 us where 7 of 224 take 156 us)
   const int64_t s_min = ceil_div(stages * R, (int64_t)256);
   int64_t s_max = stages < 64 ? stages : 64;
   if (s_max < s_min) s_max = s_min;
