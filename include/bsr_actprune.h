@@ -258,6 +258,47 @@ int bsr_t_dense_matmul_batched(const bsr_matmul_item *items, int n, int dtype,
                                void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Several conversions per call: every item is one bsr_compress (Sec. III:
+ * conversion of the activation to BSR) or one bsr_decompress (Sec. II-A read
+ * backwards), with the same outputs bit for bit; tensors that take the same
+ * kernel share launches, so a step over many small tensors costs a few launches
+ * instead of one per tensor.  `items` is a host array, read before the call
+ * returns; all items share `dtype`; outputs of different items must not overlap.
+ * Workspace of bsr_compress_batched: bsr_compress_batched_workspace_bytes(items,
+ * n, dtype), the sum of what bsr_compress needs per item (0 for the shapes that
+ * need none, and for invalid items).  Errors as for the single calls, for the
+ * first offending item; nothing is launched if any item is invalid.
+ */
+typedef struct bsr_compress_item {
+  const void *X;            /* device, [M x K], leading dimension ldx */
+  int64_t M, K, ldx;
+  int32_t br, bc;
+  const uint8_t *keep_mask; /* device, [nblocks] */
+  int64_t n_keep;
+  int32_t *row_ptr;         /* device, [nbr + 1] */
+  int32_t *col_idx;         /* device, [n_keep] */
+  void *values;             /* device, [n_keep x br x bc] */
+} bsr_compress_item;
+
+size_t bsr_compress_batched_workspace_bytes(const bsr_compress_item *items,
+                                            int n, int dtype);
+
+int bsr_compress_batched(const bsr_compress_item *items, int n, int dtype,
+                         void *ws, size_t ws_bytes, void *stream);
+
+typedef struct bsr_decompress_item {
+  const int32_t *row_ptr;   /* device */
+  const int32_t *col_idx;   /* device */
+  const void *values;       /* device */
+  int64_t M, K, ldx;
+  int32_t br, bc;
+  void *X_out;              /* device, [M x K], leading dimension ldx */
+} bsr_decompress_item;
+
+int bsr_decompress_batched(const bsr_decompress_item *items, int n, int dtype,
+                           void *stream);
+
+/*
  * Sec. VI (outlook) names a block-sparse version of ResMLP's affine scaling
  * layer, y[m,k] = alpha[k] * x[m,k] + beta[k].  Of its backward pass only the
  * scale gradient needs the saved input; from the pruned input in BSR form:

@@ -32,6 +32,7 @@ EXPORTS = (
     "bsr_decompress", "bsr_t_dense_matmul", "bsr_grouped_keep_count", "bsr_score_select_grouped",
     "bsr_affine_scale_grad", "bsr_score_select_batched", "bsr_score_select_batched_workspace_bytes",
     "bsr_t_dense_matmul_batched", "bsr_t_dense_matmul_batched_workspace_bytes",
+    "bsr_compress_batched", "bsr_compress_batched_workspace_bytes", "bsr_decompress_batched",
 )
 
 
@@ -89,6 +90,12 @@ def lib() -> C.CDLL:
     l.bsr_t_dense_matmul_batched_workspace_bytes.argtypes = [vp, i32, i32]
     l.bsr_t_dense_matmul_batched.restype = i32
     l.bsr_t_dense_matmul_batched.argtypes = [vp, i32, i32, vp, sz, vp]
+    l.bsr_compress_batched_workspace_bytes.restype = sz
+    l.bsr_compress_batched_workspace_bytes.argtypes = [vp, i32, i32]
+    l.bsr_compress_batched.restype = i32
+    l.bsr_compress_batched.argtypes = [vp, i32, i32, vp, sz, vp]
+    l.bsr_decompress_batched.restype = i32
+    l.bsr_decompress_batched.argtypes = [vp, i32, i32, vp]
     l.bsr_affine_scale_grad.restype = i32
     l.bsr_affine_scale_grad.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, vp, i64, vp, i32, vp, sz, vp]
     _lib = l
@@ -401,3 +408,90 @@ def bsr_t_dense_matmul_batched(batch: MatmulBatch, *, ws: Optional[torch.Tensor]
                                           ws.numel() if ws is not None else 0, _stream(stream))
     _check(rc, "bsr_t_dense_matmul_batched")
     return batch.dWs
+
+
+class _CompressItem(C.Structure):
+    """Mirror of bsr_compress_item."""
+    _fields_ = [("X", C.c_void_p), ("M", C.c_int64), ("K", C.c_int64), ("ldx", C.c_int64),
+                ("br", C.c_int32), ("bc", C.c_int32), ("keep_mask", C.c_void_p), ("n_keep", C.c_int64),
+                ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("values", C.c_void_p)]
+
+
+class CompressBatch:
+    """The marshalled item array of one bsr_compress_batched call (see SelectBatch).  Every entry of `problems` is
+    (X, br, bc, keep_mask, n_keep) or that plus (row_ptr, col_idx, values) tensors to write into."""
+
+    def __init__(self, problems: Sequence[tuple]):
+        n = len(problems)
+        if n == 0:
+            raise ValueError("empty batch")
+        self.dtype = dtype_code(problems[0][0].dtype)
+        self.device = problems[0][0].device
+        self.items = (_CompressItem * n)()
+        self.keep, self.outputs = [], []
+        for i, pr in enumerate(problems):
+            X, br, bc, keep_mask, n_keep = pr[:5]
+            if dtype_code(X.dtype) != self.dtype:
+                raise ValueError("all tensors of a batch must have one dtype")
+            M, K, ldx = _dense2d(X, "X")
+            nbr = -(-M // br) if br > 0 else 0
+            if len(pr) > 5:
+                row_ptr, col_idx, values = pr[5:8]
+            else:
+                row_ptr = torch.empty(nbr + 1, dtype=torch.int32, device=X.device)
+                col_idx = torch.empty(max(n_keep, 0), dtype=torch.int32, device=X.device)
+                values = torch.empty((max(n_keep, 0), br, bc), dtype=X.dtype, device=X.device)
+            self.items[i] = _CompressItem(_ptr(X), M, K, ldx, br, bc, _ptr(keep_mask), int(n_keep), _ptr(row_ptr),
+                                          _ptr(col_idx), _ptr(values))
+            self.keep.append((X, keep_mask))
+            self.outputs.append((row_ptr, col_idx, values))
+        self.n = n
+        self.ws_bytes = int(lib().bsr_compress_batched_workspace_bytes(self.items, n, self.dtype))
+
+
+def bsr_compress_batched(batch: CompressBatch, *, ws: Optional[torch.Tensor] = None, stream=None):
+    """-> list of (row_ptr, col_idx, values), each what bsr_compress gives for its item."""
+    if ws is None:
+        ws = _workspace(batch.ws_bytes, batch.device, None)
+    rc = lib().bsr_compress_batched(batch.items, batch.n, batch.dtype, _ptr(ws), ws.numel() if ws is not None else 0,
+                                    _stream(stream))
+    _check(rc, "bsr_compress_batched")
+    return batch.outputs
+
+
+class _DecompressItem(C.Structure):
+    """Mirror of bsr_decompress_item."""
+    _fields_ = [("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("values", C.c_void_p),
+                ("M", C.c_int64), ("K", C.c_int64), ("ldx", C.c_int64), ("br", C.c_int32), ("bc", C.c_int32),
+                ("X_out", C.c_void_p)]
+
+
+class DecompressBatch:
+    """The marshalled item array of one bsr_decompress_batched call (see SelectBatch).  Every entry of `problems` is
+    (row_ptr, col_idx, values, M, K, br, bc) or that plus an output tensor to write into."""
+
+    def __init__(self, problems: Sequence[tuple]):
+        n = len(problems)
+        if n == 0:
+            raise ValueError("empty batch")
+        self.dtype = dtype_code(problems[0][2].dtype)
+        self.items = (_DecompressItem * n)()
+        self.keep, self.outputs = [], []
+        for i, pr in enumerate(problems):
+            row_ptr, col_idx, values, M, K, br, bc = pr[:7]
+            if dtype_code(values.dtype) != self.dtype:
+                raise ValueError("all tensors of a batch must have one dtype")
+            out = pr[7] if len(pr) > 7 and pr[7] is not None else \
+                torch.empty((M, K), dtype=values.dtype, device=values.device)
+            _, _, ldx = _dense2d(out, "out")
+            self.items[i] = _DecompressItem(_ptr(row_ptr), _ptr(col_idx), _ptr(values), M, K, ldx, br, bc, _ptr(out))
+            self.keep.append(pr)
+            self.outputs.append(out)
+        self.n = n
+
+
+def bsr_decompress_batched(batch: DecompressBatch, *, stream=None):
+    """-> list of dense tensors, each what bsr_decompress gives for its item."""
+    rc = lib().bsr_decompress_batched(batch.items, batch.n, batch.dtype, _stream(stream))
+    _check(rc, "bsr_decompress_batched")
+    return batch.outputs

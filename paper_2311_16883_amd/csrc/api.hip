@@ -351,4 +351,67 @@ int bsr_t_dense_matmul_batched(const bsr_matmul_item *items, int n, int dtype, v
   return rc;
 }
 
+size_t bsr_compress_batched_workspace_bytes(const bsr_compress_item *items, int n, int dtype) {
+  if (items == nullptr || n <= 0) return 0;
+  size_t total = 0;
+  for (int i = 0; i < n; ++i) {
+    const bsr_compress_item &it = items[i];
+    Geometry g;
+    if (check_shape(dtype, it.M, it.K, it.ldx, it.br, it.bc, &g) != BSR_OK) return 0;
+    total += align_up(compress_ws_bytes(dtype, it.M, it.K, it.br, it.bc), 256);
+  }
+  return total;
+}
+
+int bsr_compress_batched(const bsr_compress_item *items, int n, int dtype, void *ws, size_t ws_bytes,
+                         void *stream) {
+  if (n < 0) return BSR_ERR_SHAPE;
+  if (n == 0) return BSR_OK;
+  if (items == nullptr) return BSR_ERR_NULL;
+  if (misaligned(ws, 16)) return BSR_ERR_ALIGN;
+  std::vector<CompressJob> jobs;
+  jobs.reserve((size_t)n);
+  size_t off = 0;
+  for (int i = 0; i < n; ++i) {
+    const bsr_compress_item &it = items[i];
+    Geometry g;
+    const int rc = check_shape(dtype, it.M, it.K, it.ldx, it.br, it.bc, &g);
+    if (rc != BSR_OK) return rc;
+    if (it.n_keep < 0 || it.n_keep > g.nblocks) return BSR_ERR_KEEP;
+    const size_t need = align_up(compress_ws_bytes(dtype, it.M, it.K, it.br, it.bc), 256);
+    if (need > 0 && (ws == nullptr || off + need > ws_bytes)) return BSR_ERR_WORKSPACE;
+    if (it.row_ptr == nullptr) return BSR_ERR_NULL;
+    if (g.nblocks > 0 && (it.X == nullptr || it.keep_mask == nullptr)) return BSR_ERR_NULL;
+    if (it.n_keep > 0 && (it.col_idx == nullptr || it.values == nullptr)) return BSR_ERR_NULL;
+    if (misaligned(it.X, elem_bytes(dtype)) || misaligned(it.values, elem_bytes(dtype)) ||
+        misaligned(it.row_ptr, 4) || misaligned(it.col_idx, 4))
+      return BSR_ERR_ALIGN;
+    jobs.push_back(CompressJob{it.keep_mask, it.X, it.M, it.K, it.ldx, it.br, it.bc, it.n_keep, it.row_ptr,
+                               it.col_idx, it.values, need > 0 ? static_cast<char *>(ws) + off : nullptr});
+    off += need;
+  }
+  return launch_compress_batched(jobs.data(), (int)jobs.size(), dtype, static_cast<hipStream_t>(stream));
+}
+
+int bsr_decompress_batched(const bsr_decompress_item *items, int n, int dtype, void *stream) {
+  if (n < 0) return BSR_ERR_SHAPE;
+  if (n == 0) return BSR_OK;
+  if (items == nullptr) return BSR_ERR_NULL;
+  std::vector<DecompressJob> jobs;
+  jobs.reserve((size_t)n);
+  for (int i = 0; i < n; ++i) {
+    const bsr_decompress_item &it = items[i];
+    Geometry g;
+    const int rc = check_shape(dtype, it.M, it.K, it.ldx, it.br, it.bc, &g);
+    if (rc != BSR_OK) return rc;
+    if (g.nblocks == 0) continue;
+    if (it.row_ptr == nullptr || it.X_out == nullptr) return BSR_ERR_NULL;
+    if (misaligned(it.X_out, elem_bytes(dtype)) || misaligned(it.values, elem_bytes(dtype)) ||
+        misaligned(it.row_ptr, 4) || misaligned(it.col_idx, 4))
+      return BSR_ERR_ALIGN;
+    jobs.push_back(DecompressJob{it.row_ptr, it.col_idx, it.values, it.M, it.K, it.ldx, it.br, it.bc, it.X_out});
+  }
+  return launch_decompress_batched(jobs.data(), (int)jobs.size(), dtype, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

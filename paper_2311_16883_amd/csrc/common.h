@@ -83,6 +83,27 @@ int launch_compress(const uint8_t *keep_mask, const void *X, int dtype, int64_t 
 int launch_decompress(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int dtype,
                       int64_t M, int64_t K, int64_t ldx, int br, int bc, void *X_out, hipStream_t s);
 
+// Several tensors per call (see launch_compress_batched in pack.hip).
+struct CompressJob {
+  const uint8_t *keep_mask;
+  const void *X;
+  int64_t M, K, ldx;
+  int br, bc;
+  int64_t n_keep;
+  int32_t *row_ptr, *col_idx;
+  void *values;
+  void *ws;                // this tensor's workspace (compress_ws_bytes), may be null when none is needed
+};
+struct DecompressJob {
+  const int32_t *row_ptr, *col_idx;
+  const void *values;
+  int64_t M, K, ldx;
+  int br, bc;
+  void *X_out;
+};
+int launch_compress_batched(const CompressJob *jobs, int n, int dtype, hipStream_t s);
+int launch_decompress_batched(const DecompressJob *jobs, int n, int dtype, hipStream_t s);
+
 // dw_generic.hip: any block shape, binary32 FMA.
 size_t dw_generic_ws_bytes(int64_t M, int64_t K, int64_t N, int br, int bc);
 int launch_dw_generic(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int dtype,

@@ -6,6 +6,8 @@
 //   pack        : bit copy of the kept blocks into `values` (HBM-bound gather);
 //   decompress  : BSR -> dense, pruned positions become +0.0.
 // All three are pure data movement / integer work and are bit-exact.
+#include <vector>
+
 #include "common.h"
 
 namespace bsr {
@@ -174,17 +176,32 @@ __device__ __forceinline__ uint32_t count_kept_prefix(const uint8_t *__restrict_
 // the row's kept block-columns (row_ptr / col_idx and an LDS copy), then copies the
 // kept blocks.  Thread -> (row, vector) inside a block is fixed up front, so the
 // copy loops do no division.  Positions at or beyond n_keep are never written.
+// What one tensor's launch needs (kernel arguments; an array of these for several tensors per
+// launch).  kb, ldb, bcb: row length, row pitch and block row length in bytes.
+struct CompressArgs {
+  const uint8_t *mask, *X;
+  int32_t *row_ptr, *col_idx;
+  uint8_t *values;
+  int64_t M, kb, ldb, bcb, nbr, nbc, n_keep;
+  int br;
+  uint32_t wg_begin;       // first workgroup of this tensor in a launch of several
+};
+
+// i = block-row (the workgroup's number among those of its tensor)
 template <int VB>
-__global__ __launch_bounds__(256) void compress_kernel(
-    const uint8_t *__restrict__ mask, const uint8_t *__restrict__ X, int64_t M, int64_t kb, int64_t ldb,
-    int br, int64_t bcb, int64_t nbr, int64_t nbc, int64_t n_keep, int32_t *__restrict__ row_ptr,
-    int32_t *__restrict__ col_idx, uint8_t *__restrict__ values) {
+__device__ __forceinline__ void compress_body(const CompressArgs &a, const int64_t i) {
   typedef typename BytesOf<VB>::type V;
+  const uint8_t *__restrict__ mask = a.mask;
+  const uint8_t *__restrict__ X = a.X;
+  int32_t *__restrict__ row_ptr = a.row_ptr;
+  int32_t *__restrict__ col_idx = a.col_idx;
+  uint8_t *__restrict__ values = a.values;
+  const int64_t M = a.M, kb = a.kb, ldb = a.ldb, bcb = a.bcb, nbr = a.nbr, nbc = a.nbc, n_keep = a.n_keep;
+  const int br = a.br;
   __shared__ uint32_t wave_tot[4];
   __shared__ uint32_t total;
   __shared__ int32_t kept_j[kFusedCols];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int64_t i = blockIdx.x;
   const uint32_t prefix = count_kept_prefix(mask, i * nbc, wave_tot, &total);
 
   // ---- this row's kept block-columns, in order ----
@@ -242,6 +259,23 @@ __global__ __launch_bounds__(256) void compress_kernel(
   }
 }
 
+template <int VB>
+__global__ __launch_bounds__(256) void compress_kernel(CompressArgs a) {
+  compress_body<VB>(a, blockIdx.x);
+}
+
+// Several tensors per launch: tensor k owns the workgroups [wg_begin_k, wg_begin_{k+1}).
+constexpr int kPackBatchMax = 24;
+struct CompressBatch {
+  CompressArgs it[kPackBatchMax];
+};
+template <int VB>
+__global__ __launch_bounds__(256) void compress_batched_kernel(CompressBatch b, int n) {
+  int k = 0;
+  while (k + 1 < n && blockIdx.x >= b.it[k + 1].wg_begin) ++k;
+  compress_body<VB>(b.it[k], blockIdx.x - b.it[k].wg_begin);
+}
+
 constexpr int kMapCols = 1024;   // block-columns per workgroup in decompress
 
 // Scatter: a workgroup owns block-row i and a chunk of kMapCols block-columns;
@@ -249,21 +283,35 @@ constexpr int kMapCols = 1024;   // block-columns per workgroup in decompress
 // 64 lanes of a wave run along the matrix row (1 KB stores), the four waves take
 // every fourth row; a lane looks its vector's block up once and then walks down
 // the rows with all loads of a batch in flight: no division in the copy loop.
+struct DecompressArgs {
+  const int32_t *row_ptr, *col_idx;
+  const uint8_t *values;
+  uint8_t *X_out;
+  int64_t M, kb, ldb, bcb, nbr, nbc;
+  int br;
+  uint32_t gx, gy;         // the tensor's grid: chunks of block-columns x workgroups striding over block-rows
+  uint32_t wg_begin;       // first workgroup of this tensor in a launch of several
+};
+
+// bx, by: the workgroup's place in its tensor's gx x gy grid
 template <int VB>
-__global__ __launch_bounds__(256) void decompress_kernel(
-    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-    const uint8_t *__restrict__ values, int64_t M, int64_t kb, int64_t ldb, int br, int64_t bcb,
-    int64_t nbr, int64_t nbc, uint8_t *__restrict__ X_out) {
+__device__ __forceinline__ void decompress_body(const DecompressArgs &a, const uint32_t bx, const uint32_t by) {
   typedef typename BytesOf<VB>::type V;
+  const int32_t *__restrict__ row_ptr = a.row_ptr;
+  const int32_t *__restrict__ col_idx = a.col_idx;
+  const uint8_t *__restrict__ values = a.values;
+  uint8_t *__restrict__ X_out = a.X_out;
+  const int64_t M = a.M, kb = a.kb, ldb = a.ldb, bcb = a.bcb, nbr = a.nbr, nbc = a.nbc;
+  const int br = a.br;
   __shared__ int32_t slot[kMapCols];
   const int t = threadIdx.x, lane = t & 63, rg = t >> 6;
-  const int64_t j0 = (int64_t)blockIdx.x * kMapCols;
+  const int64_t j0 = (int64_t)bx * kMapCols;
   const int ncols = (int)((nbc - j0) < kMapCols ? (nbc - j0) : kMapCols);
   const int vpb = (int)(bcb / VB);
   const int vrow = ncols * vpb;                            // vectors per matrix row in the chunk
   const int64_t block_bytes = (int64_t)br * bcb;
   constexpr int kInFlight = 8;
-  for (int64_t i = blockIdx.y; i < nbr; i += gridDim.y) {
+  for (int64_t i = by; i < nbr; i += a.gy) {
     for (int c = t; c < ncols; c += 256) slot[c] = -1;
     __syncthreads();
     const int64_t p0 = row_ptr[i], p1 = row_ptr[i + 1];
@@ -297,6 +345,22 @@ __global__ __launch_bounds__(256) void decompress_kernel(
     }
     __syncthreads();
   }
+}
+
+template <int VB>
+__global__ __launch_bounds__(256) void decompress_kernel(DecompressArgs a) {
+  decompress_body<VB>(a, blockIdx.x, blockIdx.y);
+}
+
+struct DecompressBatch {
+  DecompressArgs it[kPackBatchMax];
+};
+template <int VB>
+__global__ __launch_bounds__(256) void decompress_batched_kernel(DecompressBatch b, int n) {
+  int k = 0;
+  while (k + 1 < n && blockIdx.x >= b.it[k + 1].wg_begin) ++k;
+  const uint32_t local = blockIdx.x - b.it[k].wg_begin;
+  decompress_body<VB>(b.it[k], local % b.it[k].gx, local / b.it[k].gx);
 }
 
 // ---- narrow blocks: whole block-rows staged in LDS ----
@@ -355,19 +419,37 @@ __global__ __launch_bounds__(256) void span_count_kernel(const uint8_t *__restri
   if (lane == 0) wg_kept[w] = cnt;
 }
 
+struct CompressSpanArgs {
+  const uint8_t *mask, *X;
+  const uint32_t *wg_kept;  // kept blocks of every workgroup's mask range, or null (see span_count_kernel)
+  int32_t *row_ptr, *col_idx;
+  uint32_t *values;
+  int64_t M, nbr, n_keep;
+  SpanGeom g;
+  uint32_t span_words;
+  uint32_t wg_begin;        // first workgroup of this tensor in a launch of several
+};
+
+// wg = the workgroup's number among those of its tensor
 template <int VB>
-__global__ __launch_bounds__(256) void compress_span_kernel(
-    const uint8_t *__restrict__ mask, const uint8_t *__restrict__ X, int64_t M, int64_t nbr, int64_t n_keep,
-    SpanGeom g, size_t span_words, const uint32_t *__restrict__ wg_kept, int32_t *__restrict__ row_ptr,
-    int32_t *__restrict__ col_idx, uint32_t *__restrict__ values) {
+__device__ __forceinline__ void compress_span_body(const CompressSpanArgs &a, const uint32_t wg) {
   typedef typename BytesOf<VB>::type V;
   constexpr int kVecs = kSpanBytes / VB / 256;
+  const uint8_t *__restrict__ mask = a.mask;
+  const uint8_t *__restrict__ X = a.X;
+  const uint32_t *__restrict__ wg_kept = a.wg_kept;
+  int32_t *__restrict__ row_ptr = a.row_ptr;
+  int32_t *__restrict__ col_idx = a.col_idx;
+  uint32_t *__restrict__ values = a.values;
+  const int64_t M = a.M, nbr = a.nbr, n_keep = a.n_keep;
+  const SpanGeom &g = a.g;
+  const size_t span_words = a.span_words;
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   uint32_t *span = lds, *base = lds + span_words, *lim = base + g.rb * g.nbc;
   __shared__ uint32_t wave_tot[4];
   __shared__ uint32_t total;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int64_t i0 = (int64_t)blockIdx.x * g.rb;
+  const int64_t i0 = (int64_t)wg * g.rb;
   const int nb = (int)((nbr - i0) < g.rb ? (nbr - i0) : g.rb);
   const int64_t m0 = i0 * g.br;
   const int rows = (int)((M - m0) < (int64_t)nb * g.br ? (M - m0) : (int64_t)nb * g.br);
@@ -387,7 +469,7 @@ __global__ __launch_bounds__(256) void compress_span_kernel(
     prefix = count_kept_prefix(mask, i0 * g.nbc, wave_tot, &total);
   } else {
     uint32_t cnt = 0;
-    for (uint32_t w = t; w < blockIdx.x; w += 256) cnt += wg_kept[w];
+    for (uint32_t w = t; w < wg; w += 256) cnt += wg_kept[w];
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d, 64);
     if (lane == 0) wave_tot[wave] = cnt;
@@ -433,18 +515,47 @@ __global__ __launch_bounds__(256) void compress_span_kernel(
 }
 
 template <int VB>
-__global__ __launch_bounds__(256) void decompress_span_kernel(
-    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-    const uint32_t *__restrict__ values, int64_t M, int64_t nbr, SpanGeom g, size_t span_words,
-    uint8_t *__restrict__ X_out) {
+__global__ __launch_bounds__(256) void compress_span_kernel(CompressSpanArgs a) {
+  compress_span_body<VB>(a, blockIdx.x);
+}
+
+struct CompressSpanBatch {
+  CompressSpanArgs it[kPackBatchMax];
+};
+template <int VB>
+__global__ __launch_bounds__(256) void compress_span_batched_kernel(CompressSpanBatch b, int n) {
+  int k = 0;
+  while (k + 1 < n && blockIdx.x >= b.it[k + 1].wg_begin) ++k;
+  compress_span_body<VB>(b.it[k], blockIdx.x - b.it[k].wg_begin);
+}
+
+struct DecompressSpanArgs {
+  const int32_t *row_ptr, *col_idx;
+  const uint32_t *values;
+  uint8_t *X_out;
+  int64_t M, nbr;
+  SpanGeom g;
+  uint32_t span_words;
+  uint32_t wg_begin;        // first workgroup of this tensor in a launch of several
+};
+
+template <int VB>
+__device__ __forceinline__ void decompress_span_body(const DecompressSpanArgs &a, const uint32_t wg) {
   typedef typename BytesOf<VB>::type V;
   constexpr int kVecs = kSpanBytes / VB / 256;
   constexpr int kWords = kSpanBytes / 4 / 256;
+  const int32_t *__restrict__ row_ptr = a.row_ptr;
+  const int32_t *__restrict__ col_idx = a.col_idx;
+  const uint32_t *__restrict__ values = a.values;
+  uint8_t *__restrict__ X_out = a.X_out;
+  const int64_t M = a.M, nbr = a.nbr;
+  const SpanGeom &g = a.g;
+  const size_t span_words = a.span_words;
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   uint32_t *span = lds, *base = lds + span_words, *lim = base + g.rb * g.nbc;
   __shared__ int32_t rp[kSpanRows + 2];
   const int t = threadIdx.x;
-  const int64_t i0 = (int64_t)blockIdx.x * g.rb;
+  const int64_t i0 = (int64_t)wg * g.rb;
   const int nb = (int)((nbr - i0) < g.rb ? (nbr - i0) : g.rb);
   const int64_t m0 = i0 * g.br;
   const int rows = (int)((M - m0) < (int64_t)nb * g.br ? (M - m0) : (int64_t)nb * g.br);
@@ -492,6 +603,21 @@ __global__ __launch_bounds__(256) void decompress_span_kernel(
 #pragma unroll
   for (int k = 0; k < kVecs; ++k)
     if (t + 256 * k < nvec) dst[t + 256 * k] = sv[t + 256 * k];
+}
+
+template <int VB>
+__global__ __launch_bounds__(256) void decompress_span_kernel(DecompressSpanArgs a) {
+  decompress_span_body<VB>(a, blockIdx.x);
+}
+
+struct DecompressSpanBatch {
+  DecompressSpanArgs it[kPackBatchMax];
+};
+template <int VB>
+__global__ __launch_bounds__(256) void decompress_span_batched_kernel(DecompressSpanBatch b, int n) {
+  int k = 0;
+  while (k + 1 < n && blockIdx.x >= b.it[k + 1].wg_begin) ++k;
+  decompress_span_body<VB>(b.it[k], blockIdx.x - b.it[k].wg_begin);
 }
 
 // Widest byte vector that divides every extent and alignment involved.
@@ -587,33 +713,109 @@ size_t compress_ws_bytes(int dtype, int64_t M, int64_t K, int br, int bc) {
   return align_up((size_t)wgs * sizeof(uint32_t), 256);
 }
 
+namespace {
+
+// How one tensor is converted: the kernel family, its vector width and its arguments.
+enum { kPackSpan = 0, kPackDirect = 1, kPackOther = 2 };
+struct CompressPlan {
+  int path, vb;
+  bool count_first;          // span path: a first launch counts every workgroup's kept blocks
+  unsigned wgs;
+  size_t lds;
+  CompressArgs direct;
+  CompressSpanArgs span;
+};
+
+CompressPlan plan_compress(const CompressJob &j, int dtype) {
+  CompressPlan p{};
+  const int64_t nbr = ceil_div(j.M, j.br), nbc = ceil_div(j.K, j.bc);
+  const int e = elem_bytes(dtype);
+  SpanGeom g;
+  if (nbr > 0 && nbc > 0 && (uintptr_t)j.values % 4 == 0 &&
+      span_geometry(dtype, j.M, j.K, j.ldx, j.br, j.bc, j.X, nullptr, &g)) {
+    p.path = kPackSpan;
+    p.vb = g.vb;
+    const size_t span_words = span_lds_words(g);
+    p.lds = (span_words + 2 * (size_t)g.rb * g.nbc) * 4;
+    p.wgs = (unsigned)ceil_div(nbr, g.rb);
+    // one launch if re-counting the mask prefix in every workgroup stays cheap (bytes out of
+    // L2); else a first launch counts every workgroup's kept blocks into the workspace
+    p.count_first = compress_ws_bytes(dtype, j.M, j.K, j.br, j.bc) != 0;
+    p.span = CompressSpanArgs{j.keep_mask, static_cast<const uint8_t *>(j.X),
+                              p.count_first ? static_cast<const uint32_t *>(j.ws) : nullptr, j.row_ptr, j.col_idx,
+                              static_cast<uint32_t *>(j.values), j.M, nbr, j.n_keep, g, (uint32_t)span_words, 0u};
+    return p;
+  }
+  // one fused launch when a block-row's columns fit its LDS list and re-reading the
+  // mask prefix in every workgroup stays cheap (nbr * nblocks / 2 bytes out of L2)
+  const bool fused = nbr > 0 && nbc > 0 && nbc <= kFusedCols && nbr <= 65535 &&
+                     nbr * nbr * nbc <= (int64_t(1) << 31);
+  if (!fused) {
+    p.path = kPackOther;
+    return p;
+  }
+  p.path = kPackDirect;
+  p.vb = pick_bytes(e, j.bc, j.K, j.ldx, j.X, j.values);
+  p.wgs = (unsigned)nbr;
+  p.direct = CompressArgs{j.keep_mask, static_cast<const uint8_t *>(j.X), j.row_ptr, j.col_idx,
+                          static_cast<uint8_t *>(j.values), j.M, j.K * e, j.ldx * e, (int64_t)j.bc * e, nbr, nbc,
+                          j.n_keep, j.br, 0u};
+  return p;
+}
+
+struct DecompressPlan {
+  int path, vb;
+  unsigned wgs;
+  size_t lds;
+  DecompressArgs direct;
+  DecompressSpanArgs span;
+};
+
+DecompressPlan plan_decompress(const DecompressJob &j, int dtype) {
+  DecompressPlan p{};
+  const int e = elem_bytes(dtype);
+  const int64_t nbr = ceil_div(j.M, j.br), nbc = ceil_div(j.K, j.bc);
+  SpanGeom g;
+  if ((uintptr_t)j.values % 4 == 0 && span_geometry(dtype, j.M, j.K, j.ldx, j.br, j.bc, j.X_out, nullptr, &g)) {
+    p.path = kPackSpan;
+    p.vb = g.vb;
+    const size_t span_words = span_lds_words(g);
+    p.lds = (span_words + 2 * (size_t)g.rb * g.nbc) * 4;
+    p.wgs = (unsigned)ceil_div(nbr, g.rb);
+    p.span = DecompressSpanArgs{j.row_ptr, j.col_idx, static_cast<const uint32_t *>(j.values),
+                                static_cast<uint8_t *>(j.X_out), j.M, nbr, g, (uint32_t)span_words, 0u};
+    return p;
+  }
+  p.path = kPackDirect;
+  p.vb = pick_bytes(e, j.bc, j.K, j.ldx, j.X_out, j.values);
+  const unsigned gx = (unsigned)ceil_div(nbc, kMapCols);
+  int64_t gy = nbr;
+  if (gy > 16384) gy = 16384;
+  p.wgs = gx * (unsigned)gy;
+  p.direct = DecompressArgs{j.row_ptr, j.col_idx, static_cast<const uint8_t *>(j.values),
+                            static_cast<uint8_t *>(j.X_out), j.M, j.K * e, j.ldx * e, (int64_t)j.bc * e, nbr, nbc,
+                            j.br, gx, (uint32_t)gy, 0u};
+  return p;
+}
+
+}  // namespace
+
 int launch_compress(const uint8_t *keep_mask, const void *X, int dtype, int64_t M, int64_t K, int64_t ldx,
                     int br, int bc, int64_t n_keep, int32_t *row_ptr, int32_t *col_idx, void *values,
                     void *ws, hipStream_t s) {
-  const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
-  const int e = elem_bytes(dtype);
-  const uint8_t *x = static_cast<const uint8_t *>(X);
-  uint8_t *v = static_cast<uint8_t *>(values);
-  SpanGeom g;
-  if (nbr > 0 && nbc > 0 && (uintptr_t)values % 4 == 0 && span_geometry(dtype, M, K, ldx, br, bc, X, nullptr, &g)) {
-    const size_t span_words = span_lds_words(g);
-    const size_t lds = (span_words + 2 * (size_t)g.rb * g.nbc) * 4;
-    const int64_t wgs = ceil_div(nbr, g.rb);
-    const dim3 grid((unsigned)wgs);
-    // one launch if re-counting the mask prefix in every workgroup stays cheap (bytes out of
-    // L2); else a first launch counts every workgroup's kept blocks into the workspace
-    uint32_t *wg_kept = nullptr;
-    if (compress_ws_bytes(dtype, M, K, br, bc) != 0) {
-      wg_kept = static_cast<uint32_t *>(ws);
-      hipLaunchKernelGGL(span_count_kernel, dim3((unsigned)ceil_div(wgs, 4)), dim3(256), 0, s, keep_mask,
-                         nbr * nbc, g.rb * g.nbc, wgs, wg_kept);
+  const CompressJob job{keep_mask, X, M, K, ldx, br, bc, n_keep, row_ptr, col_idx, values, ws};
+  const CompressPlan p = plan_compress(job, dtype);
+  if (p.path == kPackSpan) {
+    if (p.count_first) {
+      const SpanGeom &g = p.span.g;
+      hipLaunchKernelGGL(span_count_kernel, dim3((unsigned)ceil_div((int64_t)p.wgs, 4)), dim3(256), 0, s, keep_mask,
+                         p.span.nbr * g.nbc, g.rb * g.nbc, (int64_t)p.wgs, static_cast<uint32_t *>(ws));
       const int rc = check_launch();
       if (rc != BSR_OK) return rc;
     }
-#define BSR_COMPRESS_SPAN(VB)                                                                              \
-  hipLaunchKernelGGL((compress_span_kernel<VB>), grid, dim3(256), lds, s, keep_mask, x, M, nbr, n_keep, g, \
-                     span_words, wg_kept, row_ptr, col_idx, reinterpret_cast<uint32_t *>(v))
-    switch (g.vb) {
+#define BSR_COMPRESS_SPAN(VB) \
+  hipLaunchKernelGGL((compress_span_kernel<VB>), dim3(p.wgs), dim3(256), p.lds, s, p.span)
+    switch (p.vb) {
       case 16: BSR_COMPRESS_SPAN(16); break;
       case 8: BSR_COMPRESS_SPAN(8); break;
       default: BSR_COMPRESS_SPAN(4); break;
@@ -621,20 +823,14 @@ int launch_compress(const uint8_t *keep_mask, const void *X, int dtype, int64_t 
 #undef BSR_COMPRESS_SPAN
     return check_launch();
   }
-  // one fused launch when a block-row's columns fit its LDS list and re-reading the
-  // mask prefix in every workgroup stays cheap (nbr * nblocks / 2 bytes out of L2)
-  const bool fused = nbr > 0 && nbc > 0 && nbc <= kFusedCols && nbr <= 65535 &&
-                     nbr * nbr * nbc <= (int64_t(1) << 31);
-  if (!fused) {
+  if (p.path == kPackOther) {
+    const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
     int rc = launch_index_build(keep_mask, nbr, nbc, n_keep, row_ptr, col_idx, s);
     if (rc != BSR_OK) return rc;
     return launch_pack(X, dtype, M, K, ldx, br, bc, row_ptr, col_idx, n_keep, values, s);
   }
-  const int vb = pick_bytes(e, bc, K, ldx, X, values);
-#define BSR_COMPRESS(VB)                                                                            \
-  hipLaunchKernelGGL((compress_kernel<VB>), dim3((unsigned)nbr), dim3(256), 0, s, keep_mask, x, M,  \
-                     K * e, ldx * e, br, (int64_t)bc * e, nbr, nbc, n_keep, row_ptr, col_idx, v)
-  switch (vb) {
+#define BSR_COMPRESS(VB) hipLaunchKernelGGL((compress_kernel<VB>), dim3(p.wgs), dim3(256), 0, s, p.direct)
+  switch (p.vb) {
     case 16: BSR_COMPRESS(16); break;
     case 8: BSR_COMPRESS(8); break;
     case 4: BSR_COMPRESS(4); break;
@@ -647,18 +843,12 @@ int launch_compress(const uint8_t *keep_mask, const void *X, int dtype, int64_t 
 int launch_decompress(const int32_t *row_ptr, const int32_t *col_idx, const void *values, int dtype,
                       int64_t M, int64_t K, int64_t ldx, int br, int bc, void *X_out, hipStream_t s) {
   if (M == 0 || K == 0) return BSR_OK;
-  const int e = elem_bytes(dtype);
-  const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
-  SpanGeom g;
-  if ((uintptr_t)values % 4 == 0 && span_geometry(dtype, M, K, ldx, br, bc, X_out, nullptr, &g)) {
-    const size_t span_words = span_lds_words(g);
-    const size_t lds = (span_words + 2 * (size_t)g.rb * g.nbc) * 4;
-    const dim3 grid((unsigned)ceil_div(nbr, g.rb));
-#define BSR_UNPACK_SPAN(VB)                                                                        \
-  hipLaunchKernelGGL((decompress_span_kernel<VB>), grid, dim3(256), lds, s, row_ptr, col_idx,      \
-                     static_cast<const uint32_t *>(values), M, nbr, g, span_words,                \
-                     static_cast<uint8_t *>(X_out))
-    switch (g.vb) {
+  const DecompressJob job{row_ptr, col_idx, values, M, K, ldx, br, bc, X_out};
+  const DecompressPlan p = plan_decompress(job, dtype);
+  if (p.path == kPackSpan) {
+#define BSR_UNPACK_SPAN(VB) \
+  hipLaunchKernelGGL((decompress_span_kernel<VB>), dim3(p.wgs), dim3(256), p.lds, s, p.span)
+    switch (p.vb) {
       case 16: BSR_UNPACK_SPAN(16); break;
       case 8: BSR_UNPACK_SPAN(8); break;
       default: BSR_UNPACK_SPAN(4); break;
@@ -666,16 +856,9 @@ int launch_decompress(const int32_t *row_ptr, const int32_t *col_idx, const void
 #undef BSR_UNPACK_SPAN
     return check_launch();
   }
-  const int vb = pick_bytes(e, bc, K, ldx, X_out, values);
-  const unsigned gx = (unsigned)ceil_div(nbc, kMapCols);
-  int64_t gy = nbr;
-  if (gy > 16384) gy = 16384;
-  const uint8_t *v = static_cast<const uint8_t *>(values);
-  uint8_t *x = static_cast<uint8_t *>(X_out);
-#define BSR_UNPACK(VB)                                                                          \
-  hipLaunchKernelGGL((decompress_kernel<VB>), dim3(gx, (unsigned)gy), dim3(256), 0, s, row_ptr, \
-                     col_idx, v, M, K * e, ldx * e, br, (int64_t)bc * e, nbr, nbc, x)
-  switch (vb) {
+#define BSR_UNPACK(VB) \
+  hipLaunchKernelGGL((decompress_kernel<VB>), dim3(p.direct.gx, p.direct.gy), dim3(256), 0, s, p.direct)
+  switch (p.vb) {
     case 16: BSR_UNPACK(16); break;
     case 8: BSR_UNPACK(8); break;
     case 4: BSR_UNPACK(4); break;
@@ -683,6 +866,133 @@ int launch_decompress(const int32_t *row_ptr, const int32_t *col_idx, const void
   }
 #undef BSR_UNPACK
   return check_launch();
+}
+
+// Several tensors per call: the tensors that take the same kernel (family and vector width) share
+// launches, kPackBatchMax per launch; a tensor that needs more than one launch of its own (counting
+// pass, separate index build) goes through the single-tensor path.  The results are those of the
+// single-tensor calls (bit copies either way).
+int launch_compress_batched(const CompressJob *jobs, int n, int dtype, hipStream_t s) {
+  static const int kVbs[4] = {16, 8, 4, 2};
+  std::vector<CompressPlan> plans((size_t)n);
+  for (int i = 0; i < n; ++i) plans[(size_t)i] = plan_compress(jobs[i], dtype);
+  for (int path = kPackSpan; path <= kPackDirect; ++path) {
+    for (int vi = 0; vi < 4; ++vi) {
+      const int vb = kVbs[vi];
+      CompressBatch db;
+      CompressSpanBatch sb;
+      int m = 0;
+      uint32_t total = 0;
+      size_t lds = 0;
+      auto flush = [&]() -> int {
+        if (m == 0) return BSR_OK;
+        if (path == kPackSpan) {
+          switch (vb) {
+            case 16: hipLaunchKernelGGL((compress_span_batched_kernel<16>), dim3(total), dim3(256), lds, s, sb, m); break;
+            case 8: hipLaunchKernelGGL((compress_span_batched_kernel<8>), dim3(total), dim3(256), lds, s, sb, m); break;
+            default: hipLaunchKernelGGL((compress_span_batched_kernel<4>), dim3(total), dim3(256), lds, s, sb, m); break;
+          }
+        } else {
+          switch (vb) {
+            case 16: hipLaunchKernelGGL((compress_batched_kernel<16>), dim3(total), dim3(256), 0, s, db, m); break;
+            case 8: hipLaunchKernelGGL((compress_batched_kernel<8>), dim3(total), dim3(256), 0, s, db, m); break;
+            case 4: hipLaunchKernelGGL((compress_batched_kernel<4>), dim3(total), dim3(256), 0, s, db, m); break;
+            default: hipLaunchKernelGGL((compress_batched_kernel<2>), dim3(total), dim3(256), 0, s, db, m); break;
+          }
+        }
+        m = 0;
+        total = 0;
+        lds = 0;
+        return check_launch();
+      };
+      for (int i = 0; i < n; ++i) {
+        const CompressPlan &p = plans[(size_t)i];
+        if (p.path != path || p.vb != vb || p.count_first || p.wgs == 0) continue;
+        if (path == kPackSpan) {
+          sb.it[m] = p.span;
+          sb.it[m].wg_begin = total;
+          if (p.lds > lds) lds = p.lds;
+        } else {
+          db.it[m] = p.direct;
+          db.it[m].wg_begin = total;
+        }
+        total += p.wgs;
+        if (++m == kPackBatchMax) {
+          const int rc = flush();
+          if (rc != BSR_OK) return rc;
+        }
+      }
+      const int rc = flush();
+      if (rc != BSR_OK) return rc;
+    }
+  }
+  for (int i = 0; i < n; ++i) {
+    const CompressPlan &p = plans[(size_t)i];
+    const CompressJob &j = jobs[i];
+    if (p.path == kPackOther || (p.path == kPackSpan && p.count_first)) {
+      const int rc = launch_compress(j.keep_mask, j.X, dtype, j.M, j.K, j.ldx, j.br, j.bc, j.n_keep, j.row_ptr,
+                                     j.col_idx, j.values, j.ws, s);
+      if (rc != BSR_OK) return rc;
+    }
+  }
+  return BSR_OK;
+}
+
+int launch_decompress_batched(const DecompressJob *jobs, int n, int dtype, hipStream_t s) {
+  static const int kVbs[4] = {16, 8, 4, 2};
+  std::vector<DecompressPlan> plans((size_t)n);
+  for (int i = 0; i < n; ++i) plans[(size_t)i] = plan_decompress(jobs[i], dtype);
+  for (int path = kPackSpan; path <= kPackDirect; ++path) {
+    for (int vi = 0; vi < 4; ++vi) {
+      const int vb = kVbs[vi];
+      DecompressBatch db;
+      DecompressSpanBatch sb;
+      int m = 0;
+      uint32_t total = 0;
+      size_t lds = 0;
+      auto flush = [&]() -> int {
+        if (m == 0) return BSR_OK;
+        if (path == kPackSpan) {
+          switch (vb) {
+            case 16: hipLaunchKernelGGL((decompress_span_batched_kernel<16>), dim3(total), dim3(256), lds, s, sb, m); break;
+            case 8: hipLaunchKernelGGL((decompress_span_batched_kernel<8>), dim3(total), dim3(256), lds, s, sb, m); break;
+            default: hipLaunchKernelGGL((decompress_span_batched_kernel<4>), dim3(total), dim3(256), lds, s, sb, m); break;
+          }
+        } else {
+          switch (vb) {
+            case 16: hipLaunchKernelGGL((decompress_batched_kernel<16>), dim3(total), dim3(256), 0, s, db, m); break;
+            case 8: hipLaunchKernelGGL((decompress_batched_kernel<8>), dim3(total), dim3(256), 0, s, db, m); break;
+            case 4: hipLaunchKernelGGL((decompress_batched_kernel<4>), dim3(total), dim3(256), 0, s, db, m); break;
+            default: hipLaunchKernelGGL((decompress_batched_kernel<2>), dim3(total), dim3(256), 0, s, db, m); break;
+          }
+        }
+        m = 0;
+        total = 0;
+        lds = 0;
+        return check_launch();
+      };
+      for (int i = 0; i < n; ++i) {
+        const DecompressPlan &p = plans[(size_t)i];
+        if (jobs[i].M == 0 || jobs[i].K == 0 || p.path != path || p.vb != vb || p.wgs == 0) continue;
+        if (path == kPackSpan) {
+          sb.it[m] = p.span;
+          sb.it[m].wg_begin = total;
+          if (p.lds > lds) lds = p.lds;
+        } else {
+          db.it[m] = p.direct;
+          db.it[m].wg_begin = total;
+        }
+        total += p.wgs;
+        if (++m == kPackBatchMax) {
+          const int rc = flush();
+          if (rc != BSR_OK) return rc;
+        }
+      }
+      const int rc = flush();
+      if (rc != BSR_OK) return rc;
+    }
+  }
+  return BSR_OK;
 }
 
 }  // namespace bsr

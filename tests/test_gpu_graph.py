@@ -149,3 +149,48 @@ def test_batched_dw_replays_match_eager():
         torch.cuda.synchronize()
         for o, w in zip(batch.dWs, want):
             assert o.cpu().numpy().tobytes() == w.tobytes(), f"replay {rep}"
+
+
+def test_batched_compress_and_decompress_replays_match_eager():
+    specs = [synth.TensorSpec("g_fc1", 3136, 384, 1, 32, 32, "bf16", keep=0.5),
+             synth.TensorSpec("g_fc2", 3136, 1536, 1, 32, 32, "bf16", keep=0.5),
+             synth.TensorSpec("g_patch", 5488, 196, 1, 14, 14, "bf16", keep=0.5)]
+    problems = []
+    for i, sp in enumerate(specs):
+        X, _ = synth.make_pair(sp, 41 + i)
+        Xd = to_dev(X)
+        mask = B.bsr_score_select(Xd, sp.br, sp.bc, sp.keep)
+        problems.append((Xd, sp.br, sp.bc, mask, B.bsr_keep_count(sp.nblocks, sp.keep)))
+    cb = B.CompressBatch(problems)
+    cws = torch.empty(cb.ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    B.bsr_compress_batched(cb, ws=cws)
+    db = B.DecompressBatch([(rp, ci, val, sp.M, sp.K, sp.br, sp.bc) for (rp, ci, val), sp in zip(cb.outputs, specs)])
+    B.bsr_decompress_batched(db)
+    torch.cuda.synchronize()
+    want = [[t.view(torch.uint8).cpu().numpy().copy() for t in trio] for trio in cb.outputs]
+    want_dense = [o.view(torch.uint8).cpu().numpy().copy() for o in db.outputs]
+    for pr, trio, sp, dense in zip(problems, want, specs, want_dense):
+        single = B.bsr_compress(*pr)
+        back = B.bsr_decompress(*single, sp.M, sp.K, sp.br, sp.bc)
+        torch.cuda.synchronize()
+        for a, w in zip(single, trio):
+            assert a.view(torch.uint8).cpu().numpy().tobytes() == w.tobytes()
+        assert back.view(torch.uint8).cpu().numpy().tobytes() == dense.tobytes()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.bsr_compress_batched(cb, ws=cws)
+        B.bsr_decompress_batched(db)
+    for rep in range(3):
+        for trio in cb.outputs:
+            for t in trio:
+                t.view(torch.uint8).fill_(0x77)
+        for o in db.outputs:
+            o.view(torch.uint8).fill_(0x77)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for trio, w3 in zip(cb.outputs, want):
+            for t, w in zip(trio, w3):
+                assert t.view(torch.uint8).cpu().numpy().tobytes() == w.tobytes(), f"replay {rep}"
+        for o, w in zip(db.outputs, want_dense):
+            assert o.view(torch.uint8).cpu().numpy().tobytes() == w.tobytes(), f"replay {rep}"

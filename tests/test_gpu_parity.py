@@ -585,3 +585,94 @@ def test_batched_dw_more_items_than_one_launch_holds():
         if i % 9 == 0:
             ref = xhat.T @ synth.to_f64(to_host(dY))
             assert dw_error(first[i], ref) <= DW_TOL_DERIVED, f"item {i}"
+
+
+PACK_BATCH = [
+    # M, K, br, bc, keep
+    (2048, 384, 32, 32, 0.5),           # direct kernels, 16-byte vectors
+    (2048, 1536, 32, 32, 0.5),
+    (1000, 200, 16, 16, 0.25),          # ragged rows and columns
+    (777, 196, 14, 14, 0.5),            # narrow blocks: LDS-staged kernels
+    (1568, 196, 14, 14, 0.5),
+    (300, 384, 1, 8, 0.5),              # row segments: LDS-staged kernels
+    (64, 20000, 1, 4, 0.3),             # more block-columns than a block-row list holds: index build + pack
+    (20000, 384, 1, 4, 0.5),            # LDS-staged with a counting pass first (needs its workspace)
+    (512, 128, 32, 32, 0.0),            # nothing kept
+    (512, 128, 32, 32, 1.0),            # everything kept
+    (0, 64, 16, 16, 0.5),               # no rows
+    (100, 70, 7, 5, 0.6),               # odd sizes: 2-byte / 4-byte vectors
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_batched_compress_and_decompress_equal_single_calls(dtype):
+    problems, singles, masks, Xs = [], [], [], []
+    for i, (M, K, br, bc, keep) in enumerate(PACK_BATCH):
+        if M > 0:
+            X, _ = rand_pair(M, K, 1, dtype, seed=500 + i)
+            Xd = to_dev(X)
+        else:
+            X = np.zeros((0, K), dtype=np.uint16 if dtype == "bf16" else np.float32)
+            Xd = torch.empty((0, K), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device="cuda")
+        nbr, nbc = oracle.grid(M, K, br, bc)
+        n_keep = B.bsr_keep_count(nbr * nbc, keep)
+        mask = B.bsr_score_select(Xd, br, bc, keep) if M > 0 else torch.empty(0, dtype=torch.uint8, device="cuda")
+        singles.append(B.bsr_compress(Xd, br, bc, mask, n_keep))
+        problems.append((Xd, br, bc, mask, n_keep))
+        masks.append(mask)
+        Xs.append(X)
+    batch = B.CompressBatch(problems)
+    assert batch.ws_bytes > 0                                   # the counting-pass item
+    for rp, ci, val in batch.outputs:                           # stale contents must be overwritten
+        rp.fill_(-7)
+        ci.fill_(-7)
+        val.view(torch.uint8).fill_(0xA5)
+    outs = B.bsr_compress_batched(batch)
+    torch.cuda.synchronize()
+    for i, ((rp, ci, val), (srp, sci, sval)) in enumerate(zip(outs, singles)):
+        assert np.array_equal(rp.cpu().numpy(), srp.cpu().numpy()), f"item {i} row_ptr"
+        assert np.array_equal(ci.cpu().numpy(), sci.cpu().numpy()), f"item {i} col_idx"
+        assert to_host(val).tobytes() == to_host(sval).tobytes(), f"item {i} values"
+    # ... and against the oracle for the items it finishes quickly
+    for i in (0, 2, 3, 5, 11):
+        M, K, br, bc, keep = PACK_BATCH[i]
+        o_rp, o_ci, o_val = oracle.bsr_from_mask(Xs[i], br, bc, masks[i].cpu().numpy())
+        assert np.array_equal(outs[i][0].cpu().numpy(), o_rp) and np.array_equal(outs[i][1].cpu().numpy(), o_ci)
+        assert to_host(outs[i][2]).tobytes() == o_val.tobytes(), f"item {i}"
+    dbatch = B.DecompressBatch([(rp, ci, val, M, K, br, bc) for (rp, ci, val), (M, K, br, bc, _) in
+                                zip(outs, PACK_BATCH)])
+    for o in dbatch.outputs:
+        if o.numel():
+            o.view(torch.uint8).fill_(0x5A)
+    backs = B.bsr_decompress_batched(dbatch)
+    torch.cuda.synchronize()
+    for i, (back, (M, K, br, bc, _)) in enumerate(zip(backs, PACK_BATCH)):
+        single = B.bsr_decompress(*outs[i], M, K, br, bc)
+        torch.cuda.synchronize()
+        assert to_host(back).tobytes() == to_host(single).tobytes(), f"item {i}"
+        if M > 0 and M * K <= 1 << 21:
+            assert to_host(back).tobytes() == oracle.mask_dense(Xs[i], br, bc, masks[i].cpu().numpy()).tobytes()
+
+
+def test_batched_compress_more_items_than_one_launch_holds():
+    rng = np.random.default_rng(9)
+    problems, Xs = [], []
+    for i in range(53):
+        M, K = 96 + 32 * (i % 5), 128
+        br, bc = (32, 32) if i % 2 == 0 else (14, 14)
+        X = synth.f32_to_bf16_bits(rng.standard_normal((M, K), dtype=np.float32))
+        Xd = to_dev(X)
+        nbr, nbc = oracle.grid(M, K, br, bc)
+        mask = B.bsr_score_select(Xd, br, bc, 0.5)
+        problems.append((Xd, br, bc, mask, B.bsr_keep_count(nbr * nbc, 0.5)))
+        Xs.append(X)
+    outs = B.bsr_compress_batched(B.CompressBatch(problems))
+    backs = B.bsr_decompress_batched(B.DecompressBatch(
+        [(rp, ci, val, pr[0].shape[0], 128, pr[1], pr[2]) for (rp, ci, val), pr in zip(outs, problems)]))
+    torch.cuda.synchronize()
+    for i, (pr, (rp, ci, val), back) in enumerate(zip(problems, outs, backs)):
+        m = pr[3].cpu().numpy()
+        o_rp, o_ci, o_val = oracle.bsr_from_mask(Xs[i], pr[1], pr[2], m)
+        assert np.array_equal(rp.cpu().numpy(), o_rp) and np.array_equal(ci.cpu().numpy(), o_ci), f"item {i}"
+        assert to_host(val).tobytes() == o_val.tobytes(), f"item {i}"
+        assert to_host(back).tobytes() == oracle.mask_dense(Xs[i], pr[1], pr[2], m).tobytes(), f"item {i}"

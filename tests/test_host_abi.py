@@ -23,7 +23,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     syms = declared_symbols()
-    assert set(syms) == set(B.EXPORTS) and len(syms) == 17
+    assert set(syms) == set(B.EXPORTS) and len(syms) == 20
     lib = B.lib()
     for s in syms:
         assert getattr(lib, s) is not None
@@ -212,6 +212,49 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert bm(big, ws=None) == B.BSR_ERR_WORKSPACE
     assert bm(big, ws_bytes=need - 1) == B.BSR_ERR_WORKSPACE
     assert lib.bsr_t_dense_matmul_batched_workspace_bytes(mm_items(br=0), 2, 1) == 0
+    def cp_items(**k):
+        arr = (B._CompressItem * 2)()
+        arr[0] = B._CompressItem(0x1000, 64, 64, 64, 16, 16, 0x1000, 8, 0x1000, 0x1000, 0x1000)
+        arr[1] = B._CompressItem(k.get("X", 0x1000), k.get("M", 128), k.get("K", 64), k.get("ldx", 64), k.get("br", 16),
+                                 k.get("bc", 16), k.get("mask", 0x1000), k.get("n_keep", 16), k.get("row_ptr", 0x1000),
+                                 k.get("col_idx", 0x1000), k.get("values", 0x1000))
+        return arr
+    bc_ = lambda arr, n=2, dtype=1, ws=None, ws_bytes=0: lib.bsr_compress_batched(arr, n, dtype, ws, ws_bytes, None)
+    assert bc_(cp_items(), n=-1) == B.BSR_ERR_SHAPE
+    assert bc_(None) == B.BSR_ERR_NULL
+    assert bc_(cp_items(), n=0) == B.BSR_OK
+    assert bc_(cp_items(), dtype=5) == B.BSR_ERR_DTYPE
+    assert bc_(cp_items(br=0)) == B.BSR_ERR_SHAPE
+    assert bc_(cp_items(ldx=8)) == B.BSR_ERR_SHAPE
+    assert bc_(cp_items(n_keep=33)) == B.BSR_ERR_KEEP
+    assert bc_(cp_items(X=None)) == B.BSR_ERR_NULL
+    assert bc_(cp_items(mask=None)) == B.BSR_ERR_NULL
+    assert bc_(cp_items(row_ptr=None)) == B.BSR_ERR_NULL
+    assert bc_(cp_items(values=None)) == B.BSR_ERR_NULL
+    assert bc_(cp_items(col_idx=0x1002)) == B.BSR_ERR_ALIGN
+    assert lib.bsr_compress_batched_workspace_bytes(cp_items(), 2, 1) == 0
+    tall = cp_items(M=1 << 21, K=8, ldx=8, br=1, bc=4, n_keep=100)          # per-workgroup counts in the workspace
+    need = lib.bsr_compress_batched_workspace_bytes(tall, 2, 1)
+    assert need == -(-B.bsr_workspace_bytes(B.BSR_OP_COMPRESS, 1 << 21, 8, 0, 1, 4, 1) // 256) * 256 > 0
+    assert bc_(tall) == B.BSR_ERR_WORKSPACE
+    assert bc_(tall, ws=fake, ws_bytes=need - 1) == B.BSR_ERR_WORKSPACE
+    assert lib.bsr_compress_batched_workspace_bytes(cp_items(br=0), 2, 1) == 0
+    def dc_items(**k):
+        arr = (B._DecompressItem * 2)()
+        arr[0] = B._DecompressItem(0x1000, 0x1000, 0x1000, 64, 64, 64, 16, 16, 0x1000)
+        arr[1] = B._DecompressItem(k.get("row_ptr", 0x1000), 0x1000, k.get("values", 0x1000), 128, 64, k.get("ldx", 64),
+                                   k.get("br", 16), 16, k.get("out", 0x1000))
+        return arr
+    bd = lambda arr, n=2, dtype=1: lib.bsr_decompress_batched(arr, n, dtype, None)
+    assert bd(dc_items(), n=-1) == B.BSR_ERR_SHAPE
+    assert bd(None) == B.BSR_ERR_NULL
+    assert bd(dc_items(), n=0) == B.BSR_OK
+    assert bd(dc_items(), dtype=7) == B.BSR_ERR_DTYPE
+    assert bd(dc_items(br=-1)) == B.BSR_ERR_SHAPE
+    assert bd(dc_items(ldx=63)) == B.BSR_ERR_SHAPE
+    assert bd(dc_items(row_ptr=None)) == B.BSR_ERR_NULL
+    assert bd(dc_items(out=None)) == B.BSR_ERR_NULL
+    assert bd(dc_items(out=0x1001)) == B.BSR_ERR_ALIGN
     assert B.lib().bsr_error_string(B.BSR_ERR_WORKSPACE) == b"BSR_ERR_WORKSPACE"
 
 
