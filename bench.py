@@ -54,6 +54,9 @@ def parse():
     p.add_argument("--dw", choices=("batched", "single"), default="batched",
                    help="batched: one bsr_t_dense_matmul_batched call for all tensors of the step after their BSR "
                         "forms exist; single: one bsr_t_dense_matmul call per tensor on its stream")
+    p.add_argument("--pack", choices=("batched", "single"), default="batched",
+                   help="batched: one bsr_compress_batched and one bsr_decompress_batched call for all tensors of the "
+                        "step; single: one bsr_compress and one bsr_decompress call per tensor on its stream")
     p.add_argument("--no-next-rows", action="store_true",
                    help="skip the measurements outside the timed step (per-sample ranking, row segments), "
                         "so that a profile of the run holds the step's kernels only")
@@ -107,14 +110,11 @@ def main():
             ws=torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev),
         ))
         del X, dY
-    # one dense output buffer per tensor shape for the decompress row
-    outs = {}
+    # every tensor has its own dense output for the decompress row (a buffer shared by the tensors of one
+    # shape would be rewritten while still in the memory-side cache, and its writes would never reach HBM)
     for t in tensors:
         s = t["spec"]
-        key = (s.M, s.K)
-        if key not in outs:
-            outs[key] = torch.empty((s.M, s.K), dtype=t["X"].dtype, device=dev)
-        t["Xhat"] = outs[key]
+        t["Xhat"] = torch.empty((s.M, s.K), dtype=t["X"].dtype, device=dev)
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
 
@@ -139,7 +139,16 @@ def main():
     phases = [("score_select", score_select), ("compress", compress), ("decompress", decompress), ("dw", dw)]
     batched = args.select == "batched"
     dw_batched = args.dw == "batched"
-    per_tensor = [p for p in phases if not (batched and p[0] == "score_select") and not (dw_batched and p[0] == "dw")]
+    pack_batched = args.pack == "batched"
+    per_tensor = [p for p in phases if not (batched and p[0] == "score_select") and not (dw_batched and p[0] == "dw")
+                  and not (pack_batched and p[0] in ("compress", "decompress"))]
+    if pack_batched:
+        # mask -> BSR and BSR -> dense of every tensor of the step in one call each
+        cpb = B.CompressBatch([(t["X"], t["spec"].br, t["spec"].bc, t["mask"], t["n_keep"], t["row_ptr"], t["col_idx"],
+                                t["values"]) for t in tensors])
+        cpb_ws = torch.empty(max(cpb.ws_bytes, 256), dtype=torch.uint8, device=dev)
+        dcb = B.DecompressBatch([(t["row_ptr"], t["col_idx"], t["values"], t["spec"].M, t["spec"].K, t["spec"].br,
+                                  t["spec"].bc, t["Xhat"]) for t in tensors])
     if dw_batched:
         # every weight gradient of the step in one call, once all BSR forms exist: same results, the kernels of
         # one block shape share launches
@@ -187,7 +196,10 @@ def main():
         main_stream = torch.cuda.current_stream()
         if batched:
             score_select_all()
-        if not side:
+        if pack_batched:
+            B.bsr_compress_batched(cpb, ws=cpb_ws)
+            B.bsr_decompress_batched(dcb)
+        if not side or not per_tensor:
             for t in tensors:
                 for _, f in per_tensor:
                     f(t)
@@ -220,11 +232,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # About 190 kernel launches behind 109 calls through ctypes per step: the host needs about
-    # 1.9 ms to enqueue them, the GPU about 2.2 ms to run them, so an eagerly issued step is
-    # close to host-bound (2.26 ms).  By default the step is therefore captured once into a HIP
-    # graph and replayed (the library only launches kernels on the stream it is given, so every
-    # call is capturable); if the capture fails the steps are issued eagerly.
+    # With every stage batched a step is four calls through ctypes and about sixteen kernel launches; with
+    # per-tensor calls (--select / --pack / --dw single) it is up to 144 calls and 190 launches, and the host
+    # needs about as long to enqueue them as the GPU to run them.  By default the step is captured once into
+    # a HIP graph and replayed (the library only launches kernels on the stream it is given, so every call
+    # is capturable); if the capture fails the steps are issued eagerly.
     step()                                       # eager once: library loaded, workspaces touched
     torch.cuda.synchronize()
     h0 = time.perf_counter()
@@ -270,6 +282,10 @@ def main():
             phase_ms[name] = timed(score_select_all, args.phase_reps)
         elif name == "dw":
             phase_ms[name] = timed(dw_all, args.phase_reps)
+        elif pack_batched and name == "compress":
+            phase_ms[name] = timed(lambda: B.bsr_compress_batched(cpb, ws=cpb_ws), args.phase_reps)
+        elif pack_batched and name == "decompress":
+            phase_ms[name] = timed(lambda: B.bsr_decompress_batched(dcb), args.phase_reps)
         else:
             phase_ms[name] = timed(lambda: [f(t) for t in tensors], args.phase_reps)
 
@@ -409,6 +425,7 @@ def main():
                    "launch": "hip graph replay" if launch == "graph" else launch,
                    "score_select": "one batched call per step" if batched else "one call per tensor",
                    "dw": "one batched call per step" if dw_batched else "one call per tensor",
+                   "pack": "one batched call per step each" if pack_batched else "one call per tensor each",
                    "step": "score+select -> compress -> decompress -> dW for every tensor"},
         "phases": {
             "compress_GBps": round(comp_alg_bytes / (comp_ms * 1e-3) / 1e9, 2),
