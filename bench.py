@@ -421,7 +421,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"ResMLP-S12 full activation set, batch {args.batch}, {args.layers} layers x "
                                "(xpatch 14x14, fc1 32x32, fc2 32x32), bf16, keep 0.5",
-                   "tensors_per_step": len(tensors), "keep": keep, "streams": max(args.streams, 1),
+                   "tensors_per_step": len(tensors), "keep": keep,
+                   "streams": max(args.streams, 1) if per_tensor else 1,
                    "launch": "hip graph replay" if launch == "graph" else launch,
                    "score_select": "one batched call per step" if batched else "one call per tensor",
                    "dw": "one batched call per step" if dw_batched else "one call per tensor",
