@@ -676,3 +676,57 @@ def test_batched_compress_more_items_than_one_launch_holds():
         assert np.array_equal(rp.cpu().numpy(), o_rp) and np.array_equal(ci.cpu().numpy(), o_ci), f"item {i}"
         assert to_host(val).tobytes() == o_val.tobytes(), f"item {i}"
         assert to_host(back).tobytes() == oracle.mask_dense(Xs[i], pr[1], pr[2], m).tobytes(), f"item {i}"
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_random_small_shapes_through_every_call(dtype):
+    """Seeded sweep: ragged edges, ties, keep ratios from 0 to 1 and every block shape family, through the
+    single calls and once more through the calls that take several tensors."""
+    rng = np.random.default_rng(2024 if dtype == "bf16" else 2025)
+    blocks = [(32, 32), (64, 64), (16, 16), (14, 14), (1, 4), (1, 8), (1, 32), (7, 5), (3, 20), (2, 50), (128, 16)]
+    cases = []
+    for _ in range(28):
+        br, bc = blocks[int(rng.integers(len(blocks)))]
+        M = int(rng.integers(1, 6 * br + 40))
+        K = int(rng.integers(1, 5 * bc + 70))
+        N = int(rng.integers(1, 150))
+        nb = -(-M // br) * -(-K // bc)
+        keep = float(rng.choice([0.0, 1.0 / nb, 0.25, 0.5, 1.0 - 1.0 / nb, 1.0, float(rng.random())]))
+        cases.append((M, K, N, br, bc, min(max(keep, 0.0), 1.0)))
+    singles = []
+    for i, (M, K, N, br, bc, keep) in enumerate(cases):
+        print(f"[case] random {i}: M={M} K={K} N={N} block={br}x{bc} keep={keep:.4f} {dtype}", flush=True)
+        if i % 3 == 0:                                   # small integers: many exactly equal scores
+            Xi = rng.integers(-2, 3, size=(M, K)).astype(np.float32)
+            X = synth.f32_to_bf16_bits(Xi) if dtype == "bf16" else Xi
+            dY = rand_pair(M, K, N, dtype, seed=900 + i)[1]
+        else:
+            X, dY = rand_pair(M, K, N, dtype, seed=900 + i)
+        (rp, ci, val), o_mask = check_forward(X, br, bc, keep, label=f"random {i}")
+        dYd = to_dev(dY)
+        dW = B.bsr_t_dense_matmul(rp, ci, val, M, K, br, bc, dYd)
+        torch.cuda.synchronize()
+        ref = oracle.dw(oracle.mask_dense(X, br, bc, o_mask), dY)
+        assert dw_error(dW.cpu().numpy(), ref) <= DW_TOL_DERIVED, f"case {i}"
+        singles.append((to_dev(X), o_mask, rp, ci, val, dYd, dW))
+    # the same tensors through the calls for several tensors
+    sel = B.SelectBatch([s[0] for s in singles], [(c[3], c[4]) for c in cases], [c[5] for c in cases])
+    B.bsr_score_select_batched(sel)
+    nks = [B.bsr_keep_count(-(-c[0] // c[3]) * -(-c[1] // c[4]), c[5]) for c in cases]
+    cb = B.CompressBatch([(s[0], c[3], c[4], m, nk) for s, c, m, nk in zip(singles, cases, sel.keep_masks, nks)])
+    outs = B.bsr_compress_batched(cb)
+    db = B.DecompressBatch([(rp, ci, val, c[0], c[1], c[3], c[4]) for (rp, ci, val), c in zip(outs, cases)])
+    backs = B.bsr_decompress_batched(db)
+    mm = B.MatmulBatch([(rp, ci, val, c[0], c[1], c[3], c[4], s[5]) for (rp, ci, val), c, s in
+                        zip(outs, cases, singles)])
+    dWs = B.bsr_t_dense_matmul_batched(mm)
+    torch.cuda.synchronize()
+    for i, (s, c) in enumerate(zip(singles, cases)):
+        assert np.array_equal(sel.keep_masks[i].cpu().numpy(), s[1]), f"case {i} mask"
+        assert np.array_equal(outs[i][0].cpu().numpy(), s[2].cpu().numpy()), f"case {i} row_ptr"
+        assert np.array_equal(outs[i][1].cpu().numpy(), s[3].cpu().numpy()), f"case {i} col_idx"
+        assert to_host(outs[i][2]).tobytes() == to_host(s[4]).tobytes(), f"case {i} values"
+        want = B.bsr_decompress(s[2], s[3], s[4], c[0], c[1], c[3], c[4])
+        torch.cuda.synchronize()
+        assert to_host(backs[i]).tobytes() == to_host(want).tobytes(), f"case {i} dense"
+        assert dw_error(dWs[i].cpu().numpy(), s[6].cpu().numpy().astype(np.float64)) <= 2e-6, f"case {i} dW"
