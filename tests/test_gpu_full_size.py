@@ -161,3 +161,38 @@ def test_s12_batched_dw_of_a_whole_step_shape(kind):
         assert err <= DW_TOL[spec.dtype], (i, err)
         for j in dead:
             assert not g[j * spec.bc:(j + 1) * spec.bc].any()
+
+
+def test_s12_step_of_batched_calls_two_layers():
+    """The benchmark's step structure at full size: the six tensors of two layers through the four calls that
+    take several tensors; masks, BSR arrays and dense outputs in full against the oracle, dW on sampled entries."""
+    specs = list(synth.s12_layer(128)) * 2
+    pairs = [synth.make_pair(sp, 70 + i) for i, sp in enumerate(specs)]
+    Xs = [to_dev(X) for X, _ in pairs]
+    dYs = [to_dev(dY) for _, dY in pairs]
+    sel = B.SelectBatch(Xs, [(sp.br, sp.bc) for sp in specs], [sp.keep for sp in specs])
+    B.bsr_score_select_batched(sel)
+    nks = [B.bsr_keep_count(sp.nblocks, sp.keep) for sp in specs]
+    cb = B.CompressBatch([(X, sp.br, sp.bc, m, nk) for X, sp, m, nk in zip(Xs, specs, sel.keep_masks, nks)])
+    outs = B.bsr_compress_batched(cb)
+    db = B.DecompressBatch([(rp, ci, val, sp.M, sp.K, sp.br, sp.bc) for (rp, ci, val), sp in zip(outs, specs)])
+    backs = B.bsr_decompress_batched(db)
+    mm = B.MatmulBatch([(rp, ci, val, sp.M, sp.K, sp.br, sp.bc, dY) for (rp, ci, val), sp, dY in
+                        zip(outs, specs, dYs)])
+    dWs = B.bsr_t_dense_matmul_batched(mm)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(12)
+    for i, (sp, (X, dY)) in enumerate(zip(specs, pairs)):
+        print(f"[case] batched step item {i}: {sp.name}", flush=True)
+        o_scores, o_mask, o_rp, o_ci, o_val = oracle.prune(X, sp.br, sp.bc, sp.keep)
+        assert np.array_equal(sel.keep_masks[i].cpu().numpy(), o_mask), f"item {i} mask"
+        assert np.array_equal(outs[i][0].cpu().numpy(), o_rp) and np.array_equal(outs[i][1].cpu().numpy(), o_ci)
+        assert to_host(outs[i][2]).tobytes() == o_val.tobytes(), f"item {i} values"
+        xhat = oracle.mask_dense(X, sp.br, sp.bc, o_mask)
+        assert to_host(backs[i]).tobytes() == xhat.tobytes(), f"item {i} dense"
+        g = dWs[i].cpu().numpy()
+        ks, ns = rng.integers(0, sp.K, 24), rng.integers(0, sp.N, 24)
+        scale = float(np.max(np.abs(g)))
+        for k, n in zip(ks, ns):
+            ref = oracle.dw_entry(xhat, dY, int(k), int(n))
+            assert abs(float(g[k, n]) - ref) <= 2e-5 * scale, f"item {i} dW[{k},{n}]"
