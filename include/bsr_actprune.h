@@ -51,7 +51,8 @@ enum {
   BSR_ERR_KEEP = -4,      /* keep outside [0,1] or NaN, or n_keep != bsr_keep_count range */
   BSR_ERR_WORKSPACE = -5, /* ws is NULL or smaller than bsr_workspace_bytes() */
   BSR_ERR_ALIGN = -6,     /* a pointer is not aligned to its element type */
-  BSR_ERR_HIP = -7        /* a HIP call failed; see bsr_last_hip_error() */
+  BSR_ERR_HIP = -7,       /* a HIP call failed; see bsr_last_hip_error() */
+  BSR_ERR_LIMIT = -8      /* problem larger than the fixed capacity of an entry point that allocates nothing */
 };
 
 enum {
@@ -146,8 +147,31 @@ int bsr_score_select_grouped(const void *X, int dtype, int64_t M, int64_t K,
                              void *ws, size_t ws_bytes, void *stream);
 
 /*
- * Sec. III / Sec. II-A: "the activation tensor is converted to the BSR
- * format".  From X and a keep mask with exactly n_keep ones build
+ * For callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, outputs (bit for bit) and error codes as
+ * bsr_score_select, without `ws`: the workspace is a fixed array of about
+ * 10.3 MiB inside the library's code object, of which every GPU that the
+ * library runs on holds its own copy until the process ends.  Limit: matrices
+ * of at most bsr_score_select_static_max_blocks() = 524288 blocks; larger ones
+ * return BSR_ERR_LIMIT before anything is launched.  No hipMalloc / hipFree, no
+ * allocating library call.  All calls on one GPU share that GPU's array, which
+ * keeps the contents of the last call (the kernels initialise what they read):
+ * calls that overlap in time on one GPU -- different streams, or graphs replayed
+ * concurrently -- race and give undefined masks; order them on one stream.
+ * bsr_static_scratch_init() resolves the array's device address for the current
+ * device ahead of time (the first call on a device does it otherwise); returns
+ * BSR_OK or BSR_ERR_HIP.
+ */
+int64_t bsr_score_select_static_max_blocks(void);
+int bsr_static_scratch_init(void);
+int bsr_score_select_static(const void *X, int dtype, int64_t M, int64_t K,
+                            int64_t ldx, int br, int bc, double keep,
+                            double *scores, uint8_t *keep_mask, void *stream);
+
+/*
+ * Sec. III / Sec. II-A: conversion of the saved activation into BSR form.
+ * From X and a keep mask with exactly n_keep ones build
  *   row_ptr [nbr+1] : running count of kept blocks per block-row (crow);
  *   col_idx [n_keep]: block-column of every kept block, block-row after
  *                     block-row, ascending inside a block-row (col);
@@ -174,14 +198,15 @@ int bsr_decompress(const int32_t *row_ptr, const int32_t *col_idx,
                    int64_t ldx, int br, int bc, void *X_out, void *stream);
 
 /*
- * Sec. III, Fig. 2, "block-sparse matrix multiplication (BSpMM)": weight
+ * Sec. III, Fig. 2 (the block-sparse product of the backward pass): weight
  * gradient of a linear layer from the pruned activation,
  *   dW[j*bc + c, n] (+)= sum over kept blocks (i,j), rows r of the block:
  *                          values[block][r][c] * dY[i*br + r, n].
  * dY: [M x N] of the same dtype as values, leading dimension lddy.  dW: [K x N]
  * binary32, leading dimension lddw; overwritten when accumulate == 0, added to
- * otherwise.  Products are exact and accumulated in binary32 (matrix cores for
- * bfloat16).  This is X^T*dY; torch's nn.Linear.weight.grad is its transpose.
+ * otherwise.  Accumulation is in binary32 on the matrix cores; bfloat16 products
+ * are exact in binary32, binary32 products are rounded like any binary32
+ * multiply-add.  This is X^T*dY; torch's nn.Linear.weight.grad is its transpose.
  * The contraction is split over block-rows; partial sums are reduced in a fixed
  * order, so results are reproducible run to run.
  * Block shapes 32x32, 64x64, 16x16 and 14x14 are multiplied as stored (pruned

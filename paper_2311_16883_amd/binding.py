@@ -21,7 +21,7 @@ BSR_OP_AFFINE_SCALE_GRAD = 4
 
 BSR_OK = 0
 BSR_ERR_NULL, BSR_ERR_SHAPE, BSR_ERR_DTYPE, BSR_ERR_KEEP = -1, -2, -3, -4
-BSR_ERR_WORKSPACE, BSR_ERR_ALIGN, BSR_ERR_HIP = -5, -6, -7
+BSR_ERR_WORKSPACE, BSR_ERR_ALIGN, BSR_ERR_HIP, BSR_ERR_LIMIT = -5, -6, -7, -8
 
 _PKG = Path(__file__).resolve().parent
 LIB_PATH = _PKG / "libbsr_actprune.so"
@@ -33,6 +33,7 @@ EXPORTS = (
     "bsr_affine_scale_grad", "bsr_score_select_batched", "bsr_score_select_batched_workspace_bytes",
     "bsr_t_dense_matmul_batched", "bsr_t_dense_matmul_batched_workspace_bytes",
     "bsr_compress_batched", "bsr_compress_batched_workspace_bytes", "bsr_decompress_batched",
+    "bsr_score_select_static", "bsr_score_select_static_max_blocks", "bsr_static_scratch_init",
 )
 
 
@@ -98,6 +99,12 @@ def lib() -> C.CDLL:
     l.bsr_decompress_batched.argtypes = [vp, i32, i32, vp]
     l.bsr_affine_scale_grad.restype = i32
     l.bsr_affine_scale_grad.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, vp, i64, vp, i32, vp, sz, vp]
+    l.bsr_score_select_static.restype = i32
+    l.bsr_score_select_static.argtypes = [vp, i32, i64, i64, i64, i32, i32, dbl, vp, vp, vp]
+    l.bsr_score_select_static_max_blocks.restype = i64
+    l.bsr_score_select_static_max_blocks.argtypes = []
+    l.bsr_static_scratch_init.restype = i32
+    l.bsr_static_scratch_init.argtypes = []
     _lib = l
     return l
 
@@ -200,6 +207,24 @@ def bsr_score_select(X: torch.Tensor, br: int, bc: int, keep: float, *,
                                 _stream(stream))
     _check(rc, "bsr_score_select")
     return (keep_mask, scores) if scores is not None else keep_mask
+
+
+def bsr_score_select_static(X: torch.Tensor, br: int, bc: int, keep: float, keep_mask: torch.Tensor, *,
+                            scores: Optional[torch.Tensor] = None, stream=None):
+    """bsr_score_select without a workspace argument; the outputs are the caller's, nothing is allocated."""
+    M, K, ldx = _dense2d(X, "X")
+    rc = lib().bsr_score_select_static(_ptr(X), dtype_code(X.dtype), M, K, ldx, br, bc, float(keep),
+                                       _ptr(scores), _ptr(keep_mask), _stream(stream))
+    _check(rc, "bsr_score_select_static")
+    return (keep_mask, scores) if scores is not None else keep_mask
+
+
+def bsr_score_select_static_max_blocks() -> int:
+    return int(lib().bsr_score_select_static_max_blocks())
+
+
+def bsr_static_scratch_init() -> None:
+    _check(lib().bsr_static_scratch_init(), "bsr_static_scratch_init")
 
 
 def bsr_grouped_keep_count(nbr: int, nbc: int, group_rows: int, keep: float) -> int:

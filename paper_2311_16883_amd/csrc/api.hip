@@ -68,6 +68,7 @@ const char *bsr_error_string(int code) {
     case BSR_ERR_WORKSPACE: return "BSR_ERR_WORKSPACE";
     case BSR_ERR_ALIGN: return "BSR_ERR_ALIGN";
     case BSR_ERR_HIP: return "BSR_ERR_HIP";
+    case BSR_ERR_LIMIT: return "BSR_ERR_LIMIT";
     default: return "BSR_ERR_UNKNOWN";
   }
 }

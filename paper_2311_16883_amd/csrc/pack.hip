@@ -1,5 +1,5 @@
 // Dense -> BSR conversion and its inverse (paper Sec. II-A: crow / col / values;
-// Sec. III: "the activation tensor is converted to the BSR format").
+// Sec. III: the saved activation is kept in that format).
 //
 //   index build : exclusive prefix sum of the keep mask in linear block order
 //                 -> row_ptr (crow) and col_idx (col), one launch;

@@ -23,7 +23,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     syms = declared_symbols()
-    assert set(syms) == set(B.EXPORTS) and len(syms) == 20
+    assert set(syms) == set(B.EXPORTS) and len(syms) == 23
     lib = B.lib()
     for s in syms:
         assert getattr(lib, s) is not None
@@ -264,3 +264,16 @@ def test_product_path_does_not_touch_the_oracle():
     for f in list(pkg.glob("*.py")) + list((pkg / "csrc").glob("*")):
         text = f.read_text()
         assert "import oracle" not in text and "from oracle" not in text and "liboracle" not in text, f
+
+
+def test_static_entry_point_refuses_oversized_problems_on_the_host():
+    lib = B.lib()
+    limit = lib.bsr_score_select_static_max_blocks()
+    assert limit == 524288
+    fake = C.c_void_p(4096)      # never dereferenced: every call below is refused before any HIP call
+    # 1025 * 512 blocks > limit
+    assert lib.bsr_score_select_static(fake, B.BSR_BF16, 1025, 2048, 2048, 1, 4, 0.5, None, fake, None) == B.BSR_ERR_LIMIT
+    assert lib.bsr_score_select_static(fake, B.BSR_F32, 1 << 30, 1 << 20, 1 << 20, 1, 1, 0.5, None, fake, None) == B.BSR_ERR_LIMIT
+    assert lib.bsr_score_select_static(fake, 7, 64, 64, 64, 16, 16, 0.5, None, fake, None) == B.BSR_ERR_DTYPE
+    assert lib.bsr_score_select_static(fake, B.BSR_F32, 64, 64, 64, 0, 16, 0.5, None, fake, None) == B.BSR_ERR_SHAPE
+    assert lib.bsr_error_string(B.BSR_ERR_LIMIT) == b"BSR_ERR_LIMIT"
