@@ -2,6 +2,8 @@
 // launches on the caller's stream.  See include/bsr_actprune.h for the contract
 // of every entry point.
 #include <cmath>
+#include <cstdio>
+#include <cstdlib>
 #include <vector>
 
 #include "common.h"
@@ -48,6 +50,26 @@ bool misaligned(const void *p, size_t a) { return p != nullptr && (uintptr_t)p %
 size_t scores_bytes(int64_t nblocks) { return align_up((size_t)nblocks * sizeof(double), 256); }
 
 size_t score_select_ws(int64_t nblocks) { return scores_bytes(nblocks) + select_ws_bytes(nblocks); }
+
+// development switch (to be removed): BSR_DW_WIDE=mode[,config[,splits]]; mode 0 = automatic,
+// 1 = the wide kernel wherever it applies, 2 = never
+int wide_mode() {
+  int m = 0, c = 0, sp = 0, dbg = 0;
+  if (const char *e = getenv("BSR_DW_WIDE")) sscanf(e, "%d,%d,%d,%d", &m, &c, &sp, &dbg);
+  dw_wide_set_config(c, sp, dbg);
+  return m;
+}
+
+// Which products take the wide-tile kernel: in a call of its own, a product whose tiles
+// fill the GPU without a deep split of the contraction; in a batched call, every product
+// that qualifies once the batch has enough tiles.
+bool use_wide_single(int dtype, int br, int bc, const void *values, const void *dY, int64_t M, int64_t K, int64_t N,
+                     int64_t lddy) {
+  if (wide_mode() == 2 || !dw_wide_supported(dtype, br, bc, values, dY, M, K, N, lddy)) return false;
+  if (wide_mode() == 1) return true;
+  const int64_t tiles = ceil_div(K, 384) * ceil_div(N, 128);
+  return tiles >= 32;
+}
 
 }  // namespace
 }  // namespace bsr
@@ -103,7 +125,11 @@ size_t bsr_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int br, int 
       {
         size_t a = dw_generic_ws_bytes(M, K, N, br, bc);
         if (dw_mfma_supported(dtype, br, bc, nullptr, M, K, N, N)) {
-          const size_t b = dw_mfma_ws_bytes(dtype, M, K, N, br, bc);
+          size_t b = dw_mfma_ws_bytes(dtype, M, K, N, br, bc);
+          if (dw_wide_supported(dtype, br, bc, nullptr, nullptr, M, K, N, N)) {
+            const size_t c = dw_wide_ws_bytes(M, K, N, br);
+            if (c > b) b = c;
+          }
           if (b > a) a = b;
         } else if (dw_reblock_supported(dtype, br, bc, M, K, N, N)) {
           const size_t b = dw_reblock_ws_bytes(dtype, M, K, N);
@@ -221,6 +247,10 @@ int bsr_t_dense_matmul(const int32_t *row_ptr, const int32_t *col_idx, const voi
     return BSR_ERR_ALIGN;
   const size_t need = bsr_workspace_bytes(BSR_OP_T_DENSE_MATMUL, M, K, N, br, bc, dtype);
   if (need > 0 && (ws == nullptr || ws_bytes < need)) return BSR_ERR_WORKSPACE;
+  if (use_wide_single(dtype, br, bc, values, dY, M, K, N, lddy)) {
+    const DwJob job{row_ptr, col_idx, values, M, K, br, bc, dY, N, lddy, dW, lddw, accumulate, ws, ws_bytes};
+    return launch_dw_wide(job, static_cast<hipStream_t>(stream));
+  }
   if (dw_mfma_supported(dtype, br, bc, values, M, K, N, lddy))
     return launch_dw_mfma(dtype, row_ptr, col_idx, values, M, K, br, bc, dY, N, lddy, dW, lddw, accumulate,
                           ws, ws_bytes, static_cast<hipStream_t>(stream));
@@ -319,8 +349,9 @@ int bsr_t_dense_matmul_batched(const bsr_matmul_item *items, int n, int dtype, v
   if (n == 0) return BSR_OK;
   if (items == nullptr) return BSR_ERR_NULL;
   if (misaligned(ws, 16)) return BSR_ERR_ALIGN;
-  std::vector<DwJob> batch, single;
+  std::vector<DwJob> batch, single, wide;
   batch.reserve(n);
+  int64_t wide_tiles = 0;
   size_t off = 0;
   for (int i = 0; i < n; ++i) {
     const bsr_matmul_item &it = items[i];
@@ -339,11 +370,23 @@ int bsr_t_dense_matmul_batched(const bsr_matmul_item *items, int n, int dtype, v
     const DwJob job{it.row_ptr, it.col_idx, it.values, it.M, it.K, it.br, it.bc, it.dY, it.N, it.lddy, it.dW,
                     it.lddw, it.accumulate, need > 0 ? static_cast<char *>(ws) + off : nullptr, need};
     off += need;
-    if (dw_mfma_supported(dtype, it.br, it.bc, it.values, it.M, it.K, it.N, it.lddy)) batch.push_back(job);
-    else single.push_back(job);
+    if (wide_mode() != 2 && dw_wide_supported(dtype, it.br, it.bc, it.values, it.dY, it.M, it.K, it.N, it.lddy)) {
+      wide.push_back(job);
+      wide_tiles += ceil_div(it.K, 384) * ceil_div(it.N, 128);
+    } else if (dw_mfma_supported(dtype, it.br, it.bc, it.values, it.M, it.K, it.N, it.lddy)) {
+      batch.push_back(job);
+    } else {
+      single.push_back(job);
+    }
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  int rc = launch_dw_mfma_batched(dtype, batch.data(), (int)batch.size(), s);
+  // too few tiles to fill the GPU without a deep split: the narrow-tile kernel suits those better
+  if (!wide.empty() && wide_mode() != 1 && wide_tiles < 64) {
+    batch.insert(batch.end(), wide.begin(), wide.end());
+    wide.clear();
+  }
+  int rc = launch_dw_wide_batched(wide.data(), (int)wide.size(), s);
+  if (rc == BSR_OK) rc = launch_dw_mfma_batched(dtype, batch.data(), (int)batch.size(), s);
   for (size_t i = 0; rc == BSR_OK && i < single.size(); ++i) {
     const DwJob &j = single[i];
     rc = bsr_t_dense_matmul(j.row_ptr, j.col_idx, j.values, dtype, j.M, j.K, j.br, j.bc, j.dY, j.N, j.lddy, j.dW,

@@ -188,6 +188,14 @@ struct DwJob {
 // K == 0 or N == 0) with as few launches as their kernel instances allow.
 int launch_dw_mfma_batched(int dtype, const DwJob *jobs, int n, hipStream_t s);
 
+// dw_wide.hip: bfloat16, 32x32 / 64x64 blocks, 384-row tiles fed by global -> LDS copies.
+bool dw_wide_supported(int dtype, int br, int bc, const void *values, const void *dY, int64_t M, int64_t K,
+                       int64_t N, int64_t lddy);
+size_t dw_wide_ws_bytes(int64_t M, int64_t K, int64_t N, int br);
+int launch_dw_wide(const DwJob &j, hipStream_t s);
+int launch_dw_wide_batched(const DwJob *jobs, int n, hipStream_t s);
+void dw_wide_set_config(int config, int splits, int debug = 0);
+
 // ---- device helpers ----
 
 // w / d for w * d < 2^32, with magic = ceil(2^32 / d) (d == 1 has no 32-bit magic)
