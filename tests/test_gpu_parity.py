@@ -587,6 +587,52 @@ def test_batched_dw_more_items_than_one_launch_holds():
             assert dw_error(first[i], ref) <= DW_TOL_DERIVED, f"item {i}"
 
 
+@pytest.mark.parametrize("bs", [32, 64])
+def test_dw_wide_tiles_ragged_everything(bs):
+    """bfloat16 products with 32 or more tiles of 384 x 128 go to the kernel with workgroup-wide
+    tiles: rows, columns and output columns that end inside a block, a tile, a 16-byte chunk."""
+    M, K, N = 2000, 1500, 1000
+    print(f"[case] wide-tile dW M={M} K={K} N={N} block={bs}", flush=True)
+    X, dY = rand_pair(M, K, N, "bf16", seed=bs, dist="gelu")
+    o_scores, o_mask, o_rp, o_ci, o_val = oracle.prune(X, bs, bs, 0.5)
+    ref = oracle.dw(oracle.mask_dense(X, bs, bs, o_mask), dY)
+    rp, ci = torch.from_numpy(o_rp).cuda(), torch.from_numpy(o_ci).cuda()
+    val = to_dev(o_val.reshape(-1, bs)).reshape(o_val.shape)
+    dYd = to_dev(dY)
+    dW = B.bsr_t_dense_matmul(rp, ci, val, M, K, bs, bs, dYd)
+    torch.cuda.synchronize()
+    assert dw_error(dW.cpu().numpy(), ref) <= DW_TOL_DERIVED
+    base = torch.full((K, N), 0.25, dtype=torch.float32, device="cuda")
+    B.bsr_t_dense_matmul(rp, ci, val, M, K, bs, bs, dYd, dW=base, accumulate=True)
+    torch.cuda.synchronize()
+    assert dw_error(base.cpu().numpy() - 0.25, ref) <= 1e-4 * max(1.0, 0.25 / np.max(np.abs(ref)))
+
+
+def test_batched_dw_with_more_tiles_than_compute_units():
+    """24 products of 16 tiles each: the first sixteen products are run tile by tile, each tile
+    by one workgroup over all 500 block-rows (more than one table's worth: two chunks), the
+    last eight are split along the contraction and summed by the reduction."""
+    M, K, N = 16000, 1536, 512
+    pairs = []
+    for i in range(3):
+        print(f"[case] batched wide-tile dW, inputs {i}", flush=True)
+        X, dY = rand_pair(M, K, N, "bf16", seed=900 + i, dist="gelu")
+        o_scores, o_mask, o_rp, o_ci, o_val = oracle.prune(X, 32, 32, 0.5)
+        rp, ci = torch.from_numpy(o_rp).cuda(), torch.from_numpy(o_ci).cuda()
+        val = to_dev(o_val.reshape(-1, 32)).reshape(o_val.shape)
+        pairs.append((X, dY, o_mask, (rp, ci, val, M, K, 32, 32, to_dev(dY))))
+    problems = [pairs[i % 3][3] for i in range(24)]
+    outs = B.bsr_t_dense_matmul_batched(B.MatmulBatch(problems))
+    torch.cuda.synchronize()
+    got = [o.cpu().numpy() for o in outs]
+    for i in (0, 23):                 # one product of either kind against the oracle, whole
+        X, dY, o_mask, _ = pairs[i % 3]
+        ref = oracle.dw(oracle.mask_dense(X, 32, 32, o_mask), dY)
+        assert dw_error(got[i], ref) <= DW_TOL_DERIVED, f"item {i}"
+    for i in range(3, 24):            # the same inputs give the same sums, in the same or another order
+        assert dw_error(got[i], got[i % 3].astype(np.float64)) <= 2e-6, f"item {i}"
+
+
 PACK_BATCH = [
     # M, K, br, bc, keep
     (2048, 384, 32, 32, 0.5),           # direct kernels, 16-byte vectors
