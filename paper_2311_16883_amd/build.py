@@ -30,7 +30,6 @@ FLAGS = [
 ]
 
 
-EXTRA = os.environ.get("BSR_EXTRA_HIPCC_FLAGS", "").split()   # development builds only
 
 
 def sources():
@@ -42,7 +41,7 @@ def build_library(verbose: bool = False, jobs: int = 8) -> Path:
 
     def compile_one(src: Path) -> Path:
         obj = OBJ / (src.stem + ".o")
-        cmd = [HIPCC, *FLAGS, *EXTRA, "-c", str(src), "-o", str(obj)]
+        cmd = [HIPCC, *FLAGS, "-c", str(src), "-o", str(obj)]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)

@@ -2,8 +2,6 @@
 // launches on the caller's stream.  See include/bsr_actprune.h for the contract
 // of every entry point.
 #include <cmath>
-#include <cstdio>
-#include <cstdlib>
 #include <vector>
 
 #include "common.h"
@@ -51,24 +49,17 @@ size_t scores_bytes(int64_t nblocks) { return align_up((size_t)nblocks * sizeof(
 
 size_t score_select_ws(int64_t nblocks) { return scores_bytes(nblocks) + select_ws_bytes(nblocks); }
 
-// development switch (to be removed): BSR_DW_WIDE=mode[,config[,splits]]; mode 0 = automatic,
-// 1 = the wide kernel wherever it applies, 2 = never
-int wide_mode() {
-  int m = 0, c = 0, sp = 0, dbg = 0;
-  if (const char *e = getenv("BSR_DW_WIDE")) sscanf(e, "%d,%d,%d,%d", &m, &c, &sp, &dbg);
-  dw_wide_set_config(c, sp, dbg);
-  return m;
+// How well a product suits the wide-tile kernel: its tiles of 384 x 128 times the ways its
+// contraction can be split, i.e. the workgroups it can keep busy.  A call takes the wide
+// kernel when that reaches half the compute units.
+int64_t wide_parallelism(int64_t M, int64_t K, int64_t N, int br) {
+  const int64_t nbr = ceil_div(M, br);
+  return ceil_div(K, 384) * ceil_div(N, 128) * (nbr < 16 ? nbr : 16);
 }
 
-// Which products take the wide-tile kernel: in a call of its own, a product whose tiles
-// fill the GPU without a deep split of the contraction; in a batched call, every product
-// that qualifies once the batch has enough tiles.
 bool use_wide_single(int dtype, int br, int bc, const void *values, const void *dY, int64_t M, int64_t K, int64_t N,
                      int64_t lddy) {
-  if (wide_mode() == 2 || !dw_wide_supported(dtype, br, bc, values, dY, M, K, N, lddy)) return false;
-  if (wide_mode() == 1) return true;
-  const int64_t tiles = ceil_div(K, 384) * ceil_div(N, 128);
-  return tiles >= 32;
+  return dw_wide_supported(dtype, br, bc, values, dY, M, K, N, lddy) && wide_parallelism(M, K, N, br) >= 128;
 }
 
 }  // namespace
@@ -351,7 +342,7 @@ int bsr_t_dense_matmul_batched(const bsr_matmul_item *items, int n, int dtype, v
   if (misaligned(ws, 16)) return BSR_ERR_ALIGN;
   std::vector<DwJob> batch, single, wide;
   batch.reserve(n);
-  int64_t wide_tiles = 0;
+  int64_t wide_par = 0;
   size_t off = 0;
   for (int i = 0; i < n; ++i) {
     const bsr_matmul_item &it = items[i];
@@ -370,9 +361,9 @@ int bsr_t_dense_matmul_batched(const bsr_matmul_item *items, int n, int dtype, v
     const DwJob job{it.row_ptr, it.col_idx, it.values, it.M, it.K, it.br, it.bc, it.dY, it.N, it.lddy, it.dW,
                     it.lddw, it.accumulate, need > 0 ? static_cast<char *>(ws) + off : nullptr, need};
     off += need;
-    if (wide_mode() != 2 && dw_wide_supported(dtype, it.br, it.bc, it.values, it.dY, it.M, it.K, it.N, it.lddy)) {
+    if (dw_wide_supported(dtype, it.br, it.bc, it.values, it.dY, it.M, it.K, it.N, it.lddy)) {
       wide.push_back(job);
-      wide_tiles += ceil_div(it.K, 384) * ceil_div(it.N, 128);
+      wide_par += wide_parallelism(it.M, it.K, it.N, it.br);
     } else if (dw_mfma_supported(dtype, it.br, it.bc, it.values, it.M, it.K, it.N, it.lddy)) {
       batch.push_back(job);
     } else {
@@ -380,8 +371,8 @@ int bsr_t_dense_matmul_batched(const bsr_matmul_item *items, int n, int dtype, v
     }
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  // too few tiles to fill the GPU without a deep split: the narrow-tile kernel suits those better
-  if (!wide.empty() && wide_mode() != 1 && wide_tiles < 64) {
+  // too few tiles to fill the GPU even with a deep split: the narrow-tile kernel suits those better
+  if (!wide.empty() && wide_par < 128) {
     batch.insert(batch.end(), wide.begin(), wide.end());
     wide.clear();
   }

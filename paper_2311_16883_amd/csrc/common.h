@@ -194,7 +194,6 @@ bool dw_wide_supported(int dtype, int br, int bc, const void *values, const void
 size_t dw_wide_ws_bytes(int64_t M, int64_t K, int64_t N, int br);
 int launch_dw_wide(const DwJob &j, hipStream_t s);
 int launch_dw_wide_batched(const DwJob *jobs, int n, hipStream_t s);
-void dw_wide_set_config(int config, int splits, int debug = 0);
 
 // ---- device helpers ----
 

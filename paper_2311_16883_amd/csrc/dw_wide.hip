@@ -473,8 +473,6 @@ __global__ __launch_bounds__(kWideThreads) void dw_wide_batched_kernel(WideBatch
 // host side
 // ---------------------------------------------------------------------------------------
 
-int g_wide_splits = 0;        // > 0: forced number of splits (measurements)
-
 int64_t wide_tiles(int64_t K, int64_t N) { return ceil_div(K, kTileK) * ceil_div(N, kTileN); }
 
 // The plan of one launch.  The products [0, whole) are not split: one workgroup runs all the
@@ -497,10 +495,6 @@ WidePlan wide_plan(const int64_t *tiles, const int64_t *stages, const int64_t *r
   int64_t s_max = min_rows < kWideMaxSplits ? min_rows : kWideMaxSplits;
   if (s_max < 1) s_max = 1;
   WidePlan best{0, 1};
-  if (g_wide_splits > 0) {
-    best.splits = (int)(g_wide_splits < s_max ? g_wide_splits : s_max);
-    return best;
-  }
   double best_cost = 0;
   bool first = true;
   for (int w = 0; w <= m; ++w) {
@@ -628,12 +622,6 @@ int wide_run_batched(const DwJob *jobs, int n, hipStream_t s) {
 }
 
 }  // namespace
-
-void dw_wide_set_config(int config, int splits, int debug) {
-  (void)config;
-  (void)debug;
-  g_wide_splits = splits;
-}
 
 // Shapes the wide kernel takes: bfloat16, 32x32 or 64x64 blocks, dY rows that are whole
 // 16-byte chunks, operands addressable with 32-bit byte offsets.

@@ -21,6 +21,7 @@ struct ScoreGeom {
   int gb;    // row groups per block-row
   int rb;    // block-rows handled per pass
   int nchunks;
+  int direct;  // 1: score_direct_body, one lane per vector column of a block-row; nchunks = its workgroups
 };
 
 // bx, by, gy: the workgroup's place in its tensor's (chunks x passes) grid.  Threads beyond
@@ -91,11 +92,59 @@ __device__ __forceinline__ void score_body(
   }
 }
 
+// Large matrices: bc / V * rs lanes own a block -- lane (part, u) reads vector u of the rows
+// part, part + rs, ... of the block, eight loads on their way at a time (consecutive lanes
+// read consecutive vectors of a matrix row, whole 64-byte pieces or more) -- and add their sums
+// with a butterfly of lane exchanges in a fixed order.  No LDS, no barrier, every lane busy.
+// rs (a power of two, g.gb) is chosen so that the tensor has enough lanes for the chip.
+// wg = index of the workgroup among the ceil(nbr * nbc * (bc / V) * rs / 256) of its tensor.
+template <typename T, int V>
+__device__ __forceinline__ void score_direct_body(
+    const T *__restrict__ X, int64_t M, int64_t K, int64_t ldx, int br, int bc, int64_t nbr,
+    int64_t nbc, int rs, double *__restrict__ scores, uint32_t wg) {
+  const uint32_t vpb = (uint32_t)(bc / V);                 // lanes across a block row: a power of two
+  const uint32_t lpb = vpb * (uint32_t)rs;                 // lanes per block: a power of two, at most 64
+  const uint32_t per_row = (uint32_t)nbc * lpb;            // lanes per block-row
+  const uint32_t gid = wg * (uint32_t)kScoreThreads + threadIdx.x;
+  const uint32_t i = gid / per_row, c = gid - i * per_row;
+  const uint32_t j = c / lpb, within = c & (lpb - 1), part = within / vpb, u = within & (vpb - 1);
+  const int64_t col = (int64_t)j * bc + (int64_t)u * V;
+  const bool live = (int64_t)i < nbr && col < K;
+  const int64_t m0 = (int64_t)i * br;
+  const int rows = live ? (int)((M - m0) < br ? (M - m0) : br) : 0;
+  const T *p = X + m0 * ldx + col;
+  double acc0 = 0.0, acc1 = 0.0;                           // even and odd elements of the vectors
+  // (eight, not more: with sixteen the registers they need leave room for three waves per SIMD only,
+  // and a workgroup has nothing in flight while it adds up)
+  constexpr int kInFlight = 8;
+  for (int r0 = (int)part; r0 < rows; r0 += kInFlight * rs) {
+    Vec<T, V> v[kInFlight];
+#pragma unroll
+    for (int b = 0; b < kInFlight; ++b)
+      if (r0 + b * rs < rows) v[b] = *reinterpret_cast<const Vec<T, V> *>(p + (int64_t)(r0 + b * rs) * ldx);
+#pragma unroll
+    for (int b = 0; b < kInFlight; ++b) {
+      if (r0 + b * rs < rows) {
+#pragma unroll
+        for (int q = 0; q < V; ++q) {
+          const double x = (double)elem_to_float<T>(v[b].e[q]);
+          if (q & 1) acc1 = fma(x, x, acc1);
+          else acc0 = fma(x, x, acc0);
+        }
+      }
+    }
+  }
+  double sum = acc0 + acc1;
+  for (uint32_t o = 1; o < lpb; o <<= 1) sum += __shfl_xor(sum, (int)o);
+  if (live && within == 0) scores[(int64_t)i * nbc + j] = sum;
+}
+
 template <typename T, int V>
 __global__ __launch_bounds__(kScoreThreads) void score_kernel(
     const T *__restrict__ X, int64_t M, int64_t K, int64_t ldx, int br, int bc, int64_t nbr,
     int64_t nbc, ScoreGeom g, double *__restrict__ scores) {
-  score_body<T, V>(X, M, K, ldx, br, bc, nbr, nbc, g, scores, blockIdx.x, blockIdx.y, gridDim.y);
+  if (g.direct) score_direct_body<T, V>(X, M, K, ldx, br, bc, nbr, nbc, g.gb, scores, blockIdx.x);
+  else score_body<T, V>(X, M, K, ldx, br, bc, nbr, nbc, g, scores, blockIdx.x, blockIdx.y, gridDim.y);
 }
 
 // Several tensors per launch: workgroup w belongs to the tensor whose range of
@@ -119,6 +168,11 @@ __global__ __launch_bounds__(kScoreThreads) void score_batched_kernel(ScoreBatch
   while (i + 1 < n && blockIdx.x >= b.it[i + 1].wg_begin) ++i;
   const ScoreItem &it = b.it[i];
   const uint32_t local = blockIdx.x - it.wg_begin;
+  if (it.g.direct) {
+    score_direct_body<T, V>(static_cast<const T *>(it.X), it.M, it.K, it.ldx, it.br, it.bc, it.nbr, it.nbc, it.g.gb, it.scores,
+                            local);
+    return;
+  }
   score_body<T, V>(static_cast<const T *>(it.X), it.M, it.K, it.ldx, it.br, it.bc, it.nbr, it.nbc, it.g, it.scores,
                    local % (uint32_t)it.g.nchunks, local / (uint32_t)it.g.nchunks, it.gy);
 }
@@ -291,6 +345,22 @@ ScoreGeom score_geometry(int V, int64_t M, int64_t K, int br, int bc, int64_t *g
   const int64_t nbr = ceil_div(M, br), nbc = ceil_div(K, bc);
   ScoreGeom g;
   const int vpb = bc / V;
+  g.direct = 0;
+  // large matrices take the direct body: rs lanes share a vector column of a block so that the
+  // tensor has at least 64 Ki lanes, and every lane still has a few rows
+  if (vpb >= 1 && vpb <= 64 && (vpb & (vpb - 1)) == 0 && vpb * V == bc) {
+    int rs = 1;
+    while (nbr * nbc * vpb * rs < 65536 && vpb * rs * 2 <= 64 && rs * 2 * 4 <= br) rs *= 2;
+    const int64_t lanes = nbr * nbc * vpb * rs;
+    if (lanes >= 16384 && lanes < (int64_t(1) << 31)) {
+      g.direct = 1;
+      g.jc = g.vpbt = g.vct = g.rb = 1;
+      g.gb = rs;
+      g.nchunks = (int)ceil_div(lanes, (int64_t)kScoreThreads);
+      *gy_out = 1;
+      return g;
+    }
+  }
   g.vpbt = vpb < kScoreThreads ? vpb : kScoreThreads;
   // about one wave across the chunk (a 1 KB row segment per load instruction), the
   // other waves of the workgroup as row groups: many workgroups, few rows per
@@ -322,7 +392,7 @@ int run_score(const void *X, int64_t M, int64_t K, int64_t ldx, int br, int bc, 
   int64_t gy;
   const ScoreGeom g = score_geometry(V, M, K, br, bc, &gy);
   dim3 grid((unsigned)g.nchunks, (unsigned)gy, 1);
-  hipLaunchKernelGGL((score_kernel<T, V>), grid, dim3(g.vct * g.gb * g.rb), 0, s,
+  hipLaunchKernelGGL((score_kernel<T, V>), grid, dim3(g.direct ? kScoreThreads : g.vct * g.gb * g.rb), 0, s,
                      static_cast<const T *>(X), M, K, ldx, br, bc, nbr, nbc, g, scores);
   return check_launch();
 }
