@@ -209,11 +209,18 @@ int bsr_decompress(const int32_t *row_ptr, const int32_t *col_idx,
  * multiply-add.  This is X^T*dY; torch's nn.Linear.weight.grad is its transpose.
  * The contraction is split over block-rows; partial sums are reduced in a fixed
  * order, so results are reproducible run to run.
- * Block shapes 32x32, 64x64, 16x16 and 14x14 are multiplied as stored (pruned
- * blocks are skipped).  Any other shape -- 1 x b row segments, b = K, rectangular
- * blocks -- is first re-tiled into 32x32 blocks inside the workspace (pruned
- * positions become +0.0 and are multiplied like any other value); the workspace
- * size reported for such a shape includes that copy (about M*K elements).
+ * Block shapes 32x32, 64x64, 16x16 and 14x14 are multiplied as stored.  Any other
+ * shape -- 1 x b row segments, b = K, rectangular blocks -- is first re-tiled into
+ * 32x32 blocks inside the workspace; the workspace size reported for such a shape
+ * includes that copy (about M*K elements).
+ * col_idx must ascend inside a block-row or not: any order is accepted.
+ * Non-finite dY: a 32x32 or 64x64 block that was pruned is never multiplied, so an
+ * inf or NaN of dY reaches only the rows of dW that belong to kept blocks of its
+ * block-row.  For every other block shape the kept blocks are multiplied inside
+ * zero-filled 32-wide tiles, and a zero of the tile times inf is NaN: there the
+ * rows of dW that belong to pruned blocks of that block-row may become NaN as
+ * well (as they all do in a dense product with the masked matrix).  Columns of dW
+ * other than the one of the non-finite value are never affected.
  */
 int bsr_t_dense_matmul(const int32_t *row_ptr, const int32_t *col_idx,
                        const void *values, int dtype, int64_t M, int64_t K,

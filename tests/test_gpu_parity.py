@@ -633,6 +633,93 @@ def test_batched_dw_with_more_tiles_than_compute_units():
         assert dw_error(got[i], got[i % 3].astype(np.float64)) <= 2e-6, f"item {i}"
 
 
+@pytest.mark.parametrize("br,bc,dtype,skips,big", [
+    (32, 32, "bf16", True, False), (64, 64, "bf16", True, False), (32, 32, "f32", True, False),
+    (64, 64, "f32", True, False), (32, 32, "bf16", True, True), (64, 64, "bf16", True, True),
+    (16, 16, "bf16", False, False), (14, 14, "bf16", False, False), (1, 32, "bf16", False, False),
+    (7, 5, "bf16", False, False),
+])
+def test_non_finite_dy_per_block_shape_family(br, bc, dtype, skips, big):
+    """One +inf in dY.  The oracle multiplies the zeros of pruned blocks with it (0 * inf = NaN in a
+    whole column of dW).  The library guarantees less and more: columns of dW other than the one of
+    the inf are untouched by it; rows of dW that belong to a kept block of the inf's block-row get
+    +-inf; rows that belong to a pruned block of that block-row are finite for 32x32 and 64x64 blocks
+    (pruned blocks are never multiplied), and for the other block shapes either finite or NaN (their
+    kept blocks are multiplied inside zero-filled tiles, and a zero of the tile times inf is NaN)."""
+    M, N = 448, 48
+    K = 210 if bc == 14 else (245 if bc == 5 else 256)
+    if big:                                # enough tiles for the kernel with workgroup-wide tiles
+        M, K, N = 2048, 1536, 1024
+    X, dY = rand_pair(M, K, N, dtype, seed=br * 100 + bc)
+    o_scores, o_mask, o_rp, o_ci, o_val = oracle.prune(X, br, bc, 0.5)
+    nbr, nbc = -(-M // br), -(-K // bc)
+    mask2 = o_mask.reshape(nbr, nbc)
+    i0 = next(i for i in range(nbr) if 0 < mask2[i].sum() < nbc)          # a block-row with kept and pruned blocks
+    m0, n0 = i0 * br + (br // 2), 7
+    clean = oracle.dw(oracle.mask_dense(X, br, bc, o_mask), dY)           # the reference without the inf
+    dYf = synth.to_f64(dY) if dtype == "bf16" else dY.astype(np.float64)
+    xhat = synth.to_f64(oracle.mask_dense(X, br, bc, o_mask)) if dtype == "bf16" else oracle.mask_dense(X, br, bc, o_mask).astype(np.float64)
+    without_row = clean[:, n0] - xhat[m0, :] * dYf[m0, n0]                # column n0 without row m0's term
+    bad = dY.copy()
+    if dtype == "bf16":
+        bad[m0, n0] = 0x7F80                                              # +inf in bfloat16
+    else:
+        bad[m0, n0] = np.inf
+    rp, ci = torch.from_numpy(o_rp).cuda(), torch.from_numpy(o_ci).cuda()
+    val = to_dev(o_val.reshape(-1, bc)).reshape(o_val.shape)
+    got = B.bsr_t_dense_matmul(rp, ci, val, M, K, br, bc, to_dev(bad)).cpu().numpy().astype(np.float64)
+    scale = float(np.max(np.abs(clean)))
+    other = np.delete(np.arange(N), n0)
+    assert np.all(np.isfinite(got[:, other]))
+    assert np.max(np.abs(got[:, other] - clean[:, other])) <= DW_TOL_DERIVED * scale
+    nan_rows = 0
+    for k in range(K):
+        j = k // bc
+        x = xhat[m0, k]
+        if mask2[i0, j] and x != 0.0:
+            assert got[k, n0] == np.sign(x) * np.inf, (k, got[k, n0])
+        elif not mask2[i0, j]:
+            if np.isnan(got[k, n0]):
+                nan_rows += 1
+                assert not skips, f"row {k} of a pruned {br}x{bc} block is NaN"
+            else:
+                assert abs(got[k, n0] - without_row[k]) <= DW_TOL_DERIVED * scale, (k, got[k, n0], without_row[k])
+    print(f"[case] {br}x{bc} {dtype}: {nan_rows} rows of pruned blocks are NaN", flush=True)
+
+
+def test_selection_of_near_ties_and_permuted_blocks():
+    """What the library guarantees for scores that are equal or nearly equal.  Blocks that hold the
+    same values in another order have the same sum of squares in exact arithmetic; with small
+    integers every partial sum is exact in binary64 whatever the order, so both sides see an exact
+    tie and the lower index wins.  A block that is larger by one unit in the last place of the score
+    (2^-52 relative) wins over its twin on both sides as long as the sums themselves are exact, which
+    they are for values whose squares need few bits."""
+    rng = np.random.default_rng(11)
+    br = bc = 16
+    nbr, nbc = 32, 16
+    base = rng.integers(-7, 8, size=(br, bc)).astype(np.float32)
+    X = np.zeros((nbr * br, nbc * bc), dtype=np.float32)
+    for i in range(nbr):
+        for j in range(nbc):
+            blk = base.copy().reshape(-1)
+            rng.shuffle(blk)                                             # same multiset, another order
+            X[i * br:(i + 1) * br, j * bc:(j + 1) * bc] = blk.reshape(br, bc)
+    # a few blocks get one element nudged so that the sum of squares grows by a part in 2^40: exact in
+    # binary64 (the squares are small integers plus a tiny power of two), invisible in binary32 sums
+    favoured = [(3, 5), (17, 2), (30, 15)]
+    for (i, j) in favoured:
+        blk = X[i * br:(i + 1) * br, j * bc:(j + 1) * bc]
+        r, c = np.argwhere(blk == 0)[0]
+        blk[r, c] = np.float32(2.0 ** -12)                               # the sum of squares grows by 2^-24
+    for keep in (3 / 512, 0.25, 0.5):
+        o_scores, o_mask, _, _, _ = oracle.prune(X, br, bc, keep)
+        assert len(np.unique(o_scores)) == 2
+        if keep == 3 / 512:                                              # exactly the three nudged blocks
+            assert sorted(np.flatnonzero(o_mask)) == sorted(i * nbc + j for i, j in favoured)
+        mask = B.bsr_score_select(torch.from_numpy(X).cuda(), br, bc, keep).cpu().numpy()
+        assert np.array_equal(mask, o_mask), np.flatnonzero(mask != o_mask)[:8]
+
+
 PACK_BATCH = [
     # M, K, br, bc, keep
     (2048, 384, 32, 32, 0.5),           # direct kernels, 16-byte vectors
