@@ -428,19 +428,16 @@ def main():
     # 196, so fc1 / fc2 use groups of 8 samples = 49 block-rows.  Not part of the timed step.
     next_rows = None
     if not args.no_next_rows:
-        one_ws = torch.empty(max(max(B.bsr_workspace_bytes(op, t["spec"].M, t["spec"].K, t["spec"].N, t["spec"].br,
-                                                           t["spec"].bc, B.dtype_code(t["X"].dtype))
-                                     for op in range(4)) for t in tensors[:3]) or 256,
-                             dtype=torch.uint8, device=dev)
-        mask_g = torch.empty(max(t["spec"].nblocks for t in tensors), dtype=torch.uint8, device=dev)
+        # (masks of their own: the step's masks stay what the parity check expects)
+        grp_sel = B.SelectBatch([t["X"] for t in tensors], [(t["spec"].br, t["spec"].bc) for t in tensors],
+                                [t["spec"].keep for t in tensors])
+        grp_rows = [14 if t["spec"].br == 14 else 49 for t in tensors]
+        grp_ws = torch.empty(max(grp_sel.ws_bytes, 256), dtype=torch.uint8, device=dev)
 
         def grouped_all():
-            for t in tensors:
-                s = t["spec"]
-                B.bsr_score_select_grouped(t["X"], s.br, s.bc, 14 if s.br == 14 else 49, s.keep,
-                                           keep_mask=mask_g[:s.nblocks], ws=one_ws)
+            B.bsr_score_select_grouped_batched(grp_sel, grp_rows, ws=grp_ws)
 
-        grouped = clock(grouped_all, reps=max(args.phase_reps // 5, 3))
+        grouped = clock(grouped_all)
 
         # 1 x b row segments (the block shape Table II's overheads imply) and b = K, at the fc1 shape
         def row_segments(bc):

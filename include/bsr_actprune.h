@@ -213,7 +213,7 @@ int bsr_decompress(const int32_t *row_ptr, const int32_t *col_idx,
  * shape -- 1 x b row segments, b = K, rectangular blocks -- is first re-tiled into
  * 32x32 blocks inside the workspace; the workspace size reported for such a shape
  * includes that copy (about M*K elements).
- * col_idx must ascend inside a block-row or not: any order is accepted.
+ * col_idx may be in any order inside a block-row.
  * Non-finite dY: a 32x32 or 64x64 block that was pruned is never multiplied, so an
  * inf or NaN of dY reaches only the rows of dW that belong to kept blocks of its
  * block-row.  For every other block shape the kept blocks are multiplied inside
@@ -254,6 +254,19 @@ size_t bsr_score_select_batched_workspace_bytes(const bsr_select_item *items,
 
 int bsr_score_select_batched(const bsr_select_item *items, int n, int dtype,
                              void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Sec. IV, local ranking, for several tensors per call: item i is ranked like
+ * bsr_score_select_grouped with groups of group_rows[i] block-rows (same masks,
+ * same keep counts per group), and tensors whose groups are of a similar size
+ * share kernel launches.  Workspace and errors as for bsr_score_select_batched
+ * (the same item type and the same workspace size); group_rows[i] < 1 is
+ * BSR_ERR_SHAPE.  `items` and `group_rows` are host arrays, read before the call
+ * returns.
+ */
+int bsr_score_select_grouped_batched(const bsr_select_item *items,
+                                     const int64_t *group_rows, int n, int dtype,
+                                     void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Several weight gradients per call (for instance those of all linear layers whose

@@ -34,6 +34,7 @@ EXPORTS = (
     "bsr_t_dense_matmul_batched", "bsr_t_dense_matmul_batched_workspace_bytes",
     "bsr_compress_batched", "bsr_compress_batched_workspace_bytes", "bsr_decompress_batched",
     "bsr_score_select_static", "bsr_score_select_static_max_blocks", "bsr_static_scratch_init",
+    "bsr_score_select_grouped_batched",
 )
 
 
@@ -87,6 +88,8 @@ def lib() -> C.CDLL:
     l.bsr_score_select_batched_workspace_bytes.argtypes = [vp, i32, i32]
     l.bsr_score_select_batched.restype = i32
     l.bsr_score_select_batched.argtypes = [vp, i32, i32, vp, sz, vp]
+    l.bsr_score_select_grouped_batched.restype = i32
+    l.bsr_score_select_grouped_batched.argtypes = [vp, vp, i32, i32, vp, sz, vp]
     l.bsr_t_dense_matmul_batched_workspace_bytes.restype = sz
     l.bsr_t_dense_matmul_batched_workspace_bytes.argtypes = [vp, i32, i32]
     l.bsr_t_dense_matmul_batched.restype = i32
@@ -383,6 +386,20 @@ def bsr_score_select_batched(batch: SelectBatch, *, ws: Optional[torch.Tensor] =
     rc = lib().bsr_score_select_batched(batch.items, batch.n, batch.dtype, _ptr(ws),
                                         ws.numel() if ws is not None else 0, _stream(stream))
     _check(rc, "bsr_score_select_batched")
+    return batch.keep_masks
+
+
+def bsr_score_select_grouped_batched(batch: SelectBatch, group_rows: Sequence[int], *,
+                                     ws: Optional[torch.Tensor] = None, stream=None):
+    """-> list of keep masks, the same as bsr_score_select_grouped tensor by tensor with group_rows[i]."""
+    if len(group_rows) != batch.n:
+        raise ValueError("one group size per tensor")
+    if ws is None:
+        ws = _workspace(batch.ws_bytes, batch.device, None)
+    rows = (C.c_int64 * batch.n)(*[int(r) for r in group_rows])
+    rc = lib().bsr_score_select_grouped_batched(batch.items, rows, batch.n, batch.dtype, _ptr(ws),
+                                                ws.numel() if ws is not None else 0, _stream(stream))
+    _check(rc, "bsr_score_select_grouped_batched")
     return batch.keep_masks
 
 

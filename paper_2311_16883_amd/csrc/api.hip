@@ -322,6 +322,46 @@ int bsr_score_select_batched(const bsr_select_item *items, int n, int dtype, voi
   return launch_select_batched(select_jobs.data(), (int)select_jobs.size(), s);
 }
 
+int bsr_score_select_grouped_batched(const bsr_select_item *items, const int64_t *group_rows, int n, int dtype,
+                                     void *ws, size_t ws_bytes, void *stream) {
+  if (n < 0) return BSR_ERR_SHAPE;
+  if (n == 0) return BSR_OK;
+  if (items == nullptr || group_rows == nullptr) return BSR_ERR_NULL;
+  if (misaligned(ws, 16)) return BSR_ERR_ALIGN;
+  std::vector<ScoreJob> score_jobs;
+  std::vector<GroupedSelectJob> select_jobs;
+  score_jobs.reserve(n);
+  select_jobs.reserve(n);
+  size_t off = 0;
+  for (int i = 0; i < n; ++i) {
+    const bsr_select_item &it = items[i];
+    Geometry g;
+    const int rc = check_shape(dtype, it.M, it.K, it.ldx, it.br, it.bc, &g);
+    if (rc != BSR_OK) return rc;
+    if (group_rows[i] < 1) return BSR_ERR_SHAPE;
+    if (!(it.keep >= 0.0 && it.keep <= 1.0)) return BSR_ERR_KEEP;
+    if (g.nblocks == 0) continue;
+    if (it.X == nullptr || it.keep_mask == nullptr) return BSR_ERR_NULL;
+    if (misaligned(it.X, elem_bytes(dtype)) || misaligned(it.scores, 8)) return BSR_ERR_ALIGN;
+    const size_t need = align_up(score_select_ws(g.nblocks), 256);
+    if (ws == nullptr || off + need > ws_bytes) return BSR_ERR_WORKSPACE;
+    char *base = static_cast<char *>(ws) + off;
+    off += need;
+    double *sc = it.scores != nullptr ? it.scores : reinterpret_cast<double *>(base);
+    const int64_t rows = group_rows[i] > g.nbr ? g.nbr : group_rows[i];
+    const int64_t groups = (g.nbr + rows - 1) / rows;
+    const int64_t last_rows = g.nbr - (groups - 1) * rows;
+    score_jobs.push_back(ScoreJob{it.X, it.M, it.K, it.ldx, it.br, it.bc, sc});
+    select_jobs.push_back(GroupedSelectJob{sc, g.nbr, g.nbc, rows, bsr_keep_count(rows * g.nbc, it.keep),
+                                           bsr_keep_count(last_rows * g.nbc, it.keep), it.keep_mask,
+                                           base + scores_bytes(g.nblocks)});
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int rc = launch_score_batched(score_jobs.data(), (int)score_jobs.size(), dtype, s);
+  if (rc != BSR_OK) return rc;
+  return launch_select_grouped_batched(select_jobs.data(), (int)select_jobs.size(), s);
+}
+
 size_t bsr_t_dense_matmul_batched_workspace_bytes(const bsr_matmul_item *items, int n, int dtype) {
   if (items == nullptr || n <= 0) return 0;
   size_t total = 0;

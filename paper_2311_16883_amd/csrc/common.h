@@ -69,6 +69,15 @@ int launch_select_grouped(const double *scores, int64_t nbr, int64_t nbc, int64_
                           int64_t n_keep_group, int64_t n_keep_last, uint8_t *keep_mask, void *ws,
                           hipStream_t s);
 
+// ... of several tensors, those with groups of a similar size sharing launches
+struct GroupedSelectJob {
+  const double *scores;
+  int64_t nbr, nbc, group_rows, n_keep_group, n_keep_last;
+  uint8_t *mask;
+  void *ws;            // select_ws_bytes(nbr * nbc) bytes of its own
+};
+int launch_select_grouped_batched(const GroupedSelectJob *jobs, int n, hipStream_t s);
+
 // pack.hip
 int launch_index_build(const uint8_t *keep_mask, int64_t nbr, int64_t nbc, int64_t n_keep,
                        int32_t *row_ptr, int32_t *col_idx, hipStream_t s);

@@ -420,6 +420,29 @@ __global__ __launch_bounds__(THREADS) void select_groups_kernel(
                                      last ? n_keep_last : n_keep_group, mask + off);
 }
 
+// Per-group selection of several tensors in one launch: tensor k owns the workgroups
+// [wg_begin_k, wg_begin_k + groups_k), one workgroup per group.
+constexpr int kGroupBatchMax = 24;
+struct GroupItem {
+  const double *scores;
+  uint8_t *mask;
+  uint32_t group_blocks, n_keep_group, last_blocks, n_keep_last, groups, wg_begin;
+};
+struct GroupBatch {
+  GroupItem it[kGroupBatchMax];
+};
+template <int THREADS, int KPT, int DB>
+__global__ __launch_bounds__(THREADS) void select_groups_batched_kernel(GroupBatch b, int n) {
+  int k = 0;
+  while (k + 1 < n && blockIdx.x >= b.it[k + 1].wg_begin) ++k;
+  const GroupItem &it = b.it[k];
+  const uint32_t g = blockIdx.x - it.wg_begin;
+  const bool last = g == it.groups - 1;
+  const size_t off = (size_t)g * it.group_blocks;
+  select_one_group<THREADS, KPT, DB>(it.scores + off, last ? it.last_blocks : it.group_blocks,
+                                     last ? it.n_keep_last : it.n_keep_group, it.mask + off);
+}
+
 // Control block shared by the two grid-wide passes (lives in the workspace;
 // written by workgroup 0 of pass 1).
 struct SelectCtrl {
@@ -913,6 +936,61 @@ int launch_select_batched(const SelectJob *jobs, int n, hipStream_t s) {
         if (it.wgs > max_wgs) max_wgs = it.wgs;
       }
       if (++m == kBatchMax) {
+        const int rc = flush();
+        if (rc != BSR_OK) return rc;
+      }
+    }
+    const int rc = flush();
+    if (rc != BSR_OK) return rc;
+  }
+  return BSR_OK;
+}
+
+int launch_select_grouped_batched(const GroupedSelectJob *jobs, int n, hipStream_t s) {
+  // classes by blocks per group: 0 <= 1024, 1 <= 8192, 2 <= kSmallLimit (one workgroup per group, the
+  // tensors of a class share launches); a tensor of one group or of larger groups goes on its own
+  for (int cls = 0; cls < 3; ++cls) {
+    GroupBatch b;
+    int m = 0;
+    uint32_t wgs = 0;
+    auto flush = [&]() -> int {
+      if (m == 0) return BSR_OK;
+      if (cls == 0)
+        hipLaunchKernelGGL((select_groups_batched_kernel<256, 4, 8>), dim3(wgs), dim3(256), 0, s, b, m);
+      else if (cls == 1)
+        hipLaunchKernelGGL((select_groups_batched_kernel<1024, 8, kDigitBits>), dim3(wgs), dim3(1024), 0, s, b, m);
+      else
+        hipLaunchKernelGGL((select_groups_batched_kernel<1024, 12, kDigitBits>), dim3(wgs), dim3(1024), 0, s, b, m);
+      m = 0;
+      wgs = 0;
+      return check_launch();
+    };
+    for (int i = 0; i < n; ++i) {
+      const GroupedSelectJob &j = jobs[i];
+      if (j.nbr == 0 || j.nbc == 0) continue;
+      const int64_t groups = ceil_div(j.nbr, j.group_rows);
+      const int64_t group_blocks = j.group_rows * j.nbc;
+      const int c = groups == 1 || group_blocks > kSmallLimit ? -1 : (group_blocks <= 1024 ? 0 : (group_blocks <= 8192 ? 1 : 2));
+      if (c == -1) {
+        if (cls == 0) {
+          const int rc = launch_select_grouped(j.scores, j.nbr, j.nbc, j.group_rows, j.n_keep_group, j.n_keep_last,
+                                               j.mask, j.ws, s);
+          if (rc != BSR_OK) return rc;
+        }
+        continue;
+      }
+      if (c != cls) continue;
+      GroupItem &it = b.it[m];
+      it.scores = j.scores;
+      it.mask = j.mask;
+      it.group_blocks = (uint32_t)group_blocks;
+      it.n_keep_group = (uint32_t)j.n_keep_group;
+      it.last_blocks = (uint32_t)((j.nbr - (groups - 1) * j.group_rows) * j.nbc);
+      it.n_keep_last = (uint32_t)j.n_keep_last;
+      it.groups = (uint32_t)groups;
+      it.wg_begin = wgs;
+      wgs += (uint32_t)groups;
+      if (++m == kGroupBatchMax) {
         const int rc = flush();
         if (rc != BSR_OK) return rc;
       }

@@ -240,6 +240,46 @@ def test_grouped_selection_parity(M, K, br, bc, group_rows, keep):
         assert to_host(values).tobytes() == o_val.tobytes()
 
 
+GROUPED_BATCH = [
+    # M, K, br, bc, group_rows, keep
+    (2744, 196, 14, 14, 14, 0.5),        # 196 blocks per group
+    (6272, 384, 32, 32, 49, 0.5),        # 588 blocks per group: shares the launch of the first
+    (6272, 1536, 32, 32, 49, 0.25),      # 2352 blocks per group: the 1024-thread workgroups
+    (1000, 200, 8, 8, 7, 0.3),           # ragged rows / columns, ragged last group
+    (8192, 512, 16, 16, 300, 0.5),       # 9600 blocks per group: twelve keys per thread
+    (8192, 512, 16, 16, 400, 0.5),       # 12800 blocks per group: on its own, group after group
+    (512, 128, 16, 16, 64, 0.6),         # one group: the ungrouped selection
+    (640, 128, 16, 16, 8, 0.0),          # nothing kept
+    (640, 128, 16, 16, 8, 1.0),          # everything kept
+]
+
+
+def test_batched_grouped_selection_equals_single_calls_and_oracle():
+    """Sec. IV, local ranking, several tensors per call: the masks of bsr_score_select_grouped tensor by
+    tensor, and of the oracle's per-group selection."""
+    rng = np.random.default_rng(41)
+    Xs, hosts = [], []
+    for (M, K, br, bc, rows, keep) in GROUPED_BATCH:
+        X = synth.f32_to_bf16_bits(rng.standard_normal((M, K), dtype=np.float32))
+        hosts.append(X)
+        Xs.append(to_dev(X))
+    batch = B.SelectBatch(Xs, [(c[2], c[3]) for c in GROUPED_BATCH], [c[5] for c in GROUPED_BATCH])
+    masks = B.bsr_score_select_grouped_batched(batch, [c[4] for c in GROUPED_BATCH])
+    torch.cuda.synchronize()
+    for (M, K, br, bc, rows, keep), X, Xd, mask in zip(GROUPED_BATCH, hosts, Xs, masks):
+        nbr, nbc = oracle.grid(M, K, br, bc)
+        if nbr * nbc == 0:
+            continue
+        o_mask, total = oracle.select_grouped(oracle.block_scores(X, br, bc), nbr, nbc, rows, keep)
+        single = B.bsr_score_select_grouped(Xd, br, bc, rows, keep)
+        torch.cuda.synchronize()
+        assert np.array_equal(mask.cpu().numpy(), single.cpu().numpy()), (M, K, br, bc, rows, keep)
+        assert np.array_equal(mask.cpu().numpy(), o_mask), (M, K, br, bc, rows, keep)
+        assert int(mask.sum()) == total
+    with pytest.raises(B.BsrError):
+        B.bsr_score_select_grouped_batched(batch, [0] * len(GROUPED_BATCH))
+
+
 def test_nan_inf_and_signed_zero_blocks():
     X, _ = rand_pair(128, 128, 8, "f32", seed=3)
     X[5, 5] = np.nan

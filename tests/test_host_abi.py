@@ -23,7 +23,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     syms = declared_symbols()
-    assert set(syms) == set(B.EXPORTS) and len(syms) == 23
+    assert set(syms) == set(B.EXPORTS) and len(syms) == 24
     lib = B.lib()
     for s in syms:
         assert getattr(lib, s) is not None
