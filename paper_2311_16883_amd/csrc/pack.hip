@@ -185,6 +185,7 @@ struct CompressArgs {
   int64_t M, kb, ldb, bcb, nbr, nbc, n_keep;
   int br;
   uint32_t wg_begin;       // first workgroup of this tensor in a launch of several
+  int have_row_ptr;        // row_ptr was written by row_ptr_batched_kernel: nothing to count here
 };
 
 // i = block-row (the workgroup's number among those of its tensor)
@@ -202,7 +203,7 @@ __device__ __forceinline__ void compress_body(const CompressArgs &a, const int64
   __shared__ uint32_t total;
   __shared__ int32_t kept_j[kFusedCols];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const uint32_t prefix = count_kept_prefix(mask, i * nbc, wave_tot, &total);
+  const uint32_t prefix = a.have_row_ptr ? (uint32_t)row_ptr[i] : count_kept_prefix(mask, i * nbc, wave_tot, &total);
 
   // ---- this row's kept block-columns, in order ----
   uint32_t row_kept = 0;
@@ -223,7 +224,7 @@ __device__ __forceinline__ void compress_body(const CompressArgs &a, const int64
     row_kept += wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
     __syncthreads();
   }
-  if (t == 0) {
+  if (t == 0 && !a.have_row_ptr) {
     row_ptr[i] = (int32_t)prefix;
     if (i == nbr - 1) row_ptr[nbr] = (int32_t)(prefix + row_kept);
   }
@@ -419,6 +420,81 @@ __global__ __launch_bounds__(256) void span_count_kernel(const uint8_t *__restri
   if (lane == 0) wg_kept[w] = cnt;
 }
 
+// row_ptr of several tensors in one launch, one workgroup of 1024 threads per tensor: the mask is
+// read front to back, 16 blocks per thread and pass, with a running count of the kept blocks in
+// front of every block (lane exchanges inside a wave, the waves' totals through LDS); the thread
+// that holds the first block of a block-row writes that row's entry.  With row_ptr at hand the
+// conversion kernels need not count the mask in front of their rows (every workgroup on its own,
+// out of L2: more bytes than the tensor itself for narrow blocks).
+constexpr int kRowPtrThreads = 1024;
+constexpr int kRowPtrBatchMax = 40;
+constexpr int64_t kRowPtrMaxBlocks = int64_t(1) << 22;     // one workgroup reads the whole mask
+struct RowPtrItem {
+  const uint8_t *mask;
+  int32_t *row_ptr;
+  int64_t nbr, nbc;
+};
+struct RowPtrBatch {
+  RowPtrItem it[kRowPtrBatchMax];
+};
+__global__ __launch_bounds__(kRowPtrThreads) void row_ptr_batched_kernel(RowPtrBatch b) {
+  const RowPtrItem &it = b.it[blockIdx.x];
+  const uint8_t *__restrict__ mask = it.mask;
+  int32_t *__restrict__ row_ptr = it.row_ptr;
+  const uint32_t nbc = (uint32_t)it.nbc;
+  const uint32_t nblocks = (uint32_t)(it.nbr * it.nbc);
+  constexpr int kPer = 16;                                  // blocks per thread and pass
+  __shared__ uint32_t wave_tot[2][kRowPtrThreads / 64];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  uint32_t base = 0;                                        // kept blocks in front of this pass
+  const bool aligned = reinterpret_cast<uintptr_t>(mask) % 16 == 0;
+  int phase = 0;
+  for (uint32_t e0 = 0; e0 < nblocks; e0 += kPer * kRowPtrThreads, phase ^= 1) {
+    const uint32_t first = e0 + (uint32_t)t * kPer;
+    uint8_t f[kPer];
+    if (aligned && first + kPer <= nblocks) {
+      const uint4 v = *reinterpret_cast<const uint4 *>(mask + first);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int k = 0; k < kPer; ++k) f[k] = (uint8_t)(w[k >> 2] >> (8 * (k & 3)));
+    } else {
+#pragma unroll
+      for (int k = 0; k < kPer; ++k) f[k] = first + k < nblocks ? mask[first + k] : (uint8_t)0;
+    }
+    uint32_t mine = 0;
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) mine += f[k] != 0 ? 1u : 0u;
+    uint32_t incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t up = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += up;
+    }
+    if (lane == 63) wave_tot[phase][wave] = incl;
+    __syncthreads();
+    uint32_t before = base, all = 0;
+#pragma unroll
+    for (int w = 0; w < kRowPtrThreads / 64; ++w) {
+      if (w < wave) before += wave_tot[phase][w];
+      all += wave_tot[phase][w];
+    }
+    uint32_t run = before + incl - mine;
+    if (first < nblocks) {
+      uint32_t r = first / nbc, c = first - r * nbc;        // block-row and column of the thread's first block
+#pragma unroll
+      for (int k = 0; k < kPer; ++k) {
+        if (first + k < nblocks) {
+          if (c == 0) row_ptr[r] = (int32_t)run;
+          run += f[k] != 0 ? 1u : 0u;
+          if (++c == nbc) { c = 0; ++r; }
+        }
+      }
+    }
+    base += all;
+  }
+  if (t == 0) row_ptr[it.nbr] = (int32_t)base;
+}
+
 struct CompressSpanArgs {
   const uint8_t *mask, *X;
   const uint32_t *wg_kept;  // kept blocks of every workgroup's mask range, or null (see span_count_kernel)
@@ -428,6 +504,7 @@ struct CompressSpanArgs {
   SpanGeom g;
   uint32_t span_words;
   uint32_t wg_begin;        // first workgroup of this tensor in a launch of several
+  int have_row_ptr;         // row_ptr was written by row_ptr_batched_kernel: nothing to count here
 };
 
 // wg = the workgroup's number among those of its tensor
@@ -465,7 +542,9 @@ __device__ __forceinline__ void compress_span_body(const CompressSpanArgs &a, co
   // kept blocks in front of this workgroup: from the mask itself, or from the per-workgroup
   // counts of span_count_kernel when the mask is too long to re-read in every workgroup
   uint32_t prefix;
-  if (wg_kept == nullptr) {
+  if (a.have_row_ptr) {
+    prefix = (uint32_t)row_ptr[i0];
+  } else if (wg_kept == nullptr) {
     prefix = count_kept_prefix(mask, i0 * g.nbc, wave_tot, &total);
   } else {
     uint32_t cnt = 0;
@@ -493,7 +572,7 @@ __device__ __forceinline__ void compress_span_body(const CompressSpanArgs &a, co
     const uint32_t pos = before + (uint32_t)__popcll(ball & ((1ull << lane) - 1ull));
     if (idx < nblk) {
       const uint32_t b = span_div((uint32_t)idx, (uint32_t)g.nbc, g.magic_nbc), j = (uint32_t)idx - b * g.nbc;
-      if (j == 0) row_ptr[i0 + b] = (int32_t)(prefix + pos);
+      if (j == 0 && !a.have_row_ptr) row_ptr[i0 + b] = (int32_t)(prefix + pos);
       if (flag) {
         base[pos] = b * g.br * g.row_words + j * g.seg_words;
         lim[pos] = span_lim(g, rows, b, j);
@@ -503,7 +582,7 @@ __device__ __forceinline__ void compress_span_body(const CompressSpanArgs &a, co
     kept += wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
     __syncthreads();
   }
-  if (t == 0 && i0 + nb == nbr) row_ptr[nbr] = (int32_t)(prefix + kept);
+  if (t == 0 && i0 + nb == nbr && !a.have_row_ptr) row_ptr[nbr] = (int32_t)(prefix + kept);
   V *sv = reinterpret_cast<V *>(span);
 #pragma unroll
   for (int k = 0; k < kVecs; ++k)
@@ -743,7 +822,7 @@ CompressPlan plan_compress(const CompressJob &j, int dtype) {
     p.count_first = compress_ws_bytes(dtype, j.M, j.K, j.br, j.bc) != 0;
     p.span = CompressSpanArgs{j.keep_mask, static_cast<const uint8_t *>(j.X),
                               p.count_first ? static_cast<const uint32_t *>(j.ws) : nullptr, j.row_ptr, j.col_idx,
-                              static_cast<uint32_t *>(j.values), j.M, nbr, j.n_keep, g, (uint32_t)span_words, 0u};
+                              static_cast<uint32_t *>(j.values), j.M, nbr, j.n_keep, g, (uint32_t)span_words, 0u, 0};
     return p;
   }
   // one fused launch when a block-row's columns fit its LDS list and re-reading the
@@ -759,7 +838,7 @@ CompressPlan plan_compress(const CompressJob &j, int dtype) {
   p.wgs = (unsigned)nbr;
   p.direct = CompressArgs{j.keep_mask, static_cast<const uint8_t *>(j.X), j.row_ptr, j.col_idx,
                           static_cast<uint8_t *>(j.values), j.M, j.K * e, j.ldx * e, (int64_t)j.bc * e, nbr, nbc,
-                          j.n_keep, j.br, 0u};
+                          j.n_keep, j.br, 0u, 0};
   return p;
 }
 
@@ -876,6 +955,38 @@ int launch_compress_batched(const CompressJob *jobs, int n, int dtype, hipStream
   static const int kVbs[4] = {16, 8, 4, 2};
   std::vector<CompressPlan> plans((size_t)n);
   for (int i = 0; i < n; ++i) plans[(size_t)i] = plan_compress(jobs[i], dtype);
+  // with several tensors in the call one more launch costs little next to what it saves: row_ptr of
+  // every tensor first, one workgroup per tensor
+  if (n >= 2) {
+    RowPtrBatch rb;
+    int m = 0;
+    auto flush_rows = [&]() -> int {
+      if (m == 0) return BSR_OK;
+      hipLaunchKernelGGL(row_ptr_batched_kernel, dim3(m), dim3(kRowPtrThreads), 0, s, rb);
+      m = 0;
+      return check_launch();
+    };
+    for (int i = 0; i < n; ++i) {
+      CompressPlan &p = plans[(size_t)i];
+      const CompressJob &j = jobs[i];
+      const int64_t nbr = ceil_div(j.M, j.br), nbc = ceil_div(j.K, j.bc);
+      if (p.path == kPackOther || p.wgs == 0 || nbr * nbc > kRowPtrMaxBlocks) continue;
+      rb.it[m] = RowPtrItem{j.keep_mask, j.row_ptr, nbr, nbc};
+      if (p.path == kPackSpan) {
+        p.span.have_row_ptr = 1;
+        p.span.wg_kept = nullptr;
+        p.count_first = false;
+      } else {
+        p.direct.have_row_ptr = 1;
+      }
+      if (++m == kRowPtrBatchMax) {
+        const int rc = flush_rows();
+        if (rc != BSR_OK) return rc;
+      }
+    }
+    const int rc = flush_rows();
+    if (rc != BSR_OK) return rc;
+  }
   for (int path = kPackSpan; path <= kPackDirect; ++path) {
     for (int vi = 0; vi < 4; ++vi) {
       const int vb = kVbs[vi];

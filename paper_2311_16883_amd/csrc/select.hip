@@ -704,7 +704,7 @@ __global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
 // per selection) naming the selection; its parameters come from the kernel
 // arguments.  Selection is bound by launch and fence latency, not by work, so a
 // batch costs about as much as one selection.
-constexpr int kBatchMax = 24;
+constexpr int kBatchMax = 40;
 struct SelectItem {
   const double *scores;
   uint8_t *mask;
@@ -751,6 +751,7 @@ __global__ void fill_u8_kernel(uint8_t *p, int64_t n, uint8_t v) {
 }
 
 constexpr int64_t kSmallLimit = 12288;     // one workgroup (up to 12 keys per thread)
+constexpr int64_t kRideAlong = 4096;       // smallest tensor that the grid-wide passes of a batched call take along
 
 constexpr int kMaxGridWgs = 256;
 
@@ -770,8 +771,9 @@ SelectPlan select_plan(int64_t nblocks) {
 
 }  // namespace
 
+// (tensors of more than kRideAlong blocks may join the grid-wide passes of a batched call)
 size_t select_ws_bytes(int64_t nblocks) {
-  return nblocks > kSmallLimit ? select_plan(nblocks).total : 0;
+  return nblocks > kRideAlong ? select_plan(nblocks).total : 0;
 }
 
 int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t *keep_mask, void *ws,
@@ -854,7 +856,15 @@ int launch_select_grouped(const double *scores, int64_t nbr, int64_t nbc, int64_
 
 int launch_select_batched(const SelectJob *jobs, int n, hipStream_t s) {
   // classes: 0 one workgroup <= 1024 blocks, 1 <= 8192, 2 <= 12288, 3 grid-wide with the
-  // 64-key sample, 4 grid-wide with the 256-key sample; everything else goes one by one
+  // 64-key sample, 4 grid-wide with the 256-key sample; everything else goes one by one.
+  // The launches of the classes run one after the other and each is bound by latency, not
+  // work: when the grid-wide passes run anyway, mid-sized tensors join them instead of
+  // having a launch of one-workgroup selections of their own.
+  bool grid_wide_runs = false;
+  for (int i = 0; i < n; ++i)
+    if (jobs[i].nblocks > kSmallLimit && jobs[i].nblocks <= 262144 && jobs[i].n_keep > 0 &&
+        jobs[i].n_keep < jobs[i].nblocks)
+      grid_wide_runs = true;
   for (int cls = 0; cls < 5; ++cls) {
     SelectBatch b;
     int m = 0;
@@ -899,6 +909,7 @@ int launch_select_batched(const SelectJob *jobs, int n, hipStream_t s) {
       int c;
       if (degenerate) c = -1;
       else if (j.nblocks <= 1024) c = 0;
+      else if (grid_wide_runs && j.nblocks > kRideAlong) c = 3;
       else if (j.nblocks <= 8192) c = 1;
       else if (j.nblocks <= kSmallLimit) c = 2;
       else if (j.nblocks <= 262144) c = 3;

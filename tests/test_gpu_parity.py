@@ -491,6 +491,7 @@ BATCH_BF16 = [
     (25088, 384, 32, 32, 0.5),      # 9408 blocks: twelve keys per thread
     (6272, 1536, 32, 32, 0.25),     # 9408 blocks again, another keep ratio
     (8192, 1536, 32, 32, 0.5),      # 12288 blocks: the last single-workgroup size
+    (4480, 1024, 32, 32, 0.4),      # 4480 blocks: the smallest that ride along with the grid-wide passes of a batch
     (12544, 1536, 32, 32, 0.5),     # 18816 blocks: grid-wide passes
     (4096, 1536, 8, 8, 0.9),        # 98304 blocks: grid-wide, long slices
     (3000, 384, 1, 32, 0.5),        # row segments: scored one by one inside the call
