@@ -57,6 +57,14 @@ int64_t wide_parallelism(int64_t M, int64_t K, int64_t N, int br) {
   return ceil_div(K, 384) * ceil_div(N, 128) * (nbr < 16 ? nbr : 16);
 }
 
+// Small square blocks and a small weight matrix (the cross-patch layers) in a batched call: the kernel whose
+// workgroups own all of dW, once the contraction is long enough to split over a few of them.  (A product on
+// its own would need so many splits to fill the GPU that the narrow-tile kernel is the faster one.)
+bool use_narrow(int dtype, int br, int bc, const void *values, const void *dY, int64_t M, int64_t K, int64_t N,
+                int64_t lddy) {
+  return dw_narrow_supported(dtype, br, bc, values, dY, M, K, N, lddy) && ceil_div(M, br) >= 16;
+}
+
 bool use_wide_single(int dtype, int br, int bc, const void *values, const void *dY, int64_t M, int64_t K, int64_t N,
                      int64_t lddy) {
   return dw_wide_supported(dtype, br, bc, values, dY, M, K, N, lddy) && wide_parallelism(M, K, N, br) >= 128;
@@ -124,6 +132,10 @@ size_t bsr_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int br, int 
           if (b > a) a = b;
         } else if (dw_reblock_supported(dtype, br, bc, M, K, N, N)) {
           const size_t b = dw_reblock_ws_bytes(dtype, M, K, N);
+          if (b > a) a = b;
+        }
+        if (dw_narrow_supported(dtype, br, bc, nullptr, nullptr, M, K, N, N)) {
+          const size_t b = dw_narrow_ws_bytes(M, K, N, br);
           if (b > a) a = b;
         }
         return align_up(a, 256);
@@ -380,7 +392,7 @@ int bsr_t_dense_matmul_batched(const bsr_matmul_item *items, int n, int dtype, v
   if (n == 0) return BSR_OK;
   if (items == nullptr) return BSR_ERR_NULL;
   if (misaligned(ws, 16)) return BSR_ERR_ALIGN;
-  std::vector<DwJob> batch, single, wide;
+  std::vector<DwJob> batch, single, wide, narrow;
   batch.reserve(n);
   int64_t wide_par = 0;
   size_t off = 0;
@@ -401,7 +413,9 @@ int bsr_t_dense_matmul_batched(const bsr_matmul_item *items, int n, int dtype, v
     const DwJob job{it.row_ptr, it.col_idx, it.values, it.M, it.K, it.br, it.bc, it.dY, it.N, it.lddy, it.dW,
                     it.lddw, it.accumulate, need > 0 ? static_cast<char *>(ws) + off : nullptr, need};
     off += need;
-    if (dw_wide_supported(dtype, it.br, it.bc, it.values, it.dY, it.M, it.K, it.N, it.lddy)) {
+    if (n > 1 && use_narrow(dtype, it.br, it.bc, it.values, it.dY, it.M, it.K, it.N, it.lddy)) {
+      narrow.push_back(job);
+    } else if (dw_wide_supported(dtype, it.br, it.bc, it.values, it.dY, it.M, it.K, it.N, it.lddy)) {
       wide.push_back(job);
       wide_par += wide_parallelism(it.M, it.K, it.N, it.br);
     } else if (dw_mfma_supported(dtype, it.br, it.bc, it.values, it.M, it.K, it.N, it.lddy)) {
@@ -417,6 +431,7 @@ int bsr_t_dense_matmul_batched(const bsr_matmul_item *items, int n, int dtype, v
     wide.clear();
   }
   int rc = launch_dw_wide_batched(wide.data(), (int)wide.size(), s);
+  if (rc == BSR_OK) rc = launch_dw_narrow_batched(narrow.data(), (int)narrow.size(), s);
   if (rc == BSR_OK) rc = launch_dw_mfma_batched(dtype, batch.data(), (int)batch.size(), s);
   for (size_t i = 0; rc == BSR_OK && i < single.size(); ++i) {
     const DwJob &j = single[i];

@@ -198,6 +198,11 @@ struct DwJob {
 int launch_dw_mfma_batched(int dtype, const DwJob *jobs, int n, hipStream_t s);
 
 // dw_wide.hip: bfloat16, 32x32 / 64x64 blocks, 384-row tiles fed by global -> LDS copies.
+// dw_narrow.hip: bfloat16, small square blocks, a weight matrix of at most 224 x 224: one workgroup owns all of dW
+bool dw_narrow_supported(int dtype, int br, int bc, const void *values, const void *dY, int64_t M, int64_t K,
+                         int64_t N, int64_t lddy);
+size_t dw_narrow_ws_bytes(int64_t M, int64_t K, int64_t N, int br);
+int launch_dw_narrow_batched(const DwJob *jobs, int n, hipStream_t s);
 bool dw_wide_supported(int dtype, int br, int bc, const void *values, const void *dY, int64_t M, int64_t K,
                        int64_t N, int64_t lddy);
 size_t dw_wide_ws_bytes(int64_t M, int64_t K, int64_t N, int br);
