@@ -19,10 +19,11 @@
 //    each, read fragments and issue matrix instructions and nothing else.
 //  * Global -> LDS copies are done by the texture path itself (buffer_load ... lds,
 //    16 bytes per lane): no staging registers, no LDS store instructions.  A copy
-//    wave issues four pairs of copies per stage, always: a pruned block is "copied"
-//    from an offset beyond the buffer, which writes zeros into a slab nobody reads
-//    and touches no memory, so the number of copies a wave has in flight does not
-//    depend on the sparsity pattern and the wait for a stage is a constant vmcnt.
+//    wave issues a pair of copies per stage for dY and one for each kept piece among
+//    its three; a pruned piece is not copied (the texture path would spend as long on
+//    a copy from beyond the buffer as on a real one).  The wave keeps count of what it
+//    issued for the stages on their way, and waits for a stage with the vmcnt that
+//    those counts add up to.
 //  * LDS holds a ring of four stages of 32 contraction rows.  An activation piece
 //    is a slab of 32 rows x 32 columns with 64-byte rows -- for 32x32 blocks 2 KB
 //    of `values` exactly as stored -- where the four rows that a 16-lane group of a
@@ -287,28 +288,64 @@ struct WideBody {
         }
         // table columns of the three pieces
         const uint32_t *offp[3] = {sOff + c / SPB, sOff + (c + 4) / SPB, sOff + (c + 8) / SPB};
-        auto issue = [&](uint32_t m0, uint32_t o0, uint32_t o1, uint32_t o2, bool lower_half) {
+        // Issues the copies of one stage and returns how many instructions that were: a pair for each
+        // kept piece of the wave's three (a pruned piece is not copied at all: the texture path spends
+        // as long on a copy from beyond the buffer as on a real one) and a pair for dY.
+        auto issue = [&](uint32_t m0, uint32_t o0, uint32_t o1, uint32_t o2, bool lower_half) -> uint32_t {
           const uint32_t vh = va + ((SPB == 2 && lower_half) ? 32u * kRowBytes : 0u);
-          const uint32_t l0 = o0 + vh, l1 = o1 + vh, l2 = o2 + vh;
-          copy_pair_to_lds(rsrc_a, m0, l0, l0 + a_hi_delta);
-          copy_pair_to_lds(rsrc_a, m0 + 4u * kSlabBytes, l1, l1 + a_hi_delta);
-          copy_pair_to_lds(rsrc_a, m0 + 8u * kSlabBytes, l2, l2 + a_hi_delta);
+          uint32_t n = 2;
+          if ((uint32_t)__builtin_amdgcn_readfirstlane((int)o0) != kBeyond) {
+            const uint32_t l0 = o0 + vh;
+            copy_pair_to_lds(rsrc_a, m0, l0, l0 + a_hi_delta);
+            n += 2;
+          }
+          if ((uint32_t)__builtin_amdgcn_readfirstlane((int)o1) != kBeyond) {
+            const uint32_t l1 = o1 + vh;
+            copy_pair_to_lds(rsrc_a, m0 + 4u * kSlabBytes, l1, l1 + a_hi_delta);
+            n += 2;
+          }
+          if ((uint32_t)__builtin_amdgcn_readfirstlane((int)o2) != kBeyond) {
+            const uint32_t l2 = o2 + vh;
+            copy_pair_to_lds(rsrc_a, m0 + 8u * kSlabBytes, l2, l2 + a_hi_delta);
+            n += 2;
+          }
           copy_pair_to_lds(rsrc_b, m0 + b_lds_delta, vb, vb + b_hi_delta);
           vb += b_step;
+          return n;
         };
+        // Waits until at most `allowed` of this wave's copies are on their way (allowed = 4, 6, .. 16: the
+        // copies of the two stages behind the one that must have landed).
+        auto wait_copies = [&](uint32_t allowed) {
+          if (allowed >= 12u) {
+            if (allowed >= 16u) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+            else if (allowed >= 14u) asm volatile("s_waitcnt vmcnt(14)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+          } else if (allowed >= 8u) {
+            if (allowed >= 10u) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+          } else {
+            if (allowed >= 6u) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+          }
+        };
+        uint32_t cnt[kAhead];                               // copies issued for the stages q .. q + 2
 #pragma unroll
         for (int d = 0; d < kAhead; ++d)
-          issue(m0_slot[d], vector_value(offp[0][(d / SPB) * JT]), vector_value(offp[1][(d / SPB) * JT]),
-                vector_value(offp[2][(d / SPB) * JT]), (d & 1) != 0);
+          cnt[d] = issue(m0_slot[d], vector_value(offp[0][(d / SPB) * JT]), vector_value(offp[1][(d / SPB) * JT]),
+                         vector_value(offp[2][(d / SPB) * JT]), (d & 1) != 0);
+        uint32_t c1 = cnt[1], c2 = cnt[2];                  // of the stages q + 1 and q + 2
         // table entries are read one stage ahead of their use
         uint32_t n0_ = offp[0][(kAhead / SPB) * JT], n1_ = offp[1][(kAhead / SPB) * JT], n2_ = offp[2][(kAhead / SPB) * JT];
         auto stage = [&](auto slot_c) {
           constexpr int slot = decltype(slot_c)::value;                  // stage q = 4 * trip + slot
           constexpr int slot_new = (slot + kAhead) % kRing;              // stage q + 3 goes where stage q - 1 was
-          // the copies of stage q have landed when only those of the stages after it are on their way
-          asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+          // the copies of stage q have landed when only those of the two stages after it are on their way
+          wait_copies(c1 + c2);
           stage_barrier();
-          issue(m0_slot[slot_new], vector_value(n0_), vector_value(n1_), vector_value(n2_), ((slot + kAhead) & 1) != 0);
+          const uint32_t c3 = issue(m0_slot[slot_new], vector_value(n0_), vector_value(n1_), vector_value(n2_),
+                                    ((slot + kAhead) & 1) != 0);
+          c1 = c2;
+          c2 = c3;
           n0_ = offp[0][((slot + kAhead + 1) / SPB) * JT];
           n1_ = offp[1][((slot + kAhead + 1) / SPB) * JT];
           n2_ = offp[2][((slot + kAhead + 1) / SPB) * JT];
