@@ -19,7 +19,7 @@
 // Small inputs (<= 12288 blocks) and per-group selection: one workgroup per
 // ranking group, bracketed_select between the group's smallest and largest key.
 //
-// Large inputs: two grid-wide passes.
+// Large inputs: two grid-wide passes and a one-workgroup finish, three launches.
 //   pass 1  every workgroup draws the same small sample, takes from it two order
 //           statistics lo <= hi that bracket the rank of the threshold, and
 //           counts its slice of the keys into 256 buckets: bucket 0 below lo, the
@@ -30,12 +30,13 @@
 //   pass 2  every workgroup adds up the counts, finds the bucket that holds the
 //           n_keep-th largest key, keeps the buckets above it, prunes the ones
 //           below and appends the keys inside it to a candidate list (one atomic
-//           per workgroup); the last workgroup to finish stages the candidates in
-//           LDS and selects among them exactly, with the bucket's key range as a
-//           bracket: 32-bit codes linear in the key, one 8-bit radix pass as a
-//           rule, then a ranking of the handful that share the threshold's code
-//           through lane reads.  The general radix select remains the fallback
-//           when a bracket misses or too many keys are equal.
+//           per workgroup).
+//   finish  one workgroup stages the candidates in LDS and selects among them
+//           exactly, with the bucket's key range as a bracket: 32-bit codes linear
+//           in the key, one 8-bit radix pass as a rule, then a ranking of the
+//           handful that share the threshold's code through lane reads.  The
+//           general radix select remains the fallback when a bracket misses or
+//           too many keys are equal.
 #include "common.h"
 
 namespace bsr {
@@ -446,7 +447,7 @@ __global__ __launch_bounds__(THREADS) void select_groups_batched_kernel(GroupBat
 // Control block shared by the two grid-wide passes (lives in the workspace;
 // written by workgroup 0 of pass 1).
 struct SelectCtrl {
-  uint32_t ticket, n_cand, shift, pad;
+  uint32_t n_cand, shift;
   uint64_t lo, hi;
 };
 
@@ -523,7 +524,6 @@ __device__ __forceinline__ void select_count_body(
   shift = shift > 8 ? shift - 8 : 0u;
   if ((range >> shift) > (uint64_t)(kBuckets - 3)) ++shift;
   if (wg == 0 && t == 0) {
-    ctrl->ticket = 0;
     ctrl->n_cand = 0;
     ctrl->shift = shift;
     ctrl->lo = lo;
@@ -555,10 +555,10 @@ __global__ __launch_bounds__(kGridThreads) void select_count_kernel(
   select_count_body<NS>(scores, nblocks, n_keep, per_wg, counts, ctrl, blockIdx.x);
 }
 
-// MODE 0: the whole pass in one kernel (the last workgroup to finish, found by an atomic
-// ticket, selects among the candidates).  MODE 1: classification only; MODE 2: only the
-// selection among the candidates, by one workgroup of a later launch -- for batches, where a
-// release fence per workgroup (an L2 write-back on this GPU) costs more than a launch.
+// MODE 1: classification only; MODE 2: only the selection among the candidates, by one
+// workgroup of a later launch.  (One kernel in which the last workgroup to finish, found by an
+// atomic ticket, does the selection needs a release fence in every workgroup -- an L2 write-back
+// on this GPU -- which costs more than the second launch.)
 template <int MODE>
 __device__ __forceinline__ void select_classify_body(
     const double *__restrict__ scores, uint32_t nblocks, uint32_t n_keep, uint32_t per_wg,
@@ -567,7 +567,7 @@ __device__ __forceinline__ void select_classify_body(
     uint32_t wg, uint32_t nwgs) {
   __shared__ SelectShared sh;
   __shared__ BracketShared bs;
-  __shared__ uint32_t is_last, wg_cand, wg_base;
+  __shared__ uint32_t wg_cand, wg_base;
   const int t = threadIdx.x;
   const uint32_t shift = ctrl->shift;
   const uint64_t lo = ctrl->lo, hi = ctrl->hi;
@@ -650,16 +650,8 @@ __device__ __forceinline__ void select_classify_body(
   }
   }
   if constexpr (MODE == 1) return;
-  if constexpr (MODE == 0) {
-    __threadfence();
-    __syncthreads();
-    if (t == 0) is_last = (atomicAdd(&ctrl->ticket, 1u) == nwgs - 1) ? 1u : 0u;
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();
-  }
 
-  // last workgroup: the candidates all lie in the threshold bucket's key range,
+  // the candidates all lie in the threshold bucket's key range,
   // which serves as the bracket of their exact selection
   const uint32_t n = __hip_atomic_load(&ctrl->n_cand, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   Candidates src{cand_key, cand_idx};
@@ -689,14 +681,6 @@ __device__ __forceinline__ void select_classify_body(
   } else {
     radix_select<kGridThreads>(src, n, n_keep - above, nblocks, mask, sh);
   }
-}
-
-__global__ __launch_bounds__(kGridThreads) void select_classify_kernel(
-    const double *__restrict__ scores, uint32_t nblocks, uint32_t n_keep, uint32_t per_wg,
-    const uint32_t *__restrict__ counts, SelectCtrl *__restrict__ ctrl,
-    uint64_t *__restrict__ cand_key, uint32_t *__restrict__ cand_idx, uint8_t *__restrict__ mask) {
-  select_classify_body<0>(scores, nblocks, n_keep, per_wg, counts, ctrl, cand_key, cand_idx, mask, blockIdx.x,
-                          gridDim.x);
 }
 
 // ---- several independent selections per launch (one per tensor of a batch) ----
@@ -815,9 +799,15 @@ int launch_select(const double *scores, int64_t nblocks, int64_t n_keep, uint8_t
                        (uint32_t)nblocks, (uint32_t)n_keep, per_wg, counts, ctrl);
   int rc = check_launch();
   if (rc != BSR_OK) return rc;
-  hipLaunchKernelGGL(select_classify_kernel, dim3((unsigned)wgs), dim3(kGridThreads), 0, s, scores,
-                     (uint32_t)nblocks, (uint32_t)n_keep, per_wg, counts, ctrl, cand_key, cand_idx,
-                     keep_mask);
+  // Classification and the selection among the candidates as two launches: one more launch costs
+  // less than the release fence of every workgroup that finding the last one to finish takes.
+  SelectBatch b;
+  b.it[0] = SelectItem{scores, keep_mask, (uint32_t)nblocks, (uint32_t)n_keep, per_wg, (uint32_t)wgs, counts, ctrl,
+                       cand_key, cand_idx};
+  hipLaunchKernelGGL(select_classify_batched_kernel, dim3((unsigned)wgs, 1), dim3(kGridThreads), 0, s, b);
+  rc = check_launch();
+  if (rc != BSR_OK) return rc;
+  hipLaunchKernelGGL(select_finish_batched_kernel, dim3(1), dim3(kGridThreads), 0, s, b);
   return check_launch();
 }
 
