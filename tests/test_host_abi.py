@@ -188,6 +188,24 @@ def test_invalid_arguments_are_rejected_on_the_host():
                        for M in (64, 128))
     assert bt(items(), ws_bytes=need - 1) == B.BSR_ERR_WORKSPACE
     assert lib.bsr_score_select_batched_workspace_bytes(items(br=0), 2, 1) == 0
+    # ... and the per-group ranking of several tensors: the same checks plus the group sizes
+    rows = lambda a, b: (C.c_int64 * 2)(a, b)
+    gb = lambda arr, gr=None, n=2, dtype=1, ws=fake, ws_bytes=1 << 20: lib.bsr_score_select_grouped_batched(
+        arr, rows(2, 4) if gr is None else gr, n, dtype, ws, ws_bytes, None)
+    assert gb(items(), n=-1) == B.BSR_ERR_SHAPE
+    assert gb(items(), n=0) == B.BSR_OK
+    assert gb(None) == B.BSR_ERR_NULL
+    assert lib.bsr_score_select_grouped_batched(items(), None, 2, 1, fake, 1 << 20, None) == B.BSR_ERR_NULL
+    assert gb(items(), gr=rows(2, 0)) == B.BSR_ERR_SHAPE
+    assert gb(items(), gr=rows(-1, 4)) == B.BSR_ERR_SHAPE
+    assert gb(items(), dtype=4) == B.BSR_ERR_DTYPE
+    assert gb(items(br=0)) == B.BSR_ERR_SHAPE
+    assert gb(items(keep=-0.1)) == B.BSR_ERR_KEEP
+    assert gb(items(X=None)) == B.BSR_ERR_NULL
+    assert gb(items(mask=None)) == B.BSR_ERR_NULL
+    assert gb(items(), ws=None) == B.BSR_ERR_WORKSPACE
+    assert gb(items(), ws_bytes=need - 1) == B.BSR_ERR_WORKSPACE
+    assert gb(items(), ws=odd) == B.BSR_ERR_ALIGN
     def mm_items(**k):
         arr = (B._MatmulItem * 2)()
         arr[0] = B._MatmulItem(0x1000, 0x1000, 0x1000, 64, 64, 16, 16, 0x1000, 32, 32, 0x1000, 32, 0)
