@@ -14,11 +14,14 @@
 //    rows, the rest zero) = one contraction step of v_mfma_f32_32x32x16_bf16: the
 //    activation group with 576-byte rows (up to 224 columns in 512 bytes that two copies
 //    fill, plus 64 bytes that put the four rows a transposing read touches into different
-//    banks), the dY group as in memory (rows of 2 N bytes; a block-row of dY is one
-//    contiguous piece of memory).
+//    banks), the dY group with rows padded to the next of 64, 192, 320, 448 bytes for the
+//    same reason (with the 392-byte rows of memory, 45 % of the LDS cycles were bank
+//    conflicts).
 //  * Both operands go from global memory to LDS through the texture path
 //    (buffer_load ... lds), a ring of four stages deep, by four copy waves that do
-//    nothing else.  dY is copied 16 bytes per lane, linearly.  The activation tile is
+//    nothing else.  dY is copied 16 bytes per lane: LDS fills in lane order, and a lane
+//    fetches the 16 bytes of the block-row (one contiguous piece of memory) that belong
+//    where it writes, or nothing in the padding of a row.  The activation tile is
 //    written row by row, 4 bytes per lane: LDS addresses ascend with the lane, the
 //    global address of a lane is that of "its" column in the kept block that covers
 //    it -- or an offset beyond the buffer when that block was pruned (or the row or
@@ -151,7 +154,10 @@ __device__ __forceinline__ void narrow_body(const NarrowParams &prm, const uint3
     __syncthreads();            // the table is complete and the ring's memory is free again
   }
   const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)sRing;
-  const int pitch_b = (int)prm.N * 2;                       // bytes per row of dY, in memory and in LDS
+  // Bytes per row of dY in memory, and in LDS: there the pitch is the next of 64, 192, 320, 448, so that the
+  // four rows that a 16-lane group of a transposing read touches start 16 banks apart (as in the activation tile).
+  const int pitch_mem = (int)prm.N * 2;
+  const int pitch_b = 64 + 128 * ((pitch_mem + 63) / 128);
 
   if (wave >= kMathWaves) {
     // ================= copy waves =================
@@ -180,8 +186,18 @@ __device__ __forceinline__ void narrow_body(const NarrowParams &prm, const uint3
       if (col_j[h] >= (uint32_t)nbc) col_j[h] = 0xFFu;      // beyond the matrix
     }
     const int live_rows = b - 8 * rh < 8 ? (b - 8 * rh < 0 ? 0 : b - 8 * rh) : 8;   // of this wave's eight rows
-    const uint32_t group_bytes_b = (uint32_t)(b * pitch_b);
-    const uint32_t lane_b = (uint32_t)(lane * 16 + 4 * rh * 1024);
+    const uint32_t group_bytes_b = (uint32_t)(b * pitch_mem);
+    // dY: the wave's four copies of 1 KB fill LDS in lane order; the 16 bytes at byte o of the group in LDS are
+    // row o / pitch_b, byte o % pitch_b of the block-row in memory -- or nothing, in the padding of a row.  (A
+    // chunk may reach over the end of its row: into the padding go the first bytes of the next row, or zeros
+    // at the end of the block-row, as the range check is per dword.)
+    uint32_t lane_b[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t o = (uint32_t)(4096 * rh + 1024 * k + 16 * lane);
+      const uint32_t row = o / (uint32_t)pitch_b, cb = o - row * (uint32_t)pitch_b;
+      lane_b[k] = cb < (uint32_t)pitch_mem ? row * (uint32_t)pitch_mem + cb : kDead;
+    }
     auto issue = [&](int q) {                               // the copies of stage q of the range
       const uint32_t slot = ring_lds + (uint32_t)((q & (kRing - 1)) * kStage);
       const int i = 2 * q + g;                              // block-row of the range (table rows beyond it: all pruned)
@@ -204,11 +220,12 @@ __device__ __forceinline__ void narrow_body(const NarrowParams &prm, const uint3
       if (left > group_bytes_b) left = group_bytes_b;
       if (left < 0) left = 0;
       const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(static_cast<const char *>(prm.dY) + (left > 0 ? at : 0), (uint32_t)left);
-      set_m0(slot + (uint32_t)(2 * kGroupA + g * kGroupB + 4 * rh * 1024));
-      dma_dwordx4<0>(rsrc_b, lane_b);
-      dma_dwordx4<1024>(rsrc_b, lane_b);
-      dma_dwordx4<2048>(rsrc_b, lane_b);
-      dma_dwordx4<3072>(rsrc_b, lane_b);
+      const uint32_t group_lds = slot + (uint32_t)(2 * kGroupA + g * kGroupB + 4 * rh * 1024);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        set_m0(group_lds + 1024u * (uint32_t)k);
+        dma_dwordx4<0>(rsrc_b, lane_b[k]);
+      }
     };
 #pragma unroll
     for (int d = 0; d < kAhead; ++d) issue(d);
