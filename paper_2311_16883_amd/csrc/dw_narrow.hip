@@ -1,7 +1,8 @@
 // Weight gradient from a BSR activation (paper Sec. III, Fig. 2: dW = Xhat^T * dY)
 // for bfloat16 inputs with small square blocks and a small weight matrix: blocks
-// of b x b, b even and at most 16, K <= 224, N <= 224 -- the cross-patch linear
-// layers of ResMLP (196 x 196 weights, 14 x 14 blocks over the patch axis).
+// of b x b, b even and at most 16, at most 14 block-columns, N <= 224 -- the
+// cross-patch linear layers of ResMLP (196 x 196 weights, 14 x 14 blocks over the
+// patch axis).
 //
 // dW is small (at most 7 x 7 matrix-core tiles of 32 x 32) and the contraction
 // is long, so one workgroup owns ALL of dW for a range of block-rows: every byte
@@ -11,30 +12,33 @@
 // masked activation, zeros where a block was pruned, and multiplied as such.
 //
 //  * A stage is two block-rows.  In LDS a block-row is a group of 16 rows (b data
-//    rows, the rest zero) = one contraction step of v_mfma_f32_32x32x16_bf16: the
-//    activation group with 576-byte rows (up to 224 columns in 512 bytes that two copies
-//    fill, plus 64 bytes that put the four rows a transposing read touches into different
-//    banks), the dY group with rows padded to the next of 64, 192, 320, 448 bytes for the
-//    same reason (with the 392-byte rows of memory, 45 % of the LDS cycles were bank
-//    conflicts).
+//    rows, the rest zero) = one contraction step of v_mfma_f32_32x32x16_bf16.  In
+//    the activation group every block-column has a slot of 16 columns (32 bytes: a
+//    matrix-core tile is two slots; the columns of a slot beyond b belong to no row
+//    of dW and hold whatever follows the block's row in memory); rows are 576 bytes
+//    apart: 448 of slots and padding that puts the four rows a transposing read
+//    touches into different banks.  The dY group has its rows padded to the next of
+//    64, 192, 320, 448 bytes for the same reason (with the 392-byte rows of memory,
+//    45 % of the LDS cycles were bank conflicts).
 //  * Both operands go from global memory to LDS through the texture path
 //    (buffer_load ... lds), a ring of four stages deep, by four copy waves that do
-//    nothing else.  dY is copied 16 bytes per lane: LDS fills in lane order, and a lane
-//    fetches the 16 bytes of the block-row (one contiguous piece of memory) that belong
-//    where it writes, or nothing in the padding of a row.  The activation tile is
-//    written row by row, 4 bytes per lane: LDS addresses ascend with the lane, the
-//    global address of a lane is that of "its" column in the kept block that covers
-//    it -- or an offset beyond the buffer when that block was pruned (or the row or
-//    column lies outside the matrix), which makes the copy write a zero.  Every wave
-//    issues the same number of copies per stage, so waiting for a stage is a constant
-//    vmcnt.
+//    nothing else, 16 bytes per lane.  LDS fills in lane order, and a lane fetches
+//    the 16 bytes that belong where it writes: of dY, a piece of the block-row (one
+//    contiguous piece of memory), or nothing in the padding of a row; of the
+//    activation, half a slot = 16 bytes of one row of the kept block of that
+//    block-column -- or nothing (an offset beyond the buffer, which makes the copy
+//    write zeros) when the block was pruned or the row or column lies outside the
+//    block or the matrix.  The range check is per dword, so a copy that reaches over
+//    the end of the buffer delivers what is inside.  Every wave issues the same
+//    number of copies per stage (9 or 8), so waiting for a stage is a constant vmcnt.
 //  * A table in LDS, built once per workgroup, holds for every block-row of its
 //    range the position of its first kept block and, per block-column, the rank of
 //    that column among the kept ones of the row (or "pruned"): col_idx may be in any
 //    order inside a block-row.
-//  * Seven multiplying waves: wave p owns rows 32 p .. 32 p + 31 of dW and all
-//    columns (7 accumulator tiles), so a fragment of the activation is read once
-//    and a fragment of dY once per wave.
+//  * Seven multiplying waves: wave p owns the tile columns 32 p .. 32 p + 31 of the
+//    activation (the rows of dW of block-columns 2 p and 2 p + 1) and all columns of
+//    dW (7 accumulator tiles), so a fragment of the activation is read once and a
+//    fragment of dY once per wave.
 //  * The block-rows are split over workgroups; partial matrices go to the workspace
 //    and the split-K reduction kernel adds them in a fixed order.
 #include "buffer_access.h"
@@ -53,7 +57,8 @@ constexpr int kNT = 7;                     // tiles of 32 along K and along N: 2
 constexpr int kMathWaves = 7;
 constexpr int kCopyWaves = 4;
 constexpr int kNarrowThreads = 64 * (kMathWaves + kCopyWaves);
-constexpr int kPitchA = 576;               // bytes per row of the activation tile: 512 written per row (two copies of 256), 64 apart in banks
+constexpr int kSlots = 14;                 // block-columns of the activation tile: a slot of 16 columns (32 bytes) each
+constexpr int kPitchA = 576;               // bytes per row of the activation tile: 448 of slots, and padding that puts rows 16 banks apart
 constexpr int kGroupA = 16 * kPitchA;      // 9 KB: one block-row of the activation tile
 constexpr int kGroupB = 8192;              // one block-row of dY: at most 16 rows x 448 bytes, copied 8 x 1 KB
 constexpr int kStage = 2 * kGroupA + 2 * kGroupB;      // 34 KB
@@ -74,14 +79,9 @@ struct NarrowParams {
   uint32_t wg_begin;       // first workgroup of this product in a launch of several
 };
 
-// Global -> LDS copies.  LDS address = M0 + IMM + 4 (or 16) * lane, global address = resource base +
-// voff + IMM: the instruction's immediate offset moves both, so one setting of M0 serves several copies.
+// Global -> LDS copies.  LDS address = M0 + IMM + 16 * lane, global address = resource base + voff + IMM.
 __device__ __forceinline__ void set_m0(uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" :: "s"(lds_addr) : "memory", "m0");
-}
-template <int IMM>
-__device__ __forceinline__ void dma_dword(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff) {
-  asm volatile("buffer_load_dword %0, %1, 0 offen offset:%2 lds" :: "v"(voff), "s"(rsrc), "n"(IMM) : "memory", "m0");
 }
 template <int IMM>
 __device__ __forceinline__ void dma_dwordx4(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff) {
@@ -161,31 +161,30 @@ __device__ __forceinline__ void narrow_body(const NarrowParams &prm, const uint3
 
   if (wave >= kMathWaves) {
     // ================= copy waves =================
-    // Copy wave c serves block-row g = c / 2 of every stage: rows 8 (c % 2) .. + 7 of its activation
-    // group (two copies of 64 four-byte columns each per row) and four of the eight 1 KB pieces of
-    // its dY group: 20 copies per stage, always.
+    // Copy wave c serves block-row g = c / 2 of every stage: of the nine 1 KB pieces of its activation
+    // group the first five (c even) or the last four, and four of the eight 1 KB pieces of its dY group:
+    // 9 or 8 copies per stage, always.
     const int c = wave - kMathWaves, g = c >> 1, rh = c & 1;
-    // The activation copies of a row differ by 576 bytes in LDS and by one block row in memory; the
-    // instruction's immediate offset adds r * 576 to both, so the per-lane offset of row r is lowered by
-    // r * (576 - block row bytes), and the resource starts kBias bytes below `values` so that no such
-    // offset goes below zero.  An offset that must read as zero starts at kDead and stays beyond the buffer.
-    constexpr uint32_t kBias = 8 * kPitchA;
-    constexpr uint32_t kDead = kBeyond + 4096u;
-    const __amdgpu_buffer_rsrc_t rsrc_a =
-        make_rsrc(reinterpret_cast<const void *>(reinterpret_cast<uintptr_t>(prm.values) - kBias), prm.values_bytes + kBias);
-    const uint32_t bw = (uint32_t)b / 2u;                   // four-byte columns per block row
+    const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(prm.values, prm.values_bytes);
     const uint32_t block_bytes = (uint32_t)(b * b * 2), row_bytes = (uint32_t)(b * 2);
-    const uint32_t step = (uint32_t)kPitchA - row_bytes;    // what the offset of the next row is lowered by
-    // this lane's two columns of the tile: block-column, byte inside the block row
-    uint32_t col_j[2], col_in[2];
+    constexpr uint32_t kDead = kBeyond + 4096u;
+    // Activation tile: LDS fills in lane order, 16 bytes per lane.  The 16 bytes at byte o of the group
+    // are row o / 576 of the tile and, inside the row, half h of the 32-byte slot of block-column j:
+    // bytes 16 h .. 16 h + 15 of that row of block j -- fetched if the block is kept, else (and in the
+    // padding of a tile row, in rows beyond the block, in block-columns beyond the matrix) nothing is
+    // fetched and zeros are written.  The second half of a slot reaches beyond the 2 b bytes of the
+    // block's row: what follows in memory lands in tile columns that belong to no row of dW.
+    const int na = rh == 0 ? 5 : 4, ka0 = rh == 0 ? 0 : 5;
+    uint32_t a_col[5], a_off[5];                            // block-column (0xFF: nothing to fetch), byte inside the block
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const uint32_t d = (uint32_t)(64 * h + lane);
-      col_j[h] = d / bw;
-      col_in[h] = (d - col_j[h] * bw) * 4u + kBias + (uint32_t)(8 * rh) * row_bytes;
-      if (col_j[h] >= (uint32_t)nbc) col_j[h] = 0xFFu;      // beyond the matrix
+    for (int k = 0; k < 5; ++k) {
+      const uint32_t o = (uint32_t)(1024 * (ka0 + k) + 16 * lane);
+      const uint32_t row = o / (uint32_t)kPitchA, cb = o - row * (uint32_t)kPitchA;
+      const uint32_t j = cb >> 5, h = (cb >> 4) & 1u;
+      const bool fetch = k < na && cb < 32u * kSlots && row < (uint32_t)b && j < (uint32_t)nbc && 16u * h < row_bytes;
+      a_col[k] = fetch ? j : 0xFFu;
+      a_off[k] = row * row_bytes + 16u * h;
     }
-    const int live_rows = b - 8 * rh < 8 ? (b - 8 * rh < 0 ? 0 : b - 8 * rh) : 8;   // of this wave's eight rows
     const uint32_t group_bytes_b = (uint32_t)(b * pitch_mem);
     // dY: the wave's four copies of 1 KB fill LDS in lane order; the 16 bytes at byte o of the group in LDS are
     // row o / pitch_b, byte o % pitch_b of the block-row in memory -- or nothing, in the padding of a row.  (A
@@ -202,17 +201,15 @@ __device__ __forceinline__ void narrow_body(const NarrowParams &prm, const uint3
       const uint32_t slot = ring_lds + (uint32_t)((q & (kRing - 1)) * kStage);
       const int i = 2 * q + g;                              // block-row of the range (table rows beyond it: all pruned)
       const uint32_t start = sStart[i];
+      const uint32_t group_a = slot + (uint32_t)(g * kGroupA + 1024 * ka0);
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const uint32_t rk = col_j[h] < 16u ? (uint32_t)sRank[i * 16 + (int)col_j[h]] : 0xFFu;
-        uint32_t v = rk == 0xFFu ? kDead : (start + rk) * block_bytes + col_in[h];
-        set_m0(slot + (uint32_t)(g * kGroupA + 8 * rh * kPitchA + 256 * h));
-        // rows beyond the block (wave-uniform) are copied from beyond the buffer: they stay zero
-#define BSR_ROW(R)                                          \
-        dma_dword<R * kPitchA>(rsrc_a, R < live_rows ? v : kDead); \
-        v -= step;
-        BSR_ROW(0) BSR_ROW(1) BSR_ROW(2) BSR_ROW(3) BSR_ROW(4) BSR_ROW(5) BSR_ROW(6) BSR_ROW(7)
-#undef BSR_ROW
+      for (int k = 0; k < 5; ++k) {
+        if (k < na) {                                       // (wave-uniform)
+          const uint32_t rk = a_col[k] < 16u ? (uint32_t)sRank[i * 16 + (int)a_col[k]] : 0xFFu;
+          const uint32_t v = rk == 0xFFu ? kDead : (start + rk) * block_bytes + a_off[k];
+          set_m0(group_a + 1024u * (uint32_t)k);
+          dma_dwordx4<0>(rsrc_a, v);
+        }
       }
       // this block-row of dY as a buffer of its own: what lies beyond it (or beyond the matrix) reads as zero
       const int64_t at = (int64_t)(i_begin + i) * group_bytes_b;
@@ -230,8 +227,9 @@ __device__ __forceinline__ void narrow_body(const NarrowParams &prm, const uint3
 #pragma unroll
     for (int d = 0; d < kAhead; ++d) issue(d);
     for (int q = 0; q < nstages; ++q) {
-      // the copies of stage q have landed when only the 40 of the two stages after it are on their way
-      asm volatile("s_waitcnt vmcnt(40)" ::: "memory");
+      // the copies of stage q have landed when only those of the two stages after it are on their way
+      if (rh == 0) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
       stage_barrier();
       issue(q + kAhead);                                    // into the slot of stage q - 1, which everybody has left
     }
@@ -241,12 +239,12 @@ __device__ __forceinline__ void narrow_body(const NarrowParams &prm, const uint3
   }
 
   // ================= multiplying waves =================
-  const int p = wave;                                       // rows 32 p .. 32 p + 31 of dW
+  const int p = wave;                                       // tile columns 32 p .. 32 p + 31: the block-columns 2 p and 2 p + 1
   const int g4 = lane >> 4, L = lane & 15;
   const int frag_row = 8 * (g4 >> 1) + (L >> 2), frag_col = 16 * (g4 & 1) + 4 * (L & 3);
   const uint8_t *const myA = sRing + frag_row * kPitchA + (32 * p + frag_col) * 2;
   const uint8_t *const myB = sRing + 2 * kGroupA + frag_row * pitch_b + frag_col * 2;
-  const bool active = 32 * p < prm.K;
+  const bool active = 2 * p < nbc;
   v16f acc[NS];
 #pragma unroll
   for (int s = 0; s < NS; ++s)
@@ -279,9 +277,11 @@ __device__ __forceinline__ void narrow_body(const NarrowParams &prm, const uint3
   for (int s = 0; s < NS; ++s) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int64_t k = 32 * p + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      // tile column -> row of dW: column c of the slot of block-column j is row j b + c, for c < b
+      const int tc = 32 * p + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      const int64_t k = (int64_t)(tc >> 4) * b + (tc & 15);
       const int64_t n = 32 * s + (lane & 31);
-      if (k < K && n < N) {
+      if ((tc & 15) < b && k < K && n < N) {
         float *dst = o + k * ldo + n;
         *dst = add ? *dst + acc[s][r] : acc[s][r];
       }
@@ -321,8 +321,8 @@ void narrow_fill(const DwJob &j, int splits, NarrowParams *p) {
 
 }  // namespace
 
-// Shapes the narrow-block kernel takes: bfloat16, square blocks of an even size up to 16, a
-// weight matrix of at most 224 x 224, dY rows contiguous in memory with every block-row of dY
+// Shapes the narrow-block kernel takes: bfloat16, square blocks of an even size up to 16, at most 14
+// block-columns and 224 columns of dW, dY rows contiguous in memory with every block-row of dY
 // starting on a 16-byte boundary, operands addressable with 32-bit byte offsets.
 bool dw_narrow_supported(int dtype, int br, int bc, const void *values, const void *dY, int64_t M, int64_t K,
                          int64_t N, int64_t lddy) {
@@ -330,7 +330,7 @@ bool dw_narrow_supported(int dtype, int br, int bc, const void *values, const vo
   if (M <= 0 || K <= 0 || N <= 0 || K > 32 * kNT || N > 32 * kNT || N % 4 != 0 || lddy != N) return false;
   if ((uintptr_t)values % 4 != 0 || (uintptr_t)dY % 16 != 0 || ((int64_t)br * N * 2) % 16 != 0) return false;
   const int64_t nbr = ceil_div(M, (int64_t)br), nbc = ceil_div(K, (int64_t)bc);
-  if (nbc > 16 || nbc * br > 32 * kNT) return false;
+  if (nbc > kSlots) return false;
   if (nbr * nbc * br * bc * 2 >= (int64_t(1) << 32) - 2 * 65536) return false;
   if ((nbr + 2 * kRing) * br * N * 2 >= (int64_t(1) << 32) - 2 * 65536) return false;
   return nbr < (int64_t(1) << 30);

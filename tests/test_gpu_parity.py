@@ -772,6 +772,9 @@ SMALL_SQUARE = [
     (500, 160, 160, 16, 1.0),       # everything kept
     (448, 196, 196, 14, 0.0),       # nothing kept
     (3500, 196, 196, 14, 0.5),      # 250 block-rows
+    (700, 56, 40, 4, 0.5),          # 14 block-columns of 4: a block row is half a 16-byte copy
+    (512, 28, 12, 2, 0.5),          # the smallest blocks
+    (600, 128, 64, 8, 0.5),         # 16 block-columns: more than the tile has slots, another kernel's product
 ]
 
 
