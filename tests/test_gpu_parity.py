@@ -826,6 +826,38 @@ PACK_BATCH = [
 ]
 
 
+def test_batched_dw_small_square_blocks_random_shapes():
+    """Seeded random block sizes, block-column counts, output widths, row counts and keep ratios inside what
+    the small-square-block kernel takes (even b <= 16, at most 14 block-columns, N a multiple of 4 up to 224,
+    block-rows of dY on 16-byte boundaries), several batched calls, the whole dW against the oracle."""
+    rng = np.random.default_rng(2311)
+    for call in range(6):
+        problems, refs, shapes = [], [], []
+        for i in range(5):
+            b = int(rng.choice([2, 4, 6, 8, 10, 12, 14, 16]))
+            nbc = int(rng.integers(1, 15))
+            K = nbc * b - int(rng.integers(0, b))                    # a ragged last block-column now and then
+            K = max(K, 1)
+            N = 4 * int(rng.integers(1, 57))
+            while (b * N * 2) % 16 != 0:
+                N += 4
+            N = min(N, 224)
+            M = b * int(rng.integers(16, 120)) + int(rng.integers(0, b))
+            keep = float(rng.choice([0.1, 0.3, 0.5, 0.8, 1.0]))
+            X, dY = rand_pair(M, K, N, "bf16", seed=9000 + 10 * call + i)
+            _, o_mask, o_rp, o_ci, o_val = oracle.prune(X, b, b, keep)
+            rp, ci = torch.from_numpy(o_rp).cuda(), torch.from_numpy(o_ci).cuda()
+            val = to_dev(o_val.reshape(-1, b)).reshape(o_val.shape) if o_val.size else \
+                torch.empty((0, b, b), dtype=torch.bfloat16, device="cuda")
+            problems.append((rp, ci, val, M, K, b, b, to_dev(dY)))
+            refs.append(oracle.dw(oracle.mask_dense(X, b, b, o_mask), dY))
+            shapes.append((M, K, N, b, keep))
+        outs = B.bsr_t_dense_matmul_batched(B.MatmulBatch(problems))
+        torch.cuda.synchronize()
+        for o, ref, shape in zip(outs, refs, shapes):
+            assert dw_error(o.cpu().numpy(), ref) <= DW_TOL_DERIVED, f"call {call}: (M, K, N, b, keep) = {shape}"
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_batched_compress_and_decompress_equal_single_calls(dtype):
     problems, singles, masks, Xs = [], [], [], []
