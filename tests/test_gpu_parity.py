@@ -650,6 +650,43 @@ def test_dw_wide_tiles_ragged_everything(bs):
     assert dw_error(base.cpu().numpy() - 0.25, ref) <= 1e-4 * max(1.0, 0.25 / np.max(np.abs(ref)))
 
 
+def test_dw_wide_tiles_random_shapes():
+    """Seeded random shapes through the wide-tile kernel, single calls and a batched call: block size 32 or
+    64, rows / columns / output columns that end anywhere (N a multiple of 8, as the kernel needs), keep
+    ratios from nearly nothing to everything, dY as a view of a wider matrix, dW with a pitch of its own."""
+    rng = np.random.default_rng(16883)
+    problems, refs, shapes = [], [], []
+    for i in range(8):
+        bs = int(rng.choice([32, 64]))
+        M = int(rng.integers(40 * bs, 90 * bs)) + int(rng.integers(0, bs))
+        K = int(rng.integers(500, 1300))
+        N = 8 * int(rng.integers(40, 80))
+        keep = float(rng.choice([0.02, 0.25, 0.5, 0.75, 1.0]))
+        print(f"[case] wide-tile dW, random shape {i}: M={M} K={K} N={N} block={bs} keep={keep}", flush=True)
+        X, dY = rand_pair(M, K, N, "bf16", seed=7000 + i, dist="gelu" if i % 2 else "normal")
+        _, o_mask, o_rp, o_ci, o_val = oracle.prune(X, bs, bs, keep)
+        ref = oracle.dw(oracle.mask_dense(X, bs, bs, o_mask), dY)
+        rp, ci = torch.from_numpy(o_rp).cuda(), torch.from_numpy(o_ci).cuda()
+        val = to_dev(o_val.reshape(-1, bs)).reshape(o_val.shape)
+        wide = torch.zeros((M, N + 8 * (i % 3)), dtype=torch.bfloat16, device="cuda")
+        wide[:, :N] = to_dev(dY)
+        dYd = wide[:, :N]                                    # leading dimension N, N + 8 or N + 16
+        out = torch.full((K, N + 4 * (i % 2)), -1.0, dtype=torch.float32, device="cuda")
+        dW = out[:, :N]
+        B.bsr_t_dense_matmul(rp, ci, val, M, K, bs, bs, dYd, dW=dW)
+        torch.cuda.synchronize()
+        assert dw_error(dW.cpu().numpy(), ref) <= DW_TOL_DERIVED, f"single call, shape {i}"
+        if out.shape[1] > N:
+            assert bool((out[:, N:] == -1.0).all()), f"columns beyond dW were written, shape {i}"
+        problems.append((rp, ci, val, M, K, bs, bs, dYd))
+        refs.append(ref)
+        shapes.append((M, K, N, bs, keep))
+    outs = B.bsr_t_dense_matmul_batched(B.MatmulBatch(problems))
+    torch.cuda.synchronize()
+    for i, (o, ref) in enumerate(zip(outs, refs)):
+        assert dw_error(o.cpu().numpy(), ref) <= DW_TOL_DERIVED, f"batched call, item {i}: {shapes[i]}"
+
+
 def test_batched_dw_with_more_tiles_than_compute_units():
     """24 products of 16 tiles each: the first sixteen products are run tile by tile, each tile
     by one workgroup over all 500 block-rows (more than one table's worth: two chunks), the
