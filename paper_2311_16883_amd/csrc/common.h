@@ -232,4 +232,28 @@ struct alignas(sizeof(T) * V) Vec {
   T e[V];
 };
 
+// Loads and stores of data that the kernel touches once (the streaming side of the HBM-bound
+// kernels): non-temporal accesses, which leave the caches to what is read again.  V is any
+// trivially copyable type of 2, 4, 8 or 16 bytes at its natural alignment.
+template <typename V>
+__device__ __forceinline__ V load_stream(const V *p) {
+  typedef uint32_t __attribute__((ext_vector_type(4))) w4;
+  typedef uint32_t __attribute__((ext_vector_type(2))) w2;
+  static_assert(sizeof(V) == 16 || sizeof(V) == 8 || sizeof(V) == 4 || sizeof(V) == 2, "2, 4, 8 or 16 bytes");
+  if constexpr (sizeof(V) == 16) return __builtin_bit_cast(V, __builtin_nontemporal_load(reinterpret_cast<const w4 *>(p)));
+  else if constexpr (sizeof(V) == 8) return __builtin_bit_cast(V, __builtin_nontemporal_load(reinterpret_cast<const w2 *>(p)));
+  else if constexpr (sizeof(V) == 4) return __builtin_bit_cast(V, __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p)));
+  else return __builtin_bit_cast(V, __builtin_nontemporal_load(reinterpret_cast<const uint16_t *>(p)));
+}
+template <typename V>
+__device__ __forceinline__ void store_stream(V *p, const V &v) {
+  typedef uint32_t __attribute__((ext_vector_type(4))) w4;
+  typedef uint32_t __attribute__((ext_vector_type(2))) w2;
+  static_assert(sizeof(V) == 16 || sizeof(V) == 8 || sizeof(V) == 4 || sizeof(V) == 2, "2, 4, 8 or 16 bytes");
+  if constexpr (sizeof(V) == 16) __builtin_nontemporal_store(__builtin_bit_cast(w4, v), reinterpret_cast<w4 *>(p));
+  else if constexpr (sizeof(V) == 8) __builtin_nontemporal_store(__builtin_bit_cast(w2, v), reinterpret_cast<w2 *>(p));
+  else if constexpr (sizeof(V) == 4) __builtin_nontemporal_store(__builtin_bit_cast(uint32_t, v), reinterpret_cast<uint32_t *>(p));
+  else __builtin_nontemporal_store(__builtin_bit_cast(uint16_t, v), reinterpret_cast<uint16_t *>(p));
+}
+
 }  // namespace bsr

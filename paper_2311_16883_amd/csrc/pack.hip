@@ -242,7 +242,7 @@ __device__ __forceinline__ void compress_body(const CompressArgs &a, const int64
     const int64_t cb = (int64_t)kept_j[q] * bcb + (int64_t)v * VB;
     V val = zero_bytes<VB>();
     if (r < rows_left && cb < kb) val = *reinterpret_cast<const V *>(xrow + (int64_t)r * ldb + cb);
-    *reinterpret_cast<V *>(vrow + ((int64_t)q * S + e) * VB) = val;
+    store_stream(reinterpret_cast<V *>(vrow + ((int64_t)q * S + e) * VB), val);
   };
   if (S <= 256) {
     const int G = 256 / S, g = t / S, e = t - g * S;      // G blocks per pass
@@ -340,7 +340,7 @@ __device__ __forceinline__ void decompress_body(const DecompressArgs &a, const u
 #pragma unroll
         for (int b = 0; b < kInFlight; ++b) {
           const int r = r0 + 4 * b;
-          if (r < rows) *reinterpret_cast<V *>(orow + (int64_t)r * ldb + cb) = val[b];
+          if (r < rows) store_stream(reinterpret_cast<V *>(orow + (int64_t)r * ldb + cb), val[b]);
         }
       }
     }
@@ -398,7 +398,7 @@ __device__ __forceinline__ void span_write_run(const SpanGeom &g, const uint32_t
     const uint32_t l = lim[q];
     uint32_t val = 0;
     if (r < (l >> 16) && c < (l & 0xFFFFu)) val = span[base[q] + r * g.row_words + c];
-    out[w] = val;
+    store_stream(out + w, val);
   }
 }
 
@@ -681,7 +681,7 @@ __device__ __forceinline__ void decompress_span_body(const DecompressSpanArgs &a
   V *dst = reinterpret_cast<V *>(X_out + m0 * g.row_words * 4);
 #pragma unroll
   for (int k = 0; k < kVecs; ++k)
-    if (t + 256 * k < nvec) dst[t + 256 * k] = sv[t + 256 * k];
+    if (t + 256 * k < nvec) store_stream(dst + t + 256 * k, sv[t + 256 * k]);
 }
 
 template <int VB>

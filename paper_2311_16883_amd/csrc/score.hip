@@ -121,7 +121,7 @@ __device__ __forceinline__ void score_direct_body(
     Vec<T, V> v[kInFlight];
 #pragma unroll
     for (int b = 0; b < kInFlight; ++b)
-      if (r0 + b * rs < rows) v[b] = *reinterpret_cast<const Vec<T, V> *>(p + (int64_t)(r0 + b * rs) * ldx);
+      if (r0 + b * rs < rows) v[b] = load_stream(reinterpret_cast<const Vec<T, V> *>(p + (int64_t)(r0 + b * rs) * ldx));
 #pragma unroll
     for (int b = 0; b < kInFlight; ++b) {
       if (r0 + b * rs < rows) {
