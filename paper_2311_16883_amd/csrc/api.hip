@@ -430,8 +430,11 @@ int bsr_t_dense_matmul_batched(const bsr_matmul_item *items, int n, int dtype, v
     batch.insert(batch.end(), wide.begin(), wide.end());
     wide.clear();
   }
-  int rc = launch_dw_wide_batched(wide.data(), (int)wide.size(), s);
-  if (rc == BSR_OK) rc = launch_dw_narrow_batched(narrow.data(), (int)narrow.size(), s);
+  // the partial tiles of both kinds of products are added up by one launch behind the two kernels
+  std::vector<ReduceJob> reductions;
+  int rc = launch_dw_wide_batched(wide.data(), (int)wide.size(), s, &reductions);
+  if (rc == BSR_OK) rc = launch_dw_narrow_batched(narrow.data(), (int)narrow.size(), s, &reductions);
+  if (rc == BSR_OK && !reductions.empty()) rc = launch_splitk_reduce_batched(reductions.data(), (int)reductions.size(), s);
   if (rc == BSR_OK) rc = launch_dw_mfma_batched(dtype, batch.data(), (int)batch.size(), s);
   for (size_t i = 0; rc == BSR_OK && i < single.size(); ++i) {
     const DwJob &j = single[i];

@@ -3,6 +3,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include <vector>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -202,12 +204,14 @@ int launch_dw_mfma_batched(int dtype, const DwJob *jobs, int n, hipStream_t s);
 bool dw_narrow_supported(int dtype, int br, int bc, const void *values, const void *dY, int64_t M, int64_t K,
                          int64_t N, int64_t lddy);
 size_t dw_narrow_ws_bytes(int64_t M, int64_t K, int64_t N, int br);
-int launch_dw_narrow_batched(const DwJob *jobs, int n, hipStream_t s);
+// `later`: when not null, the reductions of the products that were split are appended there instead of
+// being launched: the caller launches them (launch_splitk_reduce_batched) once its other kernels are queued.
+int launch_dw_narrow_batched(const DwJob *jobs, int n, hipStream_t s, std::vector<ReduceJob> *later = nullptr);
 bool dw_wide_supported(int dtype, int br, int bc, const void *values, const void *dY, int64_t M, int64_t K,
                        int64_t N, int64_t lddy);
 size_t dw_wide_ws_bytes(int64_t M, int64_t K, int64_t N, int br);
 int launch_dw_wide(const DwJob &j, hipStream_t s);
-int launch_dw_wide_batched(const DwJob *jobs, int n, hipStream_t s);
+int launch_dw_wide_batched(const DwJob *jobs, int n, hipStream_t s, std::vector<ReduceJob> *later = nullptr);
 
 // ---- device helpers ----
 

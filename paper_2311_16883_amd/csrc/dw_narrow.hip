@@ -355,7 +355,7 @@ size_t dw_narrow_ws_bytes(int64_t M, int64_t K, int64_t N, int br) {
   return s > 1 ? (size_t)s * (size_t)K * (size_t)N * sizeof(float) : 0;
 }
 
-int launch_dw_narrow_batched(const DwJob *jobs, int n, hipStream_t s) {
+int launch_dw_narrow_batched(const DwJob *jobs, int n, hipStream_t s, std::vector<ReduceJob> *later) {
   // the products with the same number of 32-column strips share launches, kNarrowBatchMax per launch
   for (int ns = 1; ns <= kNT; ++ns) {
     int mine = 0;
@@ -392,7 +392,10 @@ int launch_dw_narrow_batched(const DwJob *jobs, int n, hipStream_t s) {
         default: hipLaunchKernelGGL(dw_narrow_batched_kernel<7>, grid, block, 0, s, bt, m); break;
       }
       int rc = check_launch();
-      if (rc == BSR_OK && nred > 0) rc = launch_splitk_reduce_batched(red, nred, s);
+      if (rc == BSR_OK && nred > 0) {
+        if (later != nullptr) later->insert(later->end(), red, red + nred);
+        else rc = launch_splitk_reduce_batched(red, nred, s);
+      }
       if (rc != BSR_OK) return rc;
       left -= m;
     }

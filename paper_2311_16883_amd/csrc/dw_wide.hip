@@ -607,7 +607,7 @@ uint32_t wide_cut(const WideBatch &b, int lo, int hi, uint32_t *begin) {
 
 // One launch of up to kWideBatchMax products of block size BS, and the reduction of those it splits.
 template <int BS>
-int wide_launch(const DwJob *const *jobs, int m, hipStream_t s) {
+int wide_launch(const DwJob *const *jobs, int m, hipStream_t s, std::vector<ReduceJob> *later) {
   if (m <= 0) return BSR_OK;
   int64_t tiles[kWideBatchMax], stages[kWideBatchMax], rows[kWideBatchMax];
   double bytes_out[kWideBatchMax];
@@ -638,24 +638,27 @@ int wide_launch(const DwJob *const *jobs, int m, hipStream_t s) {
   if (longest == 0) return BSR_OK;
   hipLaunchKernelGGL((dw_wide_batched_kernel<BS>), dim3(8 * longest), dim3(kWideThreads), 0, s, b, m);
   int rc = check_launch();
-  if (rc == BSR_OK && nred > 0) rc = launch_splitk_reduce_batched(red, nred, s);
+  if (rc == BSR_OK && nred > 0) {
+    if (later != nullptr) later->insert(later->end(), red, red + nred);
+    else rc = launch_splitk_reduce_batched(red, nred, s);
+  }
   return rc;
 }
 
 template <int BS>
-int wide_run_batched(const DwJob *jobs, int n, hipStream_t s) {
+int wide_run_batched(const DwJob *jobs, int n, hipStream_t s, std::vector<ReduceJob> *later) {
   const DwJob *mine[kWideBatchMax];
   int m = 0;
   for (int i = 0; i < n; ++i) {
     if (jobs[i].br != BS) continue;
     mine[m++] = &jobs[i];
     if (m == kWideBatchMax) {
-      const int rc = wide_launch<BS>(mine, m, s);
+      const int rc = wide_launch<BS>(mine, m, s, later);
       if (rc != BSR_OK) return rc;
       m = 0;
     }
   }
-  return wide_launch<BS>(mine, m, s);
+  return wide_launch<BS>(mine, m, s, later);
 }
 
 }  // namespace
@@ -683,13 +686,13 @@ size_t dw_wide_ws_bytes(int64_t M, int64_t K, int64_t N, int br) {
 
 int launch_dw_wide(const DwJob &j, hipStream_t s) {
   const DwJob *one = &j;
-  return j.br == 32 ? wide_launch<32>(&one, 1, s) : wide_launch<64>(&one, 1, s);
+  return j.br == 32 ? wide_launch<32>(&one, 1, s, nullptr) : wide_launch<64>(&one, 1, s, nullptr);
 }
 
-int launch_dw_wide_batched(const DwJob *jobs, int n, hipStream_t s) {
-  const int rc = wide_run_batched<32>(jobs, n, s);
+int launch_dw_wide_batched(const DwJob *jobs, int n, hipStream_t s, std::vector<ReduceJob> *later) {
+  const int rc = wide_run_batched<32>(jobs, n, s, later);
   if (rc != BSR_OK) return rc;
-  return wide_run_batched<64>(jobs, n, s);
+  return wide_run_batched<64>(jobs, n, s, later);
 }
 
 }  // namespace bsr
